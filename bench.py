@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused FFN hot path on ONE MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt] [--no-cpu-baseline]
+
+A step is one pass of the whole fused chain (first product, activation/gate, second
+product, cross-workgroup sum, output conversion) over one batch of seeded synthetic input
+that is already resident in HBM.  Prints ONE JSON line.  `value` is useful TFLOP/s
+(2*M*N1*(g*K+N2) per step); `roofline` prices the dominant kernel, timed with HIP events on
+the launch stream inside the library, against the MI355X peak; `cpu_baseline` times the fp64
+CPU oracle on a bounded row sample of the same workload on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2516.6   # dense bf16/fp16: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz (published 2.5 PFLOP/s)
+HBM_PEAK_GBS = 8000.0
+ACT_NAMES = {0: "identity", 1: "relu", 2: "gelu_tanh", 3: "silu"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="gpt")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--oracle-rows", type=int, default=0, help="rows of the CPU-baseline sample (0 = auto)")
+    ap.add_argument("--plan", default="", help="force a plan: family,bm,bh[,raster]")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path shards by rows or by hidden slices, see DESIGN.md).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2512_12949_amd import binding as ff
+    from paper_2512_12949_amd import inputs
+
+    w = inputs.WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    host = inputs.make(w)
+
+    def up(a):
+        if a is None:
+            return None
+        if w.dtype == "bf16":
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(a).cuda()
+
+    dev = {k: up(v) for k, v in host.items()}
+    dt = ff.DTYPE_CODE[w.dtype]
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[w.dtype]
+    nws = max(ff.ffuse_workspace_bytes(dt, w.gated, w.M, w.K, w.N1, w.N2, False),
+              ff.ffuse_workspace_bytes(dt, w.gated, w.M, w.K, w.N1, w.N2, True), 256)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    ff.ffuse_set_workspace(ws)
+    Y = torch.empty((w.M, w.N2), dtype=tdt, device="cuda")
+    if args.plan:
+        v = [int(x) for x in args.plan.split(",")]
+        ff.ffuse_force_plan(ff.make_plan(v[0], v[1], v[2], raster=v[3] if len(v) > 3 else 4))
+    fused, unfused = ff.FUSED[w.dtype], ff.UNFUSED[w.dtype]
+
+    def step(fn):
+        fn(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            step(fn)
+        torch.cuda.synchronize()
+        ff.ffuse_profile_read()
+        ff.ffuse_profile_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step(fn)
+        torch.cuda.synchronize()
+        dt_s = time.perf_counter() - t0
+        ff.ffuse_profile_enable(False)
+        kms, kn = ff.ffuse_profile_read()
+        return dt_s / steps, (kms / kn * 1e-3 if kn else float("nan"))
+
+    t_fused, k_fused = timed(fused, args.steps, args.warmup)
+    plan = ff.ffuse_last_plan()
+    model = ff.ffuse_traffic_model(plan, dt, w.gated, w.M, w.K, w.N1, w.N2).as_dict()
+    Y_fused = Y.clone()
+    t_unf, k_unf = timed(unfused, max(3, args.steps // 2), 2)
+    diff = float((Y_fused.float() - Y.float()).abs().max() / Y.float().abs().max())
+
+    flops = float(w.flops())
+    value = flops / t_fused * 1e-12
+    decode = w.M <= 128 and flops / w.q_min() < 300.0
+    if decode:
+        roof = {"bound": "hbm", "achieved": w.q_min() / k_fused * 1e-9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": flops / k_fused * 1e-12, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    tf = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tf):
+        try:
+            roof["traffic"] = json.load(open(tf)).get(w.name, {}).get("fused_kernel_bytes")
+        except Exception:
+            pass
+    roof["kernel_ms"] = k_fused * 1e3
+
+    out = {
+        "metric": "fused FFN TFLOP/s (% MFMA peak) + HBM bytes vs unfused, 1 MI355X",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_fused * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: M={w.M} K={w.K} N1={w.N1} N2={w.N2} {w.dtype} "
+                               f"{ACT_NAMES[w.act]}{' gated' if w.gated else ''}",
+                   "plan": plan.as_dict()},
+        "pct_mfma_peak": 100.0 * value / MFMA_PEAK_TFLOPS,
+        "roofline": roof,
+        "unfused": {"ms_per_step": t_unf * 1e3, "tflops": flops / t_unf * 1e-12, "kernels_ms": k_unf * 1e3,
+                    "max_rel_diff_vs_fused": diff},
+        "bytes": {"q_min": w.q_min(), "q_unfused": w.q_unfused(), "model_hbm": model["hbm_bytes"],
+                  "model_reduce": model["reduce_bytes"], "model_fabric": model["fabric_bytes"]},
+        "model_t_pred_ms": model["t_pred"] * 1e3,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        per_row = flops / w.M
+        nrows = args.oracle_rows or int(max(1, min(w.M, 1.5e11 / per_row)))  # ~10-25 s of oracle work
+        rows = inputs.sample_rows(w.M, max(1, w.M // max(1, nrows // 2)), 2, seed=7)[:nrows]
+        t0 = time.perf_counter()
+        ref = oracle.ffn_rows(host["X"], host["W1"], host["W3"], host["W2"], w.act, rows=rows, bf16=(w.dtype == "bf16"))
+        t_cpu = time.perf_counter() - t0
+        got = Y_fused[torch.as_tensor(rows, device="cuda")].float().cpu().numpy().astype(np.float64)
+        rel = float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-300))
+        out["cpu_baseline"] = {"value": per_row * len(rows) / t_cpu * 1e-12, "unit": "TFLOP/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"{len(rows)} of {w.M} rows, all {w.N2} columns, {t_cpu:.1f} s"}
+        out["max_rel_err_vs_oracle"] = rel
+    ff.ffuse_set_workspace(None)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

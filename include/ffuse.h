@@ -1,0 +1,164 @@
+/*
+ * ffuse.h -- C ABI of libffuse.so: fused feed-forward chains for AMD MI355X (gfx950).
+ *
+ * The library evaluates the two-GEMM operator chain that the FlashFuser paper fuses
+ * (Background, Fig. "three common GEMM chains" (b) standard FFN and (c) gated FFN;
+ * Sec. 4.1, description of the tile graph):
+ *
+ *     standard:  Y = act(X * W1) * W2
+ *     gated   :  Y = (act(X * W1) .* (X * W3)) * W2          (SwiGLU when act = SiLU)
+ *
+ * in ONE pass that keeps the M x N1 intermediate out of HBM, and, for comparison, as a
+ * plain unfused two-GEMM path whose intermediate round-trips through a workspace.
+ *
+ * Conventions (all entry points)
+ *   - Every tensor is row-major and contiguous:  X[M][K], W1[K][N1], W3[K][N1], W2[N1][N2],
+ *     Y[M][N2].  Paper notation (m, k, n, l) = ours (M, K, N1, N2).
+ *   - X, W1, W3, W2, Y and the workspace are DEVICE pointers, 16-byte aligned.  The library
+ *     never allocates, frees or retains device memory; the caller owns all of it.
+ *   - Inputs are read-only; Y is fully overwritten.  Calls are asynchronous and ordered on
+ *     `stream` (a hipStream_t passed as void*, NULL = the null stream).
+ *   - Gated  <=>  W3 != NULL; `act` is then applied to the X*W1 branch (Sec. 4.1: one branch
+ *     passes through the activation, the other multiplies it element-wise).
+ *   - The activation sees complete sums over K only (Sec. 4.3, pruning Rule 3), accumulation
+ *     is fp32, the intermediate is rounded to the operand type (round-to-nearest-even) before
+ *     the second product, and Y is rounded once from fp32 to the operand type.
+ *   - Shape rules: M >= 1 (any value, row tails are masked); K, N1, N2 >= 8 and multiples
+ *     of 8; every tensor smaller than 2 GiB.  Anything else returns FFUSE_ERR_SHAPE.
+ *   - Errors are returned as negative status codes; nothing is written on a validation error.
+ *   - The fused and unfused paths need a caller-owned workspace (ffuse_workspace_bytes,
+ *     ffuse_set_workspace).  A call leaves the workspace ready for the next call on the
+ *     same stream; calls that overlap on different streams need different workspaces,
+ *     i.e. must not overlap while sharing one.
+ */
+#ifndef FFUSE_H
+#define FFUSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FFUSE_ACT_IDENTITY = 0,  /* x                                                         */
+    FFUSE_ACT_RELU = 1,      /* max(x, 0)                                                 */
+    FFUSE_ACT_GELU_TANH = 2, /* 0.5 x (1 + tanh( sqrt(2/pi) (x + 0.044715 x^3) ))         */
+    FFUSE_ACT_SILU = 3       /* x / (1 + exp(-x))   (the activation Sec. 4.1 names)       */
+} ffuse_act_t;
+
+typedef enum { FFUSE_DT_BF16 = 0, FFUSE_DT_F16 = 1, FFUSE_DT_F32 = 2 } ffuse_dtype_t;
+
+typedef enum {
+    FFUSE_OK = 0,
+    FFUSE_ERR_NULL = -1,      /* a required pointer is NULL                                */
+    FFUSE_ERR_SHAPE = -2,     /* a dimension violates the shape rules above                */
+    FFUSE_ERR_ALIGN = -3,     /* a pointer is not 16-byte aligned                          */
+    FFUSE_ERR_ACT = -4,       /* unknown activation / dtype code                           */
+    FFUSE_ERR_WORKSPACE = -5, /* no workspace set, or it is too small for this call        */
+    FFUSE_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch or a copy                */
+    FFUSE_ERR_ARCH = -7,      /* the current device is not gfx950                          */
+    FFUSE_ERR_PLAN = -8       /* a forced plan is not valid for this problem               */
+} ffuse_status_t;
+
+/*
+ * Execution plan = loop schedule + tile sizes + placement of the intermediate (Sec. 4.2:
+ * LoopSchedule, Tile Selection, Resource Mapping), reduced to the schedules that survive
+ * the pruning rules of Sec. 4.3 on a device without distributed shared memory.
+ */
+typedef enum {
+    FFUSE_FAMILY_AUTO = 0,
+    FFUSE_FAMILY_REDUCE = 1,  /* hidden dimension split across workgroups; each keeps its
+                                 activated slice on chip and the partial second products are
+                                 summed with fp32 atomics (Sec. 4.1 "reduce" strategy)      */
+    FFUSE_FAMILY_EXCHANGE = 2,/* cooperating workgroups publish activated tiles to an
+                                 L2-resident buffer and consume each other's tiles
+                                 (Sec. 4.1 "shuffle" strategy, exchange through L2)         */
+    FFUSE_FAMILY_UNFUSED = 3, /* two GEMM launches, intermediate in the workspace          */
+    FFUSE_FAMILY_SCALAR = 4   /* fp32 debug kernels (plain FMA, no matrix cores)            */
+} ffuse_family_t;
+
+typedef struct {
+    int32_t family;   /* ffuse_family_t                                                     */
+    int32_t bm;       /* rows of X per workgroup                                            */
+    int32_t bh;       /* hidden columns (of N1) per workgroup step                          */
+    int32_t bn2;      /* output columns (of N2) per inner step of the second product        */
+    int32_t bk;       /* K step of the first product                                        */
+    int32_t splits;   /* number of partial second products summed per output element        */
+    int32_t h_level;  /* where the activated slice lives: 0 registers, 1 LDS, 2 L2 buffer   */
+    int32_t raster;   /* row blocks that share one XCD's L2 at a time                       */
+    int32_t reserved[4];
+} ffuse_plan_t;
+
+/* Analytical data-movement volumes (Sec. 4.2, Algorithm 1) and per-level costs
+ * (Sec. 4.3, Eq. 1-3: cost of a level = volume / bandwidth, objective = the maximum). */
+typedef struct {
+    double flops;        /* useful flops 2*M*N1*(g*K + N2)                                  */
+    double hbm_bytes;    /* predicted HBM traffic                                           */
+    double fabric_bytes; /* bytes filled into the per-XCD L2s from Infinity Cache / HBM     */
+    double l2_bytes;     /* bytes delivered from L2 to the compute units                    */
+    double lds_bytes;    /* bytes read from LDS by the matrix pipelines                     */
+    double reduce_bytes; /* fp32 bytes combined across workgroups (atomics)                 */
+    double exchange_bytes;/* intermediate bytes written to + read from the L2 buffer        */
+    double q_min;        /* compulsory bytes: X + weights + Y once                          */
+    double q_unfused;    /* q_min + one write and one read of the intermediate              */
+    double t_mfma, t_hbm, t_fabric, t_l2, t_lds, t_reduce; /* seconds per level             */
+    double t_pred;       /* max of the above plus fixed launch/sync terms                   */
+    double lds_used;     /* bytes of LDS per workgroup                                      */
+    double acc_regs;     /* accumulator registers per lane                                  */
+    int32_t feasible;    /* capacity constraints (Eq. 3) hold                               */
+    int32_t workgroups;
+} ffuse_traffic_t;
+
+/* ---- the fused chain.  bf16 operands and output; _f16 / _f32 twins take the same
+ *      arguments (fp32 is a debug mode on plain FMA).  Returns a ffuse_status_t. ---------- */
+int ffuse_ffn(const void* X, const void* W1, const void* W3 /* NULL = not gated */, const void* W2,
+              int act, int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
+int ffuse_ffn_f16(const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M,
+                  int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
+int ffuse_ffn_f32(const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M,
+                  int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
+
+/* ---- the unfused comparison path (Evaluation, "Performance Analysis": the baseline writes
+ *      the intermediate to global memory and reads it back): GEMM + activation/gate into a
+ *      workspace-resident H[M][N1] in the operand type, then H * W2. --------------------- */
+int ffuse_ffn_unfused(const void* X, const void* W1, const void* W3, const void* W2, int act,
+                      int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
+int ffuse_ffn_unfused_f16(const void* X, const void* W1, const void* W3, const void* W2, int act,
+                          int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
+int ffuse_ffn_unfused_f32(const void* X, const void* W1, const void* W3, const void* W2, int act,
+                          int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
+
+/* ---- workspace.  ffuse_workspace_bytes: bytes the given problem needs (fused path when
+ *      unfused == 0).  ffuse_set_workspace: registers a caller-owned device buffer with the
+ *      library (it is zero-filled once on `stream`); passing NULL unregisters it. --------- */
+size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
+                             int unfused);
+int ffuse_set_workspace(void* dev_ptr, size_t bytes, void* stream);
+
+/* ---- host-side schedule chooser and traffic model (Sec. 4.2 / 4.3); no device work. ---- */
+int ffuse_choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
+                      ffuse_plan_t* out);
+int ffuse_traffic_model(const ffuse_plan_t* plan, int dtype, int gated, int64_t M, int64_t K,
+                        int64_t N1, int64_t N2, ffuse_traffic_t* out);
+/* Forces every later fused call onto *plan (NULL: back to the chooser).  Also settable with
+ * the environment variable FFUSE_FORCE_PLAN="family,bm,bh,bn2,bk,splits,h_level,raster". */
+int ffuse_force_plan(const ffuse_plan_t* plan);
+/* Plan used by the most recent fused call on this thread's library instance. */
+int ffuse_last_plan(ffuse_plan_t* out);
+
+/* ---- measurement aid: when enabled, the library brackets the dominant kernel of every
+ *      fused / unfused call with HIP events on the call's stream.  ffuse_profile_read
+ *      synchronises those events and returns the summed milliseconds and launch count
+ *      since the last read. ---------------------------------------------------------------- */
+int ffuse_profile_enable(int on);
+int ffuse_profile_read(double* kernel_ms_total, int64_t* launches);
+
+const char* ffuse_status_string(int status);
+int ffuse_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FFUSE_H */

@@ -1,0 +1,206 @@
+"""Thin ctypes binding of libffuse.so: same names as include/ffuse.h, argument marshalling
+only.  Every step of the chain runs in the library's HIP kernels; there is no Python or
+PyTorch fallback -- if the library is missing or the device is not gfx950 the calls raise.
+
+PyTorch is used by callers for device memory and streams only: tensors are passed as
+``data_ptr()`` values, streams as ``torch.cuda.current_stream().cuda_stream``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libffuse.so")
+
+ACT_IDENTITY, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
+DT_BF16, DT_F16, DT_F32 = 0, 1, 2
+FAMILY_AUTO, FAMILY_REDUCE, FAMILY_EXCHANGE, FAMILY_UNFUSED, FAMILY_SCALAR = 0, 1, 2, 3, 4
+DTYPE_CODE = {"bf16": DT_BF16, "f16": DT_F16, "f32": DT_F32}
+
+EXPORTS = [
+    "ffuse_ffn", "ffuse_ffn_f16", "ffuse_ffn_f32",
+    "ffuse_ffn_unfused", "ffuse_ffn_unfused_f16", "ffuse_ffn_unfused_f32",
+    "ffuse_workspace_bytes", "ffuse_set_workspace", "ffuse_choose_plan", "ffuse_traffic_model",
+    "ffuse_force_plan", "ffuse_last_plan", "ffuse_profile_enable", "ffuse_profile_read",
+    "ffuse_status_string", "ffuse_version",
+]
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [("family", ctypes.c_int32), ("bm", ctypes.c_int32), ("bh", ctypes.c_int32),
+                ("bn2", ctypes.c_int32), ("bk", ctypes.c_int32), ("splits", ctypes.c_int32),
+                ("h_level", ctypes.c_int32), ("raster", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+
+
+class Traffic(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in (
+        "flops", "hbm_bytes", "fabric_bytes", "l2_bytes", "lds_bytes", "reduce_bytes", "exchange_bytes",
+        "q_min", "q_unfused", "t_mfma", "t_hbm", "t_fabric", "t_l2", "t_lds", "t_reduce", "t_pred",
+        "lds_used", "acc_regs")] + [("feasible", ctypes.c_int32), ("workgroups", ctypes.c_int32)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class FfuseError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: status {code} ({status_string(code)})")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Loads libffuse.so (built by ``paper_2512_12949_amd.build``); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: run `python -m paper_2512_12949_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        for name in EXPORTS[:6]:
+            f = getattr(L, name)
+            f.restype = ci
+            f.argtypes = [vp, vp, vp, vp, ci, i64, i64, i64, i64, vp, vp]
+        L.ffuse_workspace_bytes.restype = ctypes.c_size_t
+        L.ffuse_workspace_bytes.argtypes = [ci, ci, i64, i64, i64, i64, ci]
+        L.ffuse_set_workspace.restype = ci
+        L.ffuse_set_workspace.argtypes = [vp, ctypes.c_size_t, vp]
+        L.ffuse_choose_plan.restype = ci
+        L.ffuse_choose_plan.argtypes = [ci, ci, ci, i64, i64, i64, i64, ctypes.POINTER(Plan)]
+        L.ffuse_traffic_model.restype = ci
+        L.ffuse_traffic_model.argtypes = [ctypes.POINTER(Plan), ci, ci, i64, i64, i64, i64, ctypes.POINTER(Traffic)]
+        L.ffuse_force_plan.restype = ci
+        L.ffuse_force_plan.argtypes = [ctypes.POINTER(Plan)]
+        L.ffuse_last_plan.restype = ci
+        L.ffuse_last_plan.argtypes = [ctypes.POINTER(Plan)]
+        L.ffuse_profile_enable.restype = ci
+        L.ffuse_profile_enable.argtypes = [ci]
+        L.ffuse_profile_read.restype = ci
+        L.ffuse_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+        L.ffuse_status_string.restype = ctypes.c_char_p
+        L.ffuse_status_string.argtypes = [ci]
+        L.ffuse_version.restype = ci
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().ffuse_status_string(int(code)).decode()
+
+
+def _check(code, what):
+    if code != 0:
+        raise FfuseError(code, what)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(int(t.data_ptr()) if hasattr(t, "data_ptr") else int(t))
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    return ctypes.c_void_p(int(stream))
+
+
+def _call(name, X, W1, W3, W2, act, Y, stream, check):
+    M, K = X.shape
+    N1, N2 = W2.shape
+    rc = getattr(lib(), name)(_ptr(X), _ptr(W1), _ptr(W3), _ptr(W2), int(act), M, K, N1, N2, _ptr(Y), _stream(stream))
+    if check:
+        _check(rc, name)
+    return rc
+
+
+def ffuse_ffn(X, W1, W3, W2, act, Y, stream=None, check=True):
+    return _call("ffuse_ffn", X, W1, W3, W2, act, Y, stream, check)
+
+
+def ffuse_ffn_f16(X, W1, W3, W2, act, Y, stream=None, check=True):
+    return _call("ffuse_ffn_f16", X, W1, W3, W2, act, Y, stream, check)
+
+
+def ffuse_ffn_f32(X, W1, W3, W2, act, Y, stream=None, check=True):
+    return _call("ffuse_ffn_f32", X, W1, W3, W2, act, Y, stream, check)
+
+
+def ffuse_ffn_unfused(X, W1, W3, W2, act, Y, stream=None, check=True):
+    return _call("ffuse_ffn_unfused", X, W1, W3, W2, act, Y, stream, check)
+
+
+def ffuse_ffn_unfused_f16(X, W1, W3, W2, act, Y, stream=None, check=True):
+    return _call("ffuse_ffn_unfused_f16", X, W1, W3, W2, act, Y, stream, check)
+
+
+def ffuse_ffn_unfused_f32(X, W1, W3, W2, act, Y, stream=None, check=True):
+    return _call("ffuse_ffn_unfused_f32", X, W1, W3, W2, act, Y, stream, check)
+
+
+FUSED = {"bf16": ffuse_ffn, "f16": ffuse_ffn_f16, "f32": ffuse_ffn_f32}
+UNFUSED = {"bf16": ffuse_ffn_unfused, "f16": ffuse_ffn_unfused_f16, "f32": ffuse_ffn_unfused_f32}
+
+
+def ffuse_workspace_bytes(dtype, gated, M, K, N1, N2, unfused=False) -> int:
+    return int(lib().ffuse_workspace_bytes(int(dtype), int(bool(gated)), M, K, N1, N2, int(bool(unfused))))
+
+
+def ffuse_set_workspace(buf, nbytes=None, stream=None):
+    if buf is None:
+        _check(lib().ffuse_set_workspace(None, 0, _stream(stream)), "ffuse_set_workspace")
+        return
+    if nbytes is None:
+        nbytes = buf.numel() * buf.element_size()
+    _check(lib().ffuse_set_workspace(_ptr(buf), int(nbytes), _stream(stream)), "ffuse_set_workspace")
+
+
+def ffuse_choose_plan(dtype, act, gated, M, K, N1, N2) -> Plan:
+    p = Plan()
+    _check(lib().ffuse_choose_plan(int(dtype), int(act), int(bool(gated)), M, K, N1, N2, ctypes.byref(p)),
+           "ffuse_choose_plan")
+    return p
+
+
+def ffuse_traffic_model(plan: Plan, dtype, gated, M, K, N1, N2) -> Traffic:
+    t = Traffic()
+    _check(lib().ffuse_traffic_model(ctypes.byref(plan), int(dtype), int(bool(gated)), M, K, N1, N2, ctypes.byref(t)),
+           "ffuse_traffic_model")
+    return t
+
+
+def ffuse_force_plan(plan):
+    _check(lib().ffuse_force_plan(None if plan is None else ctypes.byref(plan)), "ffuse_force_plan")
+
+
+def ffuse_last_plan() -> Plan:
+    p = Plan()
+    _check(lib().ffuse_last_plan(ctypes.byref(p)), "ffuse_last_plan")
+    return p
+
+
+def ffuse_profile_enable(on: bool):
+    _check(lib().ffuse_profile_enable(int(bool(on))), "ffuse_profile_enable")
+
+
+def ffuse_profile_read():
+    ms, n = ctypes.c_double(), ctypes.c_int64()
+    _check(lib().ffuse_profile_read(ctypes.byref(ms), ctypes.byref(n)), "ffuse_profile_read")
+    return ms.value, n.value
+
+
+def ffuse_version() -> int:
+    return int(lib().ffuse_version())
+
+
+def make_plan(family, bm=0, bh=0, bn2=128, bk=64, splits=0, h_level=0, raster=4) -> Plan:
+    p = Plan()
+    p.family, p.bm, p.bh, p.bn2, p.bk, p.splits, p.h_level, p.raster = family, bm, bh, bn2, bk, splits, h_level, raster
+    return p

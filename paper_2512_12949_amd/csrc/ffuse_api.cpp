@@ -1,0 +1,283 @@
+// C-ABI layer of libffuse.so: argument validation, plan selection, workspace bookkeeping
+// and kernel launches.  See include/ffuse.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "../../include/ffuse.h"
+#include "ffuse_launch.h"
+#include "ffuse_plan.h"
+
+namespace {
+
+struct State {
+    std::mutex mu;
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+    bool ws_dirty = false;   // the fp32 sums region may hold non-zero data
+    bool forced = false;
+    ffuse_plan_t forced_plan{};
+    ffuse_plan_t last_plan{};
+    bool env_checked = false;
+    bool profiling = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
+    int arch_ok = -1;        // -1 unknown, 0 no, 1 yes
+};
+State g;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_arch() {
+    if (g.arch_ok < 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return FFUSE_ERR_LAUNCH;
+        g.arch_ok = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 0;
+    }
+    return g.arch_ok == 1 ? FFUSE_OK : FFUSE_ERR_ARCH;
+}
+
+int validate(const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+             int64_t N1, int64_t N2, const void* Y, int elem) {
+    if (!X || !W1 || !W2 || !Y) return FFUSE_ERR_NULL;
+    if (act < FFUSE_ACT_IDENTITY || act > FFUSE_ACT_SILU) return FFUSE_ERR_ACT;
+    if (M < 1 || K < 8 || N1 < 8 || N2 < 8 || (K % 8) || (N1 % 8) || (N2 % 8)) return FFUSE_ERR_SHAPE;
+    const int64_t lim = (int64_t)1 << 31;
+    if ((M + 256) * K * elem >= lim || (K + 128) * N1 * elem >= lim || (N1 + 512) * N2 * elem >= lim ||
+        M * N2 * 4 >= ((int64_t)1 << 40) || M * N2 * elem >= lim)
+        return FFUSE_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(W1) || !aligned16(W2) || !aligned16(Y) || (W3 && !aligned16(W3)))
+        return FFUSE_ERR_ALIGN;
+    return FFUSE_OK;
+}
+
+void read_env_plan() {
+    if (g.env_checked) return;
+    g.env_checked = true;
+    const char* s = std::getenv("FFUSE_FORCE_PLAN");
+    if (!s || !*s) return;
+    int v[8] = {0, 0, 0, 128, 64, 0, 0, 4};
+    const int n = std::sscanf(s, "%d,%d,%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7]);
+    if (n >= 3) {
+        std::memset(&g.forced_plan, 0, sizeof(g.forced_plan));
+        g.forced_plan.family = v[0]; g.forced_plan.bm = v[1]; g.forced_plan.bh = v[2]; g.forced_plan.bn2 = v[3];
+        g.forced_plan.bk = v[4]; g.forced_plan.splits = v[5]; g.forced_plan.h_level = v[6]; g.forced_plan.raster = v[7];
+        g.forced = true;
+    }
+}
+
+struct Timer {  // brackets the dominant kernel with events when profiling is on
+    hipStream_t st;
+    hipEvent_t a = nullptr, b = nullptr;
+    explicit Timer(hipStream_t s) : st(s) {
+        if (g.profiling && hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) (void)hipEventRecord(a, st);
+    }
+    void stop() {
+        if (a && b) {
+            (void)hipEventRecord(b, st);
+            g.events.emplace_back(a, b);
+            a = b = nullptr;
+        }
+    }
+};
+
+int run_fused(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+              int64_t N1, int64_t N2, void* Y, void* stream) {
+    const int elem = dtype == FFUSE_DT_F32 ? 4 : 2;
+    int rc = validate(X, W1, W3, W2, act, M, K, N1, N2, Y, elem);
+    if (rc != FFUSE_OK) return rc;
+    std::lock_guard<std::mutex> lock(g.mu);
+    rc = check_arch();
+    if (rc != FFUSE_OK) return rc;
+    read_env_plan();
+    const int gated = W3 != nullptr;
+    ffuse_plan_t plan;
+    if (g.forced && g.forced_plan.family != FFUSE_FAMILY_AUTO) {
+        plan = g.forced_plan;
+        if (!ffuse::plan_valid(plan, dtype, gated, M, K, N1, N2) || plan.family == FFUSE_FAMILY_UNFUSED) return FFUSE_ERR_PLAN;
+    } else {
+        ffuse::choose_plan(dtype, act, gated, M, K, N1, N2, &plan);
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    ffuse::FusedArgs a{X, W1, W3, W2, nullptr, M, (int)K, (int)N1, (int)N2, act, plan.raster > 0 ? plan.raster : 1};
+    if (plan.family == FFUSE_FAMILY_SCALAR) {
+        Timer t(st);
+        if (ffuse::launch_fused_f32(a, reinterpret_cast<float*>(Y), st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+        t.stop();
+        g.last_plan = plan;
+        return FFUSE_OK;
+    }
+    if (plan.family != FFUSE_FAMILY_REDUCE) return FFUSE_ERR_PLAN;
+    const size_t need = sizeof(float) * (size_t)M * (size_t)N2;
+    if (!g.ws || g.ws_bytes < need) return FFUSE_ERR_WORKSPACE;
+    if (g.ws_dirty) {
+        if (ffuse::launch_zero(g.ws, g.ws_bytes, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+        g.ws_dirty = false;
+    }
+    a.Ysum = reinterpret_cast<float*>(g.ws);
+    {
+        Timer t(st);
+        if (ffuse::launch_fused_reduce(dtype, a, plan.bm, plan.bh, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+        t.stop();
+    }
+    if (ffuse::launch_finalize(dtype, a.Ysum, Y, M * N2, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+    g.last_plan = plan;
+    return FFUSE_OK;
+}
+
+int run_unfused(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M,
+                int64_t K, int64_t N1, int64_t N2, void* Y, void* stream) {
+    const int elem = dtype == FFUSE_DT_F32 ? 4 : 2;
+    int rc = validate(X, W1, W3, W2, act, M, K, N1, N2, Y, elem);
+    if (rc != FFUSE_OK) return rc;
+    if (M * N1 * elem >= ((int64_t)1 << 31)) return FFUSE_ERR_SHAPE;
+    std::lock_guard<std::mutex> lock(g.mu);
+    rc = check_arch();
+    if (rc != FFUSE_OK) return rc;
+    const size_t need = (size_t)elem * (size_t)M * (size_t)N1;
+    if (!g.ws || g.ws_bytes < need) return FFUSE_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    g.ws_dirty = true;  // H overwrites whatever the fused path kept at zero
+    ffuse::GemmArgs g0{X, W1, W3, g.ws, M, (int)K, (int)N1, act, 4};
+    ffuse::GemmArgs g1{g.ws, W2, nullptr, Y, M, (int)N1, (int)N2, FFUSE_ACT_IDENTITY, 4};
+    Timer t(st);
+    hipError_t e = dtype == FFUSE_DT_F32 ? ffuse::launch_gemm_act_f32(g0, st) : ffuse::launch_gemm_act(dtype, g0, st);
+    if (e != hipSuccess) return FFUSE_ERR_LAUNCH;
+    e = dtype == FFUSE_DT_F32 ? ffuse::launch_gemm_act_f32(g1, st) : ffuse::launch_gemm_act(dtype, g1, st);
+    if (e != hipSuccess) return FFUSE_ERR_LAUNCH;
+    t.stop();
+    return FFUSE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ffuse_ffn(const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K, int64_t N1,
+              int64_t N2, void* Y, void* stream) {
+    return run_fused(FFUSE_DT_BF16, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+}
+int ffuse_ffn_f16(const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+                  int64_t N1, int64_t N2, void* Y, void* stream) {
+    return run_fused(FFUSE_DT_F16, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+}
+int ffuse_ffn_f32(const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+                  int64_t N1, int64_t N2, void* Y, void* stream) {
+    return run_fused(FFUSE_DT_F32, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+}
+int ffuse_ffn_unfused(const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+                      int64_t N1, int64_t N2, void* Y, void* stream) {
+    return run_unfused(FFUSE_DT_BF16, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+}
+int ffuse_ffn_unfused_f16(const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+                          int64_t N1, int64_t N2, void* Y, void* stream) {
+    return run_unfused(FFUSE_DT_F16, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+}
+int ffuse_ffn_unfused_f32(const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+                          int64_t N1, int64_t N2, void* Y, void* stream) {
+    return run_unfused(FFUSE_DT_F32, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+}
+
+size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, int unfused) {
+    (void)gated; (void)K;
+    if (M < 1 || N1 < 1 || N2 < 1) return 0;
+    const size_t elem = dtype == FFUSE_DT_F32 ? 4 : 2;
+    size_t b = unfused ? elem * (size_t)M * (size_t)N1 : (dtype == FFUSE_DT_F32 ? 0 : sizeof(float) * (size_t)M * (size_t)N2);
+    return (b + 255) & ~(size_t)255;
+}
+
+int ffuse_set_workspace(void* dev_ptr, size_t bytes, void* stream) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    if (!dev_ptr) {
+        g.ws = nullptr; g.ws_bytes = 0; g.ws_dirty = false;
+        return FFUSE_OK;
+    }
+    if (!aligned16(dev_ptr)) return FFUSE_ERR_ALIGN;
+    if (bytes % 16) return FFUSE_ERR_SHAPE;
+    if (ffuse::launch_zero(dev_ptr, bytes, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return FFUSE_ERR_LAUNCH;
+    g.ws = dev_ptr; g.ws_bytes = bytes; g.ws_dirty = false;
+    return FFUSE_OK;
+}
+
+int ffuse_choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* out) {
+    if (!out) return FFUSE_ERR_NULL;
+    if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F32 || act < FFUSE_ACT_IDENTITY || act > FFUSE_ACT_SILU) return FFUSE_ERR_ACT;
+    if (M < 1 || K < 8 || N1 < 8 || N2 < 8 || (K % 8) || (N1 % 8) || (N2 % 8)) return FFUSE_ERR_SHAPE;
+    ffuse::choose_plan(dtype, act, gated ? 1 : 0, M, K, N1, N2, out);
+    return FFUSE_OK;
+}
+
+int ffuse_traffic_model(const ffuse_plan_t* plan, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
+                        ffuse_traffic_t* out) {
+    if (!plan || !out) return FFUSE_ERR_NULL;
+    if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F32) return FFUSE_ERR_ACT;
+    if (M < 1 || K < 8 || N1 < 8 || N2 < 8) return FFUSE_ERR_SHAPE;
+    if (!ffuse::plan_valid(*plan, dtype, gated ? 1 : 0, M, K, N1, N2)) return FFUSE_ERR_PLAN;
+    ffuse::traffic_model(*plan, dtype, gated ? 1 : 0, M, K, N1, N2, out);
+    return FFUSE_OK;
+}
+
+int ffuse_force_plan(const ffuse_plan_t* plan) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.env_checked = true;  // an explicit call overrides the environment
+    if (!plan) { g.forced = false; return FFUSE_OK; }
+    g.forced_plan = *plan;
+    g.forced = true;
+    return FFUSE_OK;
+}
+
+int ffuse_last_plan(ffuse_plan_t* out) {
+    if (!out) return FFUSE_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g.mu);
+    *out = g.last_plan;
+    return FFUSE_OK;
+}
+
+int ffuse_profile_enable(int on) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.profiling = on != 0;
+    return FFUSE_OK;
+}
+
+int ffuse_profile_read(double* kernel_ms_total, int64_t* launches) {
+    if (!kernel_ms_total || !launches) return FFUSE_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g.mu);
+    double total = 0.0;
+    int64_t n = 0;
+    for (auto& ev : g.events) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(ev.second) == hipSuccess && hipEventElapsedTime(&ms, ev.first, ev.second) == hipSuccess) {
+            total += ms;
+            ++n;
+        }
+        (void)hipEventDestroy(ev.first);
+        (void)hipEventDestroy(ev.second);
+    }
+    g.events.clear();
+    *kernel_ms_total = total;
+    *launches = n;
+    return FFUSE_OK;
+}
+
+const char* ffuse_status_string(int status) {
+    switch (status) {
+        case FFUSE_OK: return "ok";
+        case FFUSE_ERR_NULL: return "a required pointer is NULL";
+        case FFUSE_ERR_SHAPE: return "shape violates the rules (M>=1; K,N1,N2 multiples of 8; tensors < 2 GiB)";
+        case FFUSE_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+        case FFUSE_ERR_ACT: return "unknown activation or dtype code";
+        case FFUSE_ERR_WORKSPACE: return "workspace missing or too small";
+        case FFUSE_ERR_LAUNCH: return "HIP runtime error";
+        case FFUSE_ERR_ARCH: return "device is not gfx950";
+        case FFUSE_ERR_PLAN: return "plan not valid for this problem";
+        default: return "unknown status";
+    }
+}
+
+int ffuse_version(void) { return 1; }
+
+}  // extern "C"

@@ -1,0 +1,46 @@
+// Argument blocks and launcher prototypes shared by the kernel translation units and the
+// C-ABI layer.  Host and device side; no torch types.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ffuse {
+
+struct FusedArgs {
+    const void* X;
+    const void* W1;
+    const void* W3;  // nullptr: not gated
+    const void* W2;
+    float* Ysum;     // fp32 sums [M][N2], zero on entry
+    int64_t M;
+    int K, N1, N2;
+    int act;
+    int raster;      // row blocks per XCD patch
+};
+
+struct GemmArgs {
+    const void* A;   // [M][K]
+    const void* B;   // [K][N]
+    const void* B3;  // nullptr, or [K][N] second weight of the gated epilogue
+    void* C;         // [M][N]
+    int64_t M;
+    int K, N;
+    int act;
+    int raster;
+};
+
+// 16-bit paths (dtype 0 = bf16, 1 = fp16)
+hipError_t launch_fused_reduce(int dtype, const FusedArgs& a, int bm, int bh, hipStream_t st);
+bool fused_reduce_supported(int gated, int bm, int bh);
+hipError_t launch_finalize(int dtype, float* sums, void* Y, int64_t count, hipStream_t st);
+hipError_t launch_gemm_act(int dtype, const GemmArgs& a, hipStream_t st);
+
+// zero fill with a kernel (safe to record into a captured graph, unlike a memset node);
+// bytes must be a multiple of 16
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
+
+// fp32 debug path
+hipError_t launch_fused_f32(const FusedArgs& a, float* Y, hipStream_t st);
+hipError_t launch_gemm_act_f32(const GemmArgs& a, hipStream_t st);
+
+}  // namespace ffuse

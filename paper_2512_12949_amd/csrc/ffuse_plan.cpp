@@ -1,0 +1,167 @@
+// Host-side schedule chooser and data-movement model.  No device code.
+//
+// Re-derivation, for a device WITHOUT distributed shared memory, of the paper's Dataflow
+// Analyzer (Sec. 4.2, Algorithm 1: per-level data-movement volume of one plan, inputs and
+// outputs multiplied by the trip counts of the loops that re-access them, the intermediate
+// placed greedily in the fastest level that holds it) and of its cost model (Sec. 4.3,
+// Eq. 1-3: cost of level l = V_l / B_l, minimise the maximum subject to capacity), with a
+// matrix-core time term added because several of the workloads are compute bound.
+//
+// Memory levels on gfx950: registers (512 KB per CU) -> LDS (160 KB per CU) -> L2 (4 MB per
+// XCD, 32 CUs) -> Infinity Cache (256 MB) -> HBM.  Cross-workgroup sums go through fp32
+// atomics that execute in L2.
+#include "ffuse_plan.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <unordered_map>
+
+namespace ffuse {
+
+// Calibrated on an MI355X (standalone probes: MFMA issue loop, streaming read, LDS b128
+// read, coalesced fp32 atomic adds).  Datasheet peaks are 2516 TFLOP/s and 8 TB/s.
+const Device kDevice = {
+    /*cus*/ 256, /*xcds*/ 8,
+    /*mfma_flops*/ 2.40e15,     // 32x32x16 issue loop
+    /*hbm_bw*/ 5.6e12,          // streaming read of 2 GiB
+    /*fabric_bw*/ 9.0e12,       // re-read of an Infinity-Cache-resident 32 MiB buffer
+    /*l2_bw*/ 256 * 64.0 * 2.4e9,
+    /*lds_bw*/ 256 * 128.0 * 2.4e9,
+    /*atomic_bw*/ 1.36e12,      // fp32 atomic add, one dword per L2 channel per clock
+    /*lds_bytes*/ 160 * 1024, /*acc_regs*/ 256, /*l2_bytes*/ 4.0 * 1024 * 1024,
+    /*mall_bytes*/ 256.0 * 1024 * 1024,
+    /*launch_s*/ 4e-6};
+
+static double cdiv(double a, double b) { return std::ceil(a / b); }
+
+bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
+    (void)M; (void)K; (void)N1; (void)N2;
+    switch (p.family) {
+        case FFUSE_FAMILY_SCALAR: return dtype == FFUSE_DT_F32;
+        case FFUSE_FAMILY_UNFUSED: return true;
+        case FFUSE_FAMILY_REDUCE:
+            if (dtype == FFUSE_DT_F32) return false;
+            return fused_reduce_tile_ok(gated, p.bm, p.bh) && p.raster >= 1;
+        default: return false;
+    }
+}
+
+bool fused_reduce_tile_ok(int gated, int bm, int bh) {
+    if (!gated) return (bm == 256 && bh == 256) || (bm == 128 && (bh == 256 || bh == 128 || bh == 64));
+    return (bm == 256 && bh == 128) || (bm == 128 && (bh == 128 || bh == 64));
+}
+
+void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
+                   ffuse_traffic_t* t) {
+    const Device& d = kDevice;
+    std::memset(t, 0, sizeof(*t));
+    const double e = dtype == FFUSE_DT_F32 ? 4.0 : 2.0, g = gated ? 2.0 : 1.0;
+    const double m = (double)M, k = (double)K, n1 = (double)N1, n2 = (double)N2;
+    t->flops = 2.0 * m * n1 * (g * k + n2);
+    t->q_min = e * (m * k + g * k * n1 + n1 * n2 + m * n2);
+    t->q_unfused = t->q_min + 2.0 * e * m * n1;
+    double mfma_flops = d.mfma_flops;
+    double padded = t->flops, waves = 1.0;
+    t->feasible = 1;
+
+    if (p.family == FFUSE_FAMILY_REDUCE) {
+        const double bm = p.bm, bh = p.bh, R = std::max(1, p.raster);
+        const double MB = cdiv(m, bm), S = cdiv(n1, bh), units = MB * S;
+        t->workgroups = (int)units;
+        padded = units * 2.0 * bm * bh * (g * k + n2);
+        waves = cdiv(units, d.cus) * d.cus / units;
+        // every unit streams its X row block, its weight slices: L2 -> CU
+        t->l2_bytes = units * e * (bm * k + g * k * bh + bh * n2);
+        // an XCD patch of R row blocks x (32/R) slices fills each tile once into its L2
+        const double P = std::max(1.0, 32.0 / R);
+        t->fabric_bytes = units / 32.0 * e * (R * bm * k + P * (g * k * bh + bh * n2));
+        // matrix pipeline LDS reads: per k=16 step a wave reads (g*HT + MT) KB in the first
+        // product (4 waves split rows), JT KB in the second (H comes from registers)
+        const double ht = bh / 32.0, mt = bm / 128.0, jt = 4.0;
+        t->lds_bytes = units * 4.0 * 1024.0 * ((k / 16.0) * (g * ht + mt) + (n2 / 128.0) * (bh / 16.0) * jt);
+        t->reduce_bytes = 4.0 * m * n2 * S;
+        t->exchange_bytes = 0.0;
+        // fp32 sums: read + zero-write by the finalise pass; HBM only if they overflow the
+        // Infinity Cache
+        const double sums = 4.0 * m * n2;
+        t->hbm_bytes = t->q_min + (sums > 0.5 * d.mall_bytes ? 2.0 * sums : 0.0);
+        t->lds_used = std::max(2.0 * (bm * 128.0 + g * bh * 128.0), 2.0 * (bh >= 128 ? 2.0 : 1.0) * 128.0 * 128.0);
+        t->acc_regs = g * (bh / 32.0) * (bm / 128.0) * 16.0;
+        t->feasible = t->lds_used <= d.lds_bytes && t->acc_regs <= d.acc_regs;
+    } else if (p.family == FFUSE_FAMILY_UNFUSED) {
+        const double bm = 256.0, bh0 = gated ? 128.0 : 256.0, bh1 = 256.0;
+        const double u0 = cdiv(m, bm) * cdiv(n1, bh0), u1 = cdiv(m, bm) * cdiv(n2, bh1);
+        t->workgroups = (int)std::max(u0, u1);
+        padded = u0 * 2.0 * bm * bh0 * g * k + u1 * 2.0 * bm * bh1 * n1;
+        waves = (cdiv(u0, d.cus) * d.cus * g * k + cdiv(u1, d.cus) * d.cus * n1) / (u0 * g * k + u1 * n1);
+        t->l2_bytes = u0 * e * (bm * k + g * k * bh0) + u1 * e * (bm * n1 + n1 * bh1) + e * m * n1;
+        t->fabric_bytes = u0 / 32.0 * e * (4 * bm * k + 8 * g * k * bh0) + u1 / 32.0 * e * (4 * bm * n1 + 8 * n1 * bh1) + e * m * n1;
+        t->lds_bytes = u0 * 4.0 * 1024.0 * (k / 16.0) * (g * bh0 / 64.0 + 4.0) + u1 * 4.0 * 1024.0 * (n1 / 16.0) * 8.0;
+        const double h = e * m * n1;
+        t->hbm_bytes = t->q_min + (h > 0.5 * d.mall_bytes ? 2.0 * h : 0.0);
+        t->exchange_bytes = 2.0 * h;
+        t->lds_used = 2.0 * (bm * 128.0 + g * bh0 * 128.0);
+        t->acc_regs = 256;
+    } else {  // scalar fp32 debug path
+        const double units = cdiv(m, 16) * cdiv(n1, 64);
+        t->workgroups = (int)units;
+        mfma_flops = 256 * 128.0 * 2.4e9;  // fp32 FMA rate, not matrix cores
+        t->l2_bytes = units * e * (16 * k + g * k * 64 + 64 * n2);
+        t->fabric_bytes = t->l2_bytes / 8.0;
+        t->reduce_bytes = 4.0 * m * n2 * cdiv(n1, 64);
+        t->hbm_bytes = t->q_min;
+        t->lds_bytes = t->flops * 2.0;
+    }
+    t->t_mfma = padded * waves / mfma_flops;
+    t->t_hbm = t->hbm_bytes / d.hbm_bw;
+    t->t_fabric = t->fabric_bytes / d.fabric_bw;
+    t->t_l2 = t->l2_bytes / d.l2_bw;
+    t->t_lds = t->lds_bytes / d.lds_bw;
+    t->t_reduce = t->reduce_bytes / d.atomic_bw;
+    double worst = std::max({t->t_mfma, t->t_hbm, t->t_fabric, t->t_l2, t->t_lds});
+    // atomics of one unit are issued after its matrix work, so they add rather than overlap
+    // unless other units are still computing; model: half overlaps
+    worst = std::max(worst, t->t_reduce) + 0.5 * std::min(worst, t->t_reduce);
+    const double launches = 2.0;  // main kernel + finalise / second GEMM / zero fill
+    t->t_pred = worst + launches * d.launch_s;
+}
+
+// Enumerates the plans the kernels implement, discards infeasible ones and returns the one
+// with the smallest predicted time (Sec. 4.3, Algorithm 2 without the on-device profiling
+// of the top-k list).
+void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* out) {
+    (void)act;
+    ffuse_plan_t best;
+    std::memset(&best, 0, sizeof(best));
+    if (dtype == FFUSE_DT_F32) {
+        best.family = FFUSE_FAMILY_SCALAR;
+        best.bm = 16; best.bh = 64; best.bn2 = 256; best.bk = 32; best.h_level = 1; best.raster = 1;
+        best.splits = (int)((N1 + 63) / 64);
+        *out = best;
+        return;
+    }
+    double best_t = 1e30;
+    static const int tiles[][2] = {{256, 256}, {128, 256}, {256, 128}, {128, 128}, {128, 64}};
+    static const int rasters[] = {1, 2, 4, 8, 16};
+    for (auto& tl : tiles) {
+        if (!fused_reduce_tile_ok(gated, tl[0], tl[1])) continue;
+        for (int r : rasters) {
+            ffuse_plan_t p;
+            std::memset(&p, 0, sizeof(p));
+            p.family = FFUSE_FAMILY_REDUCE;
+            p.bm = tl[0]; p.bh = tl[1]; p.bn2 = 128; p.bk = 64; p.h_level = 0; p.raster = r;
+            p.splits = (int)((N1 + p.bh - 1) / p.bh);
+            if (r > 1 && r > (M + p.bm - 1) / p.bm) continue;
+            ffuse_traffic_t t;
+            traffic_model(p, dtype, gated, M, K, N1, N2, &t);
+            if (!t.feasible) continue;
+            if (t.t_pred < best_t) { best_t = t.t_pred; best = p; }
+        }
+    }
+    *out = best;
+}
+
+}  // namespace ffuse

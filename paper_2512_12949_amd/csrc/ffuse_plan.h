@@ -1,0 +1,30 @@
+// Host-side plan chooser / traffic model interface (no device code, no torch types).
+#pragma once
+#include <stdint.h>
+
+#include "../../include/ffuse.h"
+
+namespace ffuse {
+
+struct Device {
+    int cus, xcds;
+    double mfma_flops;   // sustained dense 16-bit MFMA rate, flop/s
+    double hbm_bw;       // achievable HBM read bandwidth, B/s
+    double fabric_bw;    // Infinity Cache -> L2 fill bandwidth, B/s
+    double l2_bw;        // L2 -> CU, all CUs, B/s
+    double lds_bw;       // LDS read, all CUs, B/s
+    double atomic_bw;    // fp32 atomic-add bytes per second, whole chip
+    double lds_bytes;    // per workgroup
+    double acc_regs;     // accumulator registers per lane at one wave per SIMD
+    double l2_bytes, mall_bytes;
+    double launch_s;     // fixed cost of one kernel launch
+};
+extern const Device kDevice;
+
+bool fused_reduce_tile_ok(int gated, int bm, int bh);
+bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2);
+void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
+                   ffuse_traffic_t* out);
+void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* out);
+
+}  // namespace ffuse

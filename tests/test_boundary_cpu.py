@@ -1,0 +1,53 @@
+"""C-ABI boundary checks that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_12949_amd import binding as ff
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "ffuse.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(ffuse_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert len(names) >= 16
+    L = ff.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(ff.EXPORTS) == names
+    assert ff.ffuse_version() >= 1
+
+
+def test_argument_validation_happens_before_any_device_work():
+    L = ff.lib()
+    a = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x1008)
+    call = L.ffuse_ffn
+    assert call(None, a, None, a, 1, 8, 8, 8, 8, a, None) == -1
+    assert call(a, a, None, a, 1, 8, 8, 8, 8, None, None) == -1
+    assert call(a, a, None, a, 9, 8, 8, 8, 8, a, None) == -4
+    assert call(a, a, None, a, 1, 0, 8, 8, 8, a, None) == -2
+    assert call(a, a, None, a, 1, 8, 12, 8, 8, a, None) == -2
+    assert call(a, a, None, a, 1, 8, 8, 4, 8, a, None) == -2
+    assert call(a, a, None, a, 1, 1 << 20, 1 << 12, 8, 8, a, None) == -2   # X of 8 GiB
+    assert call(odd, a, None, a, 1, 8, 8, 8, 8, a, None) == -3
+    assert call(a, a, odd, a, 1, 8, 8, 8, 8, a, None) == -3
+    for name in ("ffuse_ffn_f16", "ffuse_ffn_f32", "ffuse_ffn_unfused", "ffuse_ffn_unfused_f16", "ffuse_ffn_unfused_f32"):
+        assert getattr(L, name)(None, a, None, a, 1, 8, 8, 8, 8, a, None) == -1
+    assert ff.status_string(0) == "ok" and "NULL" in ff.status_string(-1)
+
+
+def test_workspace_size_formula():
+    assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 4096, 4096, 16384, 4096, False) == 4 * 4096 * 4096
+    assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 4096, 4096, 16384, 4096, True) == 2 * 4096 * 16384
+    assert ff.ffuse_workspace_bytes(ff.DT_F32, False, 128, 256, 1024, 256, True) == 4 * 128 * 1024
+    assert ff.ffuse_workspace_bytes(ff.DT_F32, False, 128, 256, 1024, 256, False) == 0

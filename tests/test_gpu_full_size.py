@@ -1,0 +1,40 @@
+"""Parity at the benchmark configurations' full sizes, in the launch configuration the
+benchmark times (the chooser's plan).  The oracle computes a stratified row sample (first,
+last and seeded interior rows of every 256-row block; every output column), and the whole
+output is checked for finiteness and against the unfused path."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_12949_amd import binding as ff
+from paper_2512_12949_amd import inputs
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+PER_BLOCK = {"gpt": 4, "llama": 4, "decode16": 16, "decode64": 64, "large": 3}
+
+
+@pytest.mark.parametrize("name", ["gpt", "llama", "decode16", "decode64", "large"])
+def test_full_size(name):
+    w = inputs.WORKLOADS[name]
+    print(f"[{name}] generating inputs", flush=True)
+    host = inputs.make(w)
+    dev = {k: gu.to_device(v, w.dtype) for k, v in host.items()}
+    rows = inputs.sample_rows(w.M, 256, PER_BLOCK[name], seed=w.cfg_id)
+    print(f"[{name}] oracle on {len(rows)} rows", flush=True)
+    ref = gu.oracle_rows(w, host, rows)
+    print(f"[{name}] fused", flush=True)
+    Y = gu.run(w, dev)
+    plan = ff.ffuse_last_plan().as_dict()
+    rel = gu.check(Y, ref, w.dtype, rows=rows, what=f"{name} fused")
+    print(f"[{name}] fused plan {plan} rel err {rel:.3e}", flush=True)
+    assert bool(torch.isfinite(Y.float()).all())
+    print(f"[{name}] unfused", flush=True)
+    Yu = gu.run(w, dev, unfused=True)
+    relu = gu.check(Yu, ref, w.dtype, rows=rows, what=f"{name} unfused")
+    scale = float(Yu.float().abs().max())
+    diff = float((Y.float() - Yu.float()).abs().max())
+    print(f"[{name}] unfused rel err {relu:.3e}; fused vs unfused {diff / scale:.3e}", flush=True)
+    assert diff <= 2 * gu.TOL[w.dtype] * scale

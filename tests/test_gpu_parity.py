@@ -1,0 +1,106 @@
+"""Parity of the HIP path (through the C ABI) against the fp64 CPU oracle, on the same seeded
+inputs.  Bar: max|Y - Y_ref| <= 2e-2 * max|Y_ref| for 16-bit operands, 1e-3 for fp32."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_12949_amd import binding as ff
+from paper_2512_12949_amd import inputs
+from paper_2512_12949_amd.inputs import ACT_GELU_TANH, ACT_IDENTITY, ACT_RELU, ACT_SILU
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+REDUCE_TILES = {False: [(256, 256), (128, 256), (128, 128), (128, 64)], True: [(256, 128), (128, 128), (128, 64)]}
+
+
+def _case(name, M, K, N1, N2, dtype, act, gated, dist="normal", cfg_id=900):
+    w = inputs.custom(name, M, K, N1, N2, dtype=dtype, act=act, gated=gated, dist=dist, cfg_id=cfg_id)
+    host = inputs.make(w)
+    dev = {k: gu.to_device(v, dtype) for k, v in host.items()}
+    return w, host, dev
+
+
+def test_tiny_fp32_config_fused_and_unfused():
+    w = inputs.WORKLOADS["tiny"]
+    host = inputs.make(w)
+    dev = {k: gu.to_device(v, w.dtype) for k, v in host.items()}
+    ref = gu.oracle_rows(w, host)
+    print("tiny fused   rel err", gu.check(gu.run(w, dev), ref, "f32", what="tiny fused"), flush=True)
+    print("tiny unfused rel err", gu.check(gu.run(w, dev, unfused=True), ref, "f32", what="tiny unfused"), flush=True)
+
+
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("act", [ACT_RELU, ACT_GELU_TANH, ACT_SILU, ACT_IDENTITY])
+def test_fp32_ragged(act, gated):
+    w, host, dev = _case("f32r", 37, 72, 200, 40, "f32", act, gated)
+    ref = gu.oracle_rows(w, host)
+    gu.check(gu.run(w, dev), ref, "f32", what="f32 fused")
+    gu.check(gu.run(w, dev, unfused=True), ref, "f32", what="f32 unfused")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("gated", [False, True])
+def test_every_reduce_tile_on_a_ragged_shape(dtype, gated):
+    """Several tiles in every dimension plus ragged tails in M, K, N1 and N2."""
+    act = ACT_SILU if gated else ACT_GELU_TANH
+    w, host, dev = _case("ragged", 300, 200, 328, 136, dtype, act, gated)
+    ref = gu.oracle_rows(w, host)
+    for bm, bh in REDUCE_TILES[gated]:
+        for raster in (1, 2):
+            plan = ff.make_plan(ff.FAMILY_REDUCE, bm, bh, raster=raster)
+            print(f"ragged {dtype} gated={gated} tile {bm}x{bh} raster {raster}", flush=True)
+            gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"tile {bm}x{bh}")
+    gu.check(gu.run(w, dev, unfused=True), ref, dtype, what="unfused")
+
+
+@pytest.mark.parametrize("act", [ACT_RELU, ACT_GELU_TANH, ACT_SILU, ACT_IDENTITY])
+@pytest.mark.parametrize("gated", [False, True])
+def test_activations_medium(act, gated):
+    w, host, dev = _case("medium", 512, 512, 1024, 384, "bf16", act, gated)
+    ref = gu.oracle_rows(w, host)
+    print("medium fused  ", gu.check(gu.run(w, dev), ref, "bf16", what="fused"), flush=True)
+    print("medium unfused", gu.check(gu.run(w, dev, unfused=True), ref, "bf16", what="unfused"), flush=True)
+
+
+@pytest.mark.parametrize("shape", [(1, 8, 8, 8), (1, 64, 64, 64), (3, 16, 24, 8), (257, 264, 72, 520), (64, 8, 1032, 16)])
+def test_degenerate_shapes(shape):
+    M, K, N1, N2 = shape
+    for gated in (False, True):
+        w, host, dev = _case("edge", M, K, N1, N2, "bf16", ACT_SILU, gated)
+        ref = gu.oracle_rows(w, host)
+        gu.check(gu.run(w, dev), ref, "bf16", what=f"fused {shape}")
+        gu.check(gu.run(w, dev, unfused=True), ref, "bf16", what=f"unfused {shape}")
+
+
+def test_zero_weights_give_exact_zero():
+    w, host, dev = _case("zero", 130, 64, 256, 128, "bf16", ACT_GELU_TANH, False)
+    dev["W2"] = torch.zeros_like(dev["W2"])
+    Y = gu.run(w, dev)
+    assert torch.all(Y == 0)
+    Y = gu.run(w, dev, unfused=True)
+    assert torch.all(Y == 0)
+
+
+def test_back_to_back_calls_share_one_workspace():
+    """The fused call leaves its fp32 sums at zero; an unfused call in between dirties the
+    workspace and the next fused call must still be right."""
+    w, host, dev = _case("b2b", 200, 128, 512, 256, "bf16", ACT_RELU, False)
+    ref = gu.oracle_rows(w, host)
+    for i in range(3):
+        gu.check(gu.run(w, dev), ref, "bf16", what=f"call {i}")
+    gu.check(gu.run(w, dev, unfused=True), ref, "bf16", what="unfused between")
+    gu.check(gu.run(w, dev), ref, "bf16", what="fused after unfused")
+
+
+def test_workspace_errors_on_device():
+    w, host, dev = _case("ws", 64, 64, 64, 64, "bf16", ACT_RELU, False)
+    Y = torch.empty((64, 64), dtype=torch.bfloat16, device="cuda")
+    ff.ffuse_set_workspace(None)
+    gu.Workspace.buf = None
+    assert ff.ffuse_ffn(dev["X"], dev["W1"], None, dev["W2"], ACT_RELU, Y, check=False) == -5
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    ff.ffuse_set_workspace(small)
+    assert ff.ffuse_ffn(dev["X"], dev["W1"], None, dev["W2"], ACT_RELU, Y, check=False) == -5
+    ff.ffuse_set_workspace(None)
