@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--oracle-rows", type=int, default=0, help="rows of the CPU-baseline sample (0 = auto)")
     ap.add_argument("--plan", default="", help="force a plan: family,bm,bh[,raster]")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU; --gpus N with N > 1 is not supported "
@@ -131,7 +133,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         per_row = flops / w.M
-        nrows = args.oracle_rows or int(max(1, min(w.M, 1.5e11 / per_row)))  # ~10-25 s of oracle work
+        nrows = args.oracle_rows or int(max(1, min(w.M, 1.2e12 / per_row)))  # ~10-25 s of oracle work
         rows = inputs.sample_rows(w.M, max(1, w.M // max(1, nrows // 2)), 2, seed=7)[:nrows]
         t0 = time.perf_counter()
         ref = oracle.ffn_rows(host["X"], host["W1"], host["W3"], host["W2"], w.act, rows=rows, bf16=(w.dtype == "bf16"))
@@ -142,6 +144,12 @@ def main():
                                "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": f"{len(rows)} of {w.M} rows, all {w.N2} columns, {t_cpu:.1f} s"}
         out["max_rel_err_vs_oracle"] = rel
+    if args.copy_calibration:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
     ff.ffuse_set_workspace(None)
     print(json.dumps(out))
 

@@ -59,7 +59,9 @@ typedef enum {
     FFUSE_ERR_WORKSPACE = -5, /* no workspace set, or it is too small for this call        */
     FFUSE_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch or a copy                */
     FFUSE_ERR_ARCH = -7,      /* the current device is not gfx950                          */
-    FFUSE_ERR_PLAN = -8       /* a forced plan is not valid for this problem               */
+    FFUSE_ERR_PLAN = -8,      /* a forced plan is not valid for this problem               */
+    FFUSE_ERR_TIMEOUT = -9,   /* a cooperative kernel gave up waiting for a peer workgroup  */
+    FFUSE_ERR_PLACEMENT = -10 /* workgroups of an exchange group did not share one XCD      */
 } ffuse_status_t;
 
 /*
@@ -88,7 +90,12 @@ typedef struct {
     int32_t splits;   /* number of partial second products summed per output element        */
     int32_t h_level;  /* where the activated slice lives: 0 registers, 1 LDS, 2 L2 buffer   */
     int32_t raster;   /* row blocks that share one XCD's L2 at a time                       */
-    int32_t reserved[4];
+    int32_t producers;/* exchange family: producer workgroups per XCD group (0 = default)  */
+    int32_t ring;     /* exchange family: ring slots per XCD group (0 = default)           */
+    int32_t coherent; /* exchange family: 0 = ring kept coherent through the XCD's shared L2
+                         (needs group x on XCD x, checked on the device); 1 = agent-scope
+                         release/acquire, valid for any placement, much slower            */
+    int32_t reserved[1];
 } ffuse_plan_t;
 
 /* Analytical data-movement volumes (Sec. 4.2, Algorithm 1) and per-level costs
@@ -143,10 +150,16 @@ int ffuse_choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64
 int ffuse_traffic_model(const ffuse_plan_t* plan, int dtype, int gated, int64_t M, int64_t K,
                         int64_t N1, int64_t N2, ffuse_traffic_t* out);
 /* Forces every later fused call onto *plan (NULL: back to the chooser).  Also settable with
- * the environment variable FFUSE_FORCE_PLAN="family,bm,bh,bn2,bk,splits,h_level,raster". */
+ * the environment variable FFUSE_FORCE_PLAN="family,bm,bh,bn2,bk,splits,h_level,raster,producers,ring,coherent". */
 int ffuse_force_plan(const ffuse_plan_t* plan);
-/* Plan used by the most recent fused call on this thread's library instance. */
+/* Plan used by the most recent fused call of this process. */
 int ffuse_last_plan(ffuse_plan_t* out);
+/* Blocks until `stream` is idle, then reports whether the most recent exchange-family launch
+ * ran to completion: FFUSE_OK, or FFUSE_ERR_TIMEOUT if a workgroup's bounded wait for a peer
+ * expired, or FFUSE_ERR_PLACEMENT if the XCD-local protocol found a workgroup on the wrong
+ * XCD (the output of that call is then undefined; force coherent = 1).  Other families
+ * always report OK. */
+int ffuse_sync_status(void* stream);
 
 /* ---- measurement aid: when enabled, the library brackets the dominant kernel of every
  *      fused / unfused call with HIP events on the call's stream.  ffuse_profile_read

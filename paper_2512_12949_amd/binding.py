@@ -22,7 +22,7 @@ EXPORTS = [
     "ffuse_ffn", "ffuse_ffn_f16", "ffuse_ffn_f32",
     "ffuse_ffn_unfused", "ffuse_ffn_unfused_f16", "ffuse_ffn_unfused_f32",
     "ffuse_workspace_bytes", "ffuse_set_workspace", "ffuse_choose_plan", "ffuse_traffic_model",
-    "ffuse_force_plan", "ffuse_last_plan", "ffuse_profile_enable", "ffuse_profile_read",
+    "ffuse_force_plan", "ffuse_last_plan", "ffuse_sync_status", "ffuse_profile_enable", "ffuse_profile_read",
     "ffuse_status_string", "ffuse_version",
 ]
 
@@ -30,7 +30,8 @@ EXPORTS = [
 class Plan(ctypes.Structure):
     _fields_ = [("family", ctypes.c_int32), ("bm", ctypes.c_int32), ("bh", ctypes.c_int32),
                 ("bn2", ctypes.c_int32), ("bk", ctypes.c_int32), ("splits", ctypes.c_int32),
-                ("h_level", ctypes.c_int32), ("raster", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
+                ("h_level", ctypes.c_int32), ("raster", ctypes.c_int32), ("producers", ctypes.c_int32),
+                ("ring", ctypes.c_int32), ("coherent", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
@@ -81,6 +82,8 @@ def lib():
         L.ffuse_force_plan.argtypes = [ctypes.POINTER(Plan)]
         L.ffuse_last_plan.restype = ci
         L.ffuse_last_plan.argtypes = [ctypes.POINTER(Plan)]
+        L.ffuse_sync_status.restype = ci
+        L.ffuse_sync_status.argtypes = [vp]
         L.ffuse_profile_enable.restype = ci
         L.ffuse_profile_enable.argtypes = [ci]
         L.ffuse_profile_read.restype = ci
@@ -186,6 +189,13 @@ def ffuse_last_plan() -> Plan:
     return p
 
 
+def ffuse_sync_status(stream=None, check=True):
+    rc = lib().ffuse_sync_status(_stream(stream))
+    if check:
+        _check(rc, "ffuse_sync_status")
+    return rc
+
+
 def ffuse_profile_enable(on: bool):
     _check(lib().ffuse_profile_enable(int(bool(on))), "ffuse_profile_enable")
 
@@ -200,7 +210,8 @@ def ffuse_version() -> int:
     return int(lib().ffuse_version())
 
 
-def make_plan(family, bm=0, bh=0, bn2=128, bk=64, splits=0, h_level=0, raster=4) -> Plan:
+def make_plan(family, bm=0, bh=0, bn2=128, bk=64, splits=0, h_level=0, raster=4, producers=0, ring=0, coherent=0) -> Plan:
     p = Plan()
     p.family, p.bm, p.bh, p.bn2, p.bk, p.splits, p.h_level, p.raster = family, bm, bh, bn2, bk, splits, h_level, raster
+    p.producers, p.ring, p.coherent = producers, ring, coherent
     return p

@@ -2,6 +2,7 @@
 // and kernel launches.  See include/ffuse.h for the contract of every entry point.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -26,6 +27,12 @@ struct State {
     bool profiling = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
     int arch_ok = -1;        // -1 unknown, 0 no, 1 yes
+    int cus = 0;             // compute units of the current device
+    uint32_t* exch_err = nullptr;  // device address of the error word of the last exchange launch
+    bool log = std::getenv("FFUSE_LOG") != nullptr;  // diagnostics on stderr
+    uint64_t* exch_stats = nullptr;
+    uint64_t* gemm_stats = nullptr;
+    int exch_wgs = 0;
 };
 State g;
 
@@ -37,6 +44,7 @@ int check_arch() {
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return FFUSE_ERR_LAUNCH;
         g.arch_ok = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 0;
+        g.cus = prop.multiProcessorCount;
     }
     return g.arch_ok == 1 ? FFUSE_OK : FFUSE_ERR_ARCH;
 }
@@ -60,12 +68,14 @@ void read_env_plan() {
     g.env_checked = true;
     const char* s = std::getenv("FFUSE_FORCE_PLAN");
     if (!s || !*s) return;
-    int v[8] = {0, 0, 0, 128, 64, 0, 0, 4};
-    const int n = std::sscanf(s, "%d,%d,%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7]);
+    int v[11] = {0, 0, 0, 128, 64, 0, 0, 4, 0, 0, 0};
+    const int n = std::sscanf(s, "%d,%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7],
+                              &v[8], &v[9], &v[10]);
     if (n >= 3) {
         std::memset(&g.forced_plan, 0, sizeof(g.forced_plan));
         g.forced_plan.family = v[0]; g.forced_plan.bm = v[1]; g.forced_plan.bh = v[2]; g.forced_plan.bn2 = v[3];
         g.forced_plan.bk = v[4]; g.forced_plan.splits = v[5]; g.forced_plan.h_level = v[6]; g.forced_plan.raster = v[7];
+        g.forced_plan.producers = v[8]; g.forced_plan.ring = v[9]; g.forced_plan.coherent = v[10];
         g.forced = true;
     }
 }
@@ -111,6 +121,28 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
         g.last_plan = plan;
         return FFUSE_OK;
     }
+    if (plan.family == FFUSE_FAMILY_EXCHANGE) {
+        ffuse::ExchangeGeometry e;
+        if (!ffuse::exchange_geometry(plan, gated, M, N1, N2, g.cus, &e)) return FFUSE_ERR_PLAN;
+        if (!g.ws || g.ws_bytes < e.ws_bytes) return FFUSE_ERR_WORKSPACE;
+        char* base = reinterpret_cast<char*>(g.ws);
+        if (ffuse::launch_zero(base, ffuse::kExchangeFlagBytes, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+        g.ws_dirty = true;  // the ring overwrites the region the reduce family keeps at zero
+        ffuse::ExchangeArgs x{X, W1, W3, W2, Y, base + ffuse::kExchangeFlagBytes, reinterpret_cast<uint32_t*>(base),
+                              M, (int)K, (int)N1, (int)N2, act, e.P, e.NCT, e.PG, e.R, e.NH, plan.coherent, nullptr};
+        if (g.log && g.ws_bytes >= e.ws_bytes + 8192 * 4) {
+            x.stats = reinterpret_cast<uint64_t*>(base + e.ws_bytes);
+            g.exch_stats = x.stats;
+            g.exch_wgs = 8 * e.wgs_per_group;
+            if (ffuse::launch_zero(x.stats, 8192 * 4, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+        }
+        g.exch_err = reinterpret_cast<uint32_t*>(base) + 16 * e.R;
+        Timer t(st);
+        if (ffuse::launch_fused_exchange(dtype, x, e.wgs_per_group, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+        t.stop();
+        g.last_plan = plan;
+        return FFUSE_OK;
+    }
     if (plan.family != FFUSE_FAMILY_REDUCE) return FFUSE_ERR_PLAN;
     const size_t need = sizeof(float) * (size_t)M * (size_t)N2;
     if (!g.ws || g.ws_bytes < need) return FFUSE_ERR_WORKSPACE;
@@ -119,6 +151,7 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
         g.ws_dirty = false;
     }
     a.Ysum = reinterpret_cast<float*>(g.ws);
+    g.exch_err = nullptr;
     {
         Timer t(st);
         if (ffuse::launch_fused_reduce(dtype, a, plan.bm, plan.bh, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
@@ -142,8 +175,15 @@ int run_unfused(int dtype, const void* X, const void* W1, const void* W3, const 
     if (!g.ws || g.ws_bytes < need) return FFUSE_ERR_WORKSPACE;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     g.ws_dirty = true;  // H overwrites whatever the fused path kept at zero
-    ffuse::GemmArgs g0{X, W1, W3, g.ws, M, (int)K, (int)N1, act, 4};
-    ffuse::GemmArgs g1{g.ws, W2, nullptr, Y, M, (int)N1, (int)N2, FFUSE_ACT_IDENTITY, 4};
+    g.exch_err = nullptr;
+    ffuse::GemmArgs g0{X, W1, W3, g.ws, M, (int)K, (int)N1, act, 4, nullptr};
+    ffuse::GemmArgs g1{g.ws, W2, nullptr, Y, M, (int)N1, (int)N2, FFUSE_ACT_IDENTITY, 4, nullptr};
+    if (g.log && dtype != FFUSE_DT_F32 && g.ws_bytes >= need + (1u << 20)) {
+        // diagnostics: per-workgroup phase times of both GEMMs behind the intermediate
+        g0.stats = reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(g.ws) + ((need + 255) & ~(size_t)255));
+        g1.stats = g0.stats + 4 * 16384;
+        g.gemm_stats = g0.stats;
+    }
     Timer t(st);
     hipError_t e = dtype == FFUSE_DT_F32 ? ffuse::launch_gemm_act_f32(g0, st) : ffuse::launch_gemm_act(dtype, g0, st);
     if (e != hipSuccess) return FFUSE_ERR_LAUNCH;
@@ -187,19 +227,24 @@ size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t
     if (M < 1 || N1 < 1 || N2 < 1) return 0;
     const size_t elem = dtype == FFUSE_DT_F32 ? 4 : 2;
     size_t b = unfused ? elem * (size_t)M * (size_t)N1 : (dtype == FFUSE_DT_F32 ? 0 : sizeof(float) * (size_t)M * (size_t)N2);
+    if (!unfused && dtype != FFUSE_DT_F32) {
+        // room for the exchange family's flags + ring at its largest ring setting
+        const size_t ex = ffuse::kExchangeFlagBytes + (size_t)8 * ffuse::kExchangeMaxRing * 256 * (gated ? 128 : 256) * 2;
+        if (ex > b) b = ex;
+    }
     return (b + 255) & ~(size_t)255;
 }
 
 int ffuse_set_workspace(void* dev_ptr, size_t bytes, void* stream) {
     std::lock_guard<std::mutex> lock(g.mu);
     if (!dev_ptr) {
-        g.ws = nullptr; g.ws_bytes = 0; g.ws_dirty = false;
+        g.ws = nullptr; g.ws_bytes = 0; g.ws_dirty = false; g.exch_err = nullptr;
         return FFUSE_OK;
     }
     if (!aligned16(dev_ptr)) return FFUSE_ERR_ALIGN;
     if (bytes % 16) return FFUSE_ERR_SHAPE;
     if (ffuse::launch_zero(dev_ptr, bytes, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return FFUSE_ERR_LAUNCH;
-    g.ws = dev_ptr; g.ws_bytes = bytes; g.ws_dirty = false;
+    g.ws = dev_ptr; g.ws_bytes = bytes; g.ws_dirty = false; g.exch_err = nullptr;
     return FFUSE_OK;
 }
 
@@ -235,6 +280,43 @@ int ffuse_last_plan(ffuse_plan_t* out) {
     std::lock_guard<std::mutex> lock(g.mu);
     *out = g.last_plan;
     return FFUSE_OK;
+}
+
+int ffuse_sync_status(void* stream) {
+    if (hipStreamSynchronize(reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return FFUSE_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g.mu);
+    if (g.log && g.gemm_stats) {
+        std::vector<uint64_t> h(8 * 16384);
+        if (hipMemcpy(h.data(), g.gemm_stats, h.size() * 8, hipMemcpyDeviceToHost) == hipSuccess) {
+            for (int k = 0; k < 2; ++k) {
+                double p = 0, l = 0, e = 0, st = 0; int n = 0;
+                for (int i = 0; i < 16384; ++i) {
+                    const uint64_t* q = &h[(size_t)k * 4 * 16384 + 4 * i];
+                    if (q[3]) { p += q[0]; l += q[1]; e += q[2]; st += q[3]; ++n; }
+                }
+                if (n) std::fprintf(stderr, "[ffuse] gemm %d: %d tiles, prologue %.2f us, loop %.2f us (%.3f us/step), epilogue %.2f us\n",
+                                    k, n, p / n * 0.01, l / n * 0.01, l / st * 0.01, e / n * 0.01);
+            }
+        }
+        g.gemm_stats = nullptr;
+    }
+    if (!g.exch_err) return FFUSE_OK;
+    uint32_t word = 0;
+    if (hipMemcpy(&word, g.exch_err, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess) return FFUSE_ERR_LAUNCH;
+    if (g.log && g.exch_stats) {
+        std::vector<uint64_t> h(4 * (size_t)g.exch_wgs);
+        if (hipMemcpy(h.data(), g.exch_stats, h.size() * 8, hipMemcpyDeviceToHost) == hipSuccess) {
+            for (int role = 1; role <= 2; ++role) {
+                double tot = 0, wt = 0, mx = 0, mxw = 0; int n = 0;
+                for (int i = 0; i < g.exch_wgs; ++i)
+                    if ((int)h[4 * i] == role) { tot += h[4 * i + 1]; wt += h[4 * i + 2]; mx = std::max(mx, (double)h[4 * i + 1]); mxw = std::max(mxw, (double)h[4 * i + 2]); ++n; }
+                if (n) std::fprintf(stderr, "[ffuse] exchange %s: %d wgs, busy+wait avg %.1f us (max %.1f), waiting avg %.1f us (max %.1f)\n",
+                                    role == 1 ? "producers" : "consumers", n, tot / n * 0.01, mx * 0.01, wt / n * 0.01, mxw * 0.01);
+            }
+        }
+    }
+    if (word & 2u) return FFUSE_ERR_PLACEMENT;
+    return word ? FFUSE_ERR_TIMEOUT : FFUSE_OK;
 }
 
 int ffuse_profile_enable(int on) {
@@ -274,6 +356,8 @@ const char* ffuse_status_string(int status) {
         case FFUSE_ERR_LAUNCH: return "HIP runtime error";
         case FFUSE_ERR_ARCH: return "device is not gfx950";
         case FFUSE_ERR_PLAN: return "plan not valid for this problem";
+        case FFUSE_ERR_TIMEOUT: return "a cooperative kernel timed out waiting for a peer workgroup";
+        case FFUSE_ERR_PLACEMENT: return "exchange group not placed on one XCD (force coherent = 1)";
         default: return "unknown status";
     }
 }

@@ -53,6 +53,16 @@ __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t b
 // 8x8 transpose of 16-bit elements held in registers.  in[r] = row r (8 elements, element c
 // in bits 16*(c%2) of dword c/2); out[c] = column c as 8 elements ordered by row.
 // ---------------------------------------------------------------------------------------
+// column c of the 8x8 block alone
+__device__ __forceinline__ u32x4 transpose8x8_col(const u32x4 (&in)[8], int c) {
+    u32x4 out;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t lo = in[2 * d][c >> 1], hi = in[2 * d + 1][c >> 1];
+        out[d] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+    }
+    return out;
+}
 __device__ __forceinline__ void transpose8x8_b16(const u32x4 (&in)[8], u32x4 (&out)[8]) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) {

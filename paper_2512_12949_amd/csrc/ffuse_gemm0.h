@@ -1,17 +1,24 @@
-// First product of the chain on the matrix cores: a BH x BM block of (X * W1)^T (and of
-// (X * W3)^T for the gated chain) with K innermost and complete, as the activation requires
-// (paper Sec. 4.3, Rule 3).  Shared by the fused kernels and by the plain GEMM kernel of the
-// unfused path.
+// Block GEMM on the matrix cores, shared by every 16-bit kernel of the library:
+//   D^T[BH x BM] += B^T[BH x K] * A^T[K x BM]
+// i.e. a BM x BH block of A*B (and of A*B3 for the gated chain) computed TRANSPOSED: the
+// weight matrix B[K][N] is the MFMA "A" operand, the row operand A[M][K] the MFMA "B"
+// operand, so that every lane ends up holding 4 consecutive columns n of one row m -- the
+// layout the second product of the chain wants for its own row operand, and the layout
+// that turns the output tile into 8-byte stores.
 //
-// The product is computed transposed -- weights are the MFMA "A" operand, X the "B" operand --
-// so that every lane ends up holding 4 consecutive hidden indices of one row of X: exactly
-// the operand layout the second product needs for H, with no shuffle in between.
+// K is innermost and complete before anything downstream sees the sums, as the activation
+// between the two products requires (paper Sec. 4.3, Rule 3).
 //
-// 256 threads = 4 waves arranged WM (over rows of X) x WN (over hidden columns).
-// Per K step of 64: X tile [BM][64] and W tile [64][BH] go global -> registers -> LDS
-// (weights through the 8x8 register transpose), double buffered in LDS, one barrier per step.
+// 256 threads = 4 waves arranged WM (over rows) x WN (over columns).  Per K step of 64:
+//   A tile [BM][64] and B tile [64][BH]: global -> registers -> LDS (B through an 8x8
+//   register transpose), LDS double buffered, one barrier per step, prefetch distance two
+//   steps: the registers loaded during step i are written to LDS during step i+1 (between
+//   its MFMAs) and multiplied in step i+2.
 #pragma once
+#include <utility>
+
 #include "ffuse_dev.h"
+
 
 namespace ffuse {
 
@@ -20,17 +27,18 @@ struct FirstGemm {
     static_assert(WM * WN == 4, "four waves");
     typedef typename Mma<T>::vec8 vec8;
     static constexpr int G = GATED ? 2 : 1;
-    static constexpr int WMR = BM / WM, WHR = BH / WN;  // rows / hidden columns per wave
+    static constexpr int WMR = BM / WM, WHR = BH / WN;  // rows / columns per wave
     static constexpr int MT = WMR / 32, HT = WHR / 32;  // 32x32 tiles per wave
     static_assert(MT >= 1 && HT >= 1 && BM % 32 == 0 && BH % 64 == 0, "tile shape");
-    static constexpr int XB = BM * 128;       // bytes of one X stage
-    static constexpr int WB = BH * 128;       // bytes of one weight stage
+    static constexpr int XB = BM * 128;       // bytes of one A stage
+    static constexpr int WB = BH * 128;       // bytes of one B stage
     static constexpr int STAGE = XB + G * WB;
     static constexpr int LDS_BYTES = 2 * STAGE;
-    static constexpr int XCH = BM / 32;       // 16-byte X chunks per thread per stage
-    static constexpr int NBLK1 = BH;          // 8x8 weight blocks per matrix per stage
+    static constexpr int XCH = BM / 32;       // 16-byte A chunks per thread per stage
+    static constexpr int NBLK1 = BH;          // 8x8 B blocks per matrix per stage
     static constexpr int NBLK = NBLK1 * G;
     static constexpr int WPT = (NBLK + 255) / 256;
+    static constexpr bool ALL_LOAD_B = (NBLK % 256) == 0;  // every thread owns a B block
 
     struct Stage {
         u32x4 x[XCH];
@@ -39,53 +47,70 @@ struct FirstGemm {
 
     struct Ctx {
         __amdgpu_buffer_rsrc_t rx;
-        __amdgpu_buffer_rsrc_t rw[WPT];  // W1 or W3, uniform per wave
-        uint32_t xoff[XCH];   // byte offset of this thread's X chunks at k0 = 0
-        uint32_t woff[WPT];   // byte offset of row 0 of this thread's weight block(s)
-        uint32_t wrow;        // bytes per weight row
-        uint32_t xc;          // this thread's chunk (0..7) within an X row
-        int K;
+        __amdgpu_buffer_rsrc_t rw[WPT];  // B or B3, uniform per wave
+        uint32_t xoff[XCH];   // byte offset of this thread's A chunks at k = 0
+        uint32_t abase;       // uniform byte offset added to every A offset (kOob: reads as zero)
+        uint32_t woff[WPT];   // byte offset of row 0 of this thread's B block(s)
+        uint32_t wrow;        // bytes per B row
+        uint32_t xc;          // this thread's chunk (0..7) within an A row
+        int KX;               // extent of the A operand along k (chunks at or past it read as 0)
+        // LDS read offsets of this lane's fragments at sub-step 0, stage 0
+        uint32_t rdx[MT], rdw[HT];
     };
 
-    // m0: first row of X; n0: first hidden column; N1: row length of the weights.
-    static __device__ __forceinline__ void init(Ctx& c, const void* X, const void* W1, const void* W3,
-                                                int64_t M, int K, int N1, int m0, int n0, int tid) {
-        c.rx = make_rsrc(X, (uint32_t)((uint64_t)M * K * 2));
-        c.K = K;
-        c.wrow = (uint32_t)N1 * 2u;
+    // A operand: `rows x lda` elements at `A` (+ base_bytes), first row row0; rows past the
+    // end of the buffer read as zero.
+    static __device__ __forceinline__ void init_a(Ctx& c, const void* A, uint32_t a_bytes, uint32_t base_bytes,
+                                                  uint32_t row0, uint32_t lda, int kx, int tid) {
+        c.rx = make_rsrc(A, a_bytes);
+        c.KX = kx;
+        c.abase = base_bytes;
         c.xc = tid & 7;
 #pragma unroll
         for (int p = 0; p < XCH; ++p) {
-            const uint32_t row = (uint32_t)m0 + (tid >> 3) + 32u * p;
-            c.xoff[p] = (row * (uint32_t)K + 8u * c.xc) * 2u;
+            const uint32_t row = row0 + (tid >> 3) + 32u * p;
+            c.xoff[p] = (row * lda + 8u * c.xc) * 2u;
         }
+    }
+    // B operands: [K][ldb] matrices, first column n0 (columns at or past ncols read as zero).
+    static __device__ __forceinline__ void init_b(Ctx& c, const void* B, const void* B3, uint32_t b_bytes,
+                                                  uint32_t ldb, uint32_t ncols, uint32_t n0, int tid) {
+        c.wrow = ldb * 2u;
 #pragma unroll
         for (int q = 0; q < WPT; ++q) {
             const int blk = tid + 256 * q;
             // which matrix this thread's block belongs to: constant per wave by construction
             int which = 0;
             if (GATED)
-                which = (NBLK1 >= 256) ? (256 * q) / NBLK1
-                                       : (__builtin_amdgcn_readfirstlane(tid / NBLK1) & 1);
-            c.rw[q] = make_rsrc(which ? W3 : W1, (uint32_t)((uint64_t)K * N1 * 2));
+                which = (NBLK1 >= 256) ? (256 * q) / NBLK1 : (__builtin_amdgcn_readfirstlane(tid / NBLK1) & 1);
+            c.rw[q] = make_rsrc(which ? B3 : B, b_bytes);
             const int b = blk % NBLK1;
             const int ng = b % (BH / 8), kg = b / (BH / 8);
-            const uint32_t col = (uint32_t)n0 + 8u * ng;
-            c.woff[q] = (blk < NBLK && col < (uint32_t)N1)
-                            ? ((uint32_t)(8 * kg) * (uint32_t)N1 + col) * 2u
-                            : kOob;
+            const uint32_t col = n0 + 8u * ng;
+            c.woff[q] = (blk < NBLK && col < ncols) ? ((uint32_t)(8 * kg) * ldb + col) * 2u : kOob;
         }
     }
-
-    static __device__ __forceinline__ void gload(const Ctx& c, Stage& s, int k0) {
-        const bool xok = (k0 + 8 * (int)c.xc) < c.K;
+    static __device__ __forceinline__ void init_lds(Ctx& c, int tid) {
+        const int wave = tid >> 6, lane = tid & 63;
+        const int wm = wave % WM, wn = wave / WM;
+        const uint32_t x = lane & 31, h = lane >> 5;
 #pragma unroll
-        for (int p = 0; p < XCH; ++p)
-            s.x[p] = buf_load16(c.rx, xok ? c.xoff[p] + (uint32_t)k0 * 2u : kOob);
+        for (int mt = 0; mt < MT; ++mt) c.rdx[mt] = lds_row_off(wm * WMR + 32 * mt + x, h);
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) c.rdw[ht] = XB + lds_col_off<BH>(wn * WHR + 32 * ht + x, h);
+    }
+
+    // global -> registers for the K step whose A columns start at kx / B rows at kw
+    static __device__ __forceinline__ void gload_a(const Ctx& c, Stage& s, int kx) {
+        const bool xok = (kx + 8 * (int)c.xc) < c.KX && c.abase != kOob;
+#pragma unroll
+        for (int p = 0; p < XCH; ++p) s.x[p] = buf_load16(c.rx, xok ? c.xoff[p] + c.abase + (uint32_t)kx * 2u : kOob);
+    }
+    static __device__ __forceinline__ void gload_b(const Ctx& c, Stage& s, int kw) {
 #pragma unroll
         for (int q = 0; q < WPT; ++q) {
             const uint32_t base = c.woff[q];
-            const uint32_t kb = (uint32_t)k0 * c.wrow;
+            const uint32_t kb = (uint32_t)kw * c.wrow;
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
                 const uint32_t off = (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow;
@@ -93,15 +118,20 @@ struct FirstGemm {
             }
         }
     }
+    static __device__ __forceinline__ void gload(const Ctx& c, Stage& s, int kx, int kw) {
+        gload_a(c, s, kx);
+        gload_b(c, s, kw);
+    }
 
-    static __device__ __forceinline__ void lds_store(char* smem, const Stage& s, int tid) {
+    static __device__ __forceinline__ void store_a(char* smem, const Stage& s, int tid) {
 #pragma unroll
-        for (int p = 0; p < XCH; ++p)
-            lds_write16(smem, lds_row_off((tid >> 3) + 32u * p, tid & 7), s.x[p]);
+        for (int p = 0; p < XCH; ++p) lds_write16(smem, lds_row_off((tid >> 3) + 32u * p, tid & 7), s.x[p]);
+    }
+    static __device__ __forceinline__ void store_b(char* smem, const Stage& s, int tid) {
 #pragma unroll
         for (int q = 0; q < WPT; ++q) {
             const int blk = tid + 256 * q;
-            if (blk < NBLK) {
+            if (ALL_LOAD_B || blk < NBLK) {
                 const int which = blk / NBLK1, b = blk % NBLK1;
                 const int ng = b % (BH / 8), kg = b / (BH / 8);
                 u32x4 t[8];
@@ -113,42 +143,127 @@ struct FirstGemm {
         }
     }
 
-    // One K step of 64 from the LDS stage at `smem`.
-    static __device__ __forceinline__ void compute(const char* smem, f32x16 (&acc)[HT][MT],
-                                                   f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
-                                                   int wm, int wn, int lane) {
-        const uint32_t x = lane & 31, h = lane >> 5;
+    struct Frags {
+        vec8 b[MT];
+        vec8 a[HT];
+        vec8 a3[GATED ? HT : 1];
+    };
+    // fragments of sub-step ks (k = 16*ks .. +15 of the stage at `smem`)
+    static __device__ __forceinline__ void load_frags(const char* smem, const Ctx& c, int ks, Frags& f) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const uint32_t chunk = 2 * ks + h;
-            vec8 b[MT];
+        for (int mt = 0; mt < MT; ++mt) f.b[mt] = lds_read16<vec8>(smem, c.rdx[mt] ^ (uint32_t)(ks << 5));
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                b[mt] = lds_read16<vec8>(smem, lds_row_off(wm * WMR + 32 * mt + x, chunk));
+        for (int ht = 0; ht < HT; ++ht) {
+            f.a[ht] = lds_read16<vec8>(smem, c.rdw[ht] ^ (uint32_t)(ks << 5));
+            if (GATED) f.a3[ht] = lds_read16<vec8>(smem + WB, c.rdw[ht] ^ (uint32_t)(ks << 5));
+        }
+    }
+    static __device__ __forceinline__ void mma_frags(const Frags& f, f32x16 (&acc)[HT][MT],
+                                                     f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1]) {
 #pragma unroll
-            for (int ht = 0; ht < HT; ++ht) {
-                const uint32_t off = lds_col_off<BH>(wn * WHR + 32 * ht + x, chunk);
-                const vec8 a = lds_read16<vec8>(smem + XB, off);
+        for (int ht = 0; ht < HT; ++ht) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) acc[ht][mt] = Mma<T>::mma(a, b[mt], acc[ht][mt]);
-                if (GATED) {
-                    const vec8 a3 = lds_read16<vec8>(smem + XB + WB, off);
+            for (int mt = 0; mt < MT; ++mt) acc[ht][mt] = Mma<T>::mma(f.a[ht], f.b[mt], acc[ht][mt]);
+            if (GATED) {
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) acc3[ht][mt] = Mma<T>::mma(a3, b[mt], acc3[ht][mt]);
-                }
+                for (int mt = 0; mt < MT; ++mt) acc3[ht][mt] = Mma<T>::mma(f.a3[ht], f.b[mt], acc3[ht][mt]);
             }
         }
     }
 
-    // Whole K loop.  On return acc[ht][mt][r] holds (X*W1)[m][n] with
-    //   m = m0 + wm*WMR + 32*mt + lane%32,
-    //   n = n0 + wn*WHR + 32*ht + 8*(r/4) + 4*(lane/32) + r%4,
-    // acc3 the same for W3.  Ends with a barrier: LDS may be reused by the caller.
-    static __device__ __forceinline__ void run(char* smem, const Ctx& c, f32x16 (&acc)[HT][MT],
-                                               f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
-                                               int tid) {
-        const int wave = tid >> 6, lane = tid & 63;
-        const int wm = wave % WM, wn = wave / WM;
+    // fragment read number i of a sub-step, in the order the MFMAs need them:
+    // b[0], a[0] (, a3[0]), b[1..MT-1], a[1] (, a3[1]), ...
+    static __device__ __forceinline__ void read_one(const char* smem, const Ctx& c, int ks, int i, Frags& f) {
+        const uint32_t kx = (uint32_t)(ks << 5);
+        if (i == 0) { f.b[0] = lds_read16<vec8>(smem, c.rdx[0] ^ kx); return; }
+        if (i == 1) { f.a[0] = lds_read16<vec8>(smem, c.rdw[0] ^ kx); return; }
+        int j = i - 2;
+        if (GATED) {
+            if (j == 0) { f.a3[0] = lds_read16<vec8>(smem + WB, c.rdw[0] ^ kx); return; }
+            j -= 1;
+        }
+        if (j < MT - 1) { f.b[j + 1] = lds_read16<vec8>(smem, c.rdx[j + 1] ^ kx); return; }
+        j -= MT - 1;
+        const int ht = 1 + j / G;
+        if (!GATED || (j % G) == 0) f.a[ht] = lds_read16<vec8>(smem, c.rdw[ht] ^ kx);
+        else f.a3[ht] = lds_read16<vec8>(smem + WB, c.rdw[ht] ^ kx);
+    }
+    // MFMA number i of a sub-step: ht-major, then (gate,) mt
+    static __device__ __forceinline__ void mma_one(const Frags& f, int i, f32x16 (&acc)[HT][MT],
+                                                   f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1]) {
+        const int ht = i / (MT * G), r = i % (MT * G);
+        if (!GATED || r < MT) acc[ht][r % MT] = Mma<T>::mma(f.a[ht], f.b[r % MT], acc[ht][r % MT]);
+        else acc3[GATED ? ht : 0][GATED ? r - MT : 0] = Mma<T>::mma(f.a3[GATED ? ht : 0], f.b[r - MT], acc3[GATED ? ht : 0][GATED ? r - MT : 0]);
+    }
+
+    // One K step of 64 out of the stage at `cur`.  Meanwhile the registers in `st` (loaded
+    // one step earlier) are written to the stage at `nxt` and re-filled from global memory
+    // for the step after that (A columns from kx, B rows from kw).  With one wave per SIMD
+    // nothing but the issue order hides latency, so the step is written as micro-chunks of
+    // one MFMA plus a little other work, fenced so the compiler keeps the interleaving:
+    //   sub-steps 0-2: the fragment reads of the next sub-step ride under the MFMAs,
+    //   sub-step 2   : + A stores to LDS, each followed by the A load that refills its register,
+    //   sub-step 3   : + B transpose, B stores and B loads.
+    static __device__ __forceinline__ void step(const char* cur, char* nxt, const Ctx& c, Stage& st, int kx, int kw,
+                                                f32x16 (&acc)[HT][MT],
+                                                f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1], int tid) {
+        constexpr int NM = HT * MT * G;   // MFMAs per sub-step
+        constexpr int NR = MT + HT * G;   // LDS fragment reads per sub-step
+        Frags f[2];
+#pragma unroll
+        for (int i = 0; i < NR; ++i) read_one(cur, c, 0, i, f[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        const bool xok = (kx + 8 * (int)c.xc) < c.KX && c.abase != kOob;
+        const uint32_t kb = (uint32_t)kw * c.wrow;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                mma_one(f[ks & 1], i, acc, acc3);
+                if (ks < 3) {
+#pragma unroll
+                    for (int e = (i * NR) / NM; e < ((i + 1) * NR) / NM; ++e) read_one(cur, c, ks + 1, e, f[(ks + 1) & 1]);
+                }
+                if (ks == 2) {
+#pragma unroll
+                    for (int e = (i * XCH) / NM; e < ((i + 1) * XCH) / NM; ++e) {
+                        lds_write16(nxt, lds_row_off((tid >> 3) + 32u * e, tid & 7), st.x[e]);
+                        st.x[e] = buf_load16(c.rx, xok ? c.xoff[e] + c.abase + (uint32_t)kx * 2u : kOob);
+                    }
+                }
+                if (ks == 3) {
+                    // first half of the MFMAs: transpose + store the 8*WPT columns of the old
+                    // B block(s); second half: refill the same registers (every column needs
+                    // all 8 old rows, so no row may be overwritten before the last store)
+                    constexpr int H1 = (NM + 1) / 2, H2 = NM - H1;
+                    if (i < H1) {
+#pragma unroll
+                        for (int e = (i * 8 * WPT) / H1; e < ((i + 1) * 8 * WPT) / H1; ++e) {
+                            const int q = e / 8, r = e % 8;
+                            const int blk = tid + 256 * q;
+                            if (ALL_LOAD_B || blk < NBLK) {
+                                const int which = blk / NBLK1, b = blk % NBLK1;
+                                const int ng = b % (BH / 8), kg = b / (BH / 8);
+                                lds_write16(nxt + XB + which * WB, lds_col_off<BH>(8 * ng + r, kg),
+                                            transpose8x8_col(st.w[q], r));
+                            }
+                        }
+                    } else {
+                        const int i2 = i - H1;
+#pragma unroll
+                        for (int e = (i2 * 8 * WPT) / (H2 > 0 ? H2 : 1); e < ((i2 + 1) * 8 * WPT) / (H2 > 0 ? H2 : 1); ++e) {
+                            const int q = e / 8, r = e % 8;
+                            const uint32_t base = c.woff[q];
+                            st.w[q][r] = buf_load16(c.rw[q], (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow);
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    static __device__ __forceinline__ void zero(f32x16 (&acc)[HT][MT], f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1]) {
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht)
 #pragma unroll
@@ -160,19 +275,76 @@ struct FirstGemm {
                     for (int r = 0; r < 16; ++r) acc3[ht][mt][r] = 0.0f;
                 }
             }
-        const int KT = (c.K + 63) / 64;
+    }
+
+    // Whole K loop over k = 0 .. K-1 (A columns and B rows advance together).  On return
+    // acc[ht][mt][r] holds (A*B)[m][n] with
+    //   m = row0 + wm*WMR + 32*mt + lane%32,
+    //   n = n0 + wn*WHR + 32*ht + 8*(r/4) + 4*(lane/32) + r%4,
+    // acc3 the same for B3.  Loads past K return zeros (buffer range check), so the
+    // prefetch needs no tail branch.  Ends with a barrier: LDS may be reused by the caller.
+    static __device__ __forceinline__ void run(char* smem, const Ctx& c, int K, f32x16 (&acc)[HT][MT],
+                                               f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1], int tid,
+                                               uint64_t* t_loop = nullptr) {
+        zero(acc, acc3);
+        const int KT = (K + 63) / 64;
         Stage st;
-        gload(c, st, 0);
-        lds_store(smem, st, tid);
+        gload(c, st, 0, 0);
+        store_a(smem, st, tid);
+        store_b(smem, st, tid);
+        gload(c, st, 64, 64);
         __syncthreads();
+        if (t_loop) *t_loop = wall_clock64();
         for (int kt = 0; kt < KT; ++kt) {
             char* cur = smem + (kt & 1) * STAGE;
             char* nxt = smem + ((kt + 1) & 1) * STAGE;
-            const bool more = kt + 1 < KT;
-            if (more) gload(c, st, (kt + 1) * 64);
-            compute(cur, acc, acc3, wm, wn, lane);
-            if (more) lds_store(nxt, st, tid);
+            step(cur, nxt, c, st, (kt + 2) * 64, (kt + 2) * 64, acc, acc3, tid);
             __syncthreads();
+        }
+    }
+
+    // acc (and the gate) -> activation -> type T -> C[row][col] (leading dimension ldc),
+    // rows < row_lim and columns < col_lim only.  8-byte stores: 4 consecutive columns.
+    template <int ACT>
+    static __device__ __forceinline__ void store_tile(const f32x16 (&acc)[HT][MT],
+                                                      const f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
+                                                      char* C, int64_t ldc, int64_t row0, int col0,
+                                                      int64_t row_lim, int col_lim, int tid) {
+        const int wave = tid >> 6, lane = tid & 63;
+        const int wm = wave % WM, wn = wave / WM;
+        const int x = lane & 31, h = lane >> 5;
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int64_t row = row0 + wm * WMR + 32 * mt + x;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = col0 + wn * WHR + 32 * ht + 8 * q + 4 * h;
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = activate<ACT>(acc[ht][mt][4 * q + e]);
+                        if (GATED) v[e] *= acc3[ht][mt][4 * q + e];
+                    }
+                    if (row < row_lim && col < col_lim) {
+                        uint2 o;
+                        o.x = pack2<T>(v[0], v[1]);
+                        o.y = pack2<T>(v[2], v[3]);
+                        *reinterpret_cast<uint2*>(C + (row * ldc + col) * 2) = o;
+                    }
+                }
+            }
+    }
+    static __device__ __forceinline__ void store_tile_rt(int act, const f32x16 (&acc)[HT][MT],
+                                                         const f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
+                                                         char* C, int64_t ldc, int64_t row0, int col0,
+                                                         int64_t row_lim, int col_lim, int tid) {
+        switch (act) {
+            case ACT_RELU: store_tile<ACT_RELU>(acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
+            case ACT_GELU_TANH: store_tile<ACT_GELU_TANH>(acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
+            case ACT_SILU: store_tile<ACT_SILU>(acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
+            default: store_tile<ACT_IDENTITY>(acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
         }
     }
 };

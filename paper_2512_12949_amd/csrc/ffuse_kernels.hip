@@ -1,11 +1,15 @@
 // gfx950 kernels of the 16-bit paths:
-//   * fused_reduce_kernel  -- the whole chain for one (row block, hidden slice) unit; the
+//   * fused_reduce_kernel   -- the whole chain for one (row block, hidden slice) unit; the
 //     activated slice never leaves registers; partial second products are summed across
-//     hidden slices with fp32 atomics (paper Sec. 4.1: "reduce" strategy, with the hidden
+//     hidden slices with fp32 atomics (paper Sec. 4.1 "reduce" strategy, with the hidden
 //     split taking the place of the cluster's n dimension).
-//   * finalize_kernel      -- fp32 sums -> Y in the operand type, workspace back to zero.
-//   * gemm_act_kernel      -- plain GEMM with the activation/gate epilogue: the two launches of
-//     the unfused comparison path.
+//   * fused_exchange_kernel -- persistent cooperative kernel; on every XCD some workgroups
+//     produce activated tiles into a ring buffer that stays in that XCD's L2, the others
+//     consume them into register-resident output tiles (Sec. 4.1 "shuffle" strategy with
+//     the XCD as the cluster and its L2 as the shared on-chip pool).
+//   * finalize_kernel       -- fp32 sums -> Y in the operand type, workspace back to zero.
+//   * gemm_act_kernel       -- plain GEMM with the activation/gate epilogue: the two launches
+//     of the unfused comparison path.
 #include "ffuse_gemm0.h"
 #include "ffuse_launch.h"
 
@@ -14,7 +18,7 @@ namespace ffuse {
 // blockIdx -> work unit, XCD aware.  Workgroups are dealt round-robin to the 8 XCDs, so
 // blockIdx % 8 is the XCD and blockIdx / 8 the arrival order on it.  Each XCD gets one
 // contiguous range of units ordered so that the ~32 units in flight on it form a patch of
-// `raster` row blocks x consecutive hidden slices: the patch shares X row blocks and weight
+// `raster` row blocks x consecutive column slices: the patch shares row blocks and weight
 // slices through that XCD's L2.
 __device__ __forceinline__ bool map_unit(int MB, int S, int raster, int& i, int& s) {
     const int total = MB * S;
@@ -30,18 +34,33 @@ __device__ __forceinline__ bool map_unit(int MB, int S, int raster, int& i, int&
     return true;
 }
 
-template <typename T> __device__ __forceinline__ float act_rt(int act, float x) {
-    switch (act) {
-        case ACT_RELU: return activate<ACT_RELU>(x);
-        case ACT_GELU_TANH: return activate<ACT_GELU_TANH>(x);
-        case ACT_SILU: return activate<ACT_SILU>(x);
-        default: return x;
-    }
-}
-
 // ---------------------------------------------------------------------------------------
 // Fused chain, "reduce" family.
 // ---------------------------------------------------------------------------------------
+template <typename T, bool GATED, int HT, int MT, int ACT>
+__device__ __forceinline__ void make_h(const f32x16 (&acc)[HT][MT], const f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
+                                       typename Mma<T>::vec8 (&hreg)[HT][MT][2]) {
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                u32x4 pk;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    float v0 = activate<ACT>(acc[ht][mt][8 * b + 2 * d]);
+                    float v1 = activate<ACT>(acc[ht][mt][8 * b + 2 * d + 1]);
+                    if (GATED) {
+                        v0 *= acc3[ht][mt][8 * b + 2 * d];
+                        v1 *= acc3[ht][mt][8 * b + 2 * d + 1];
+                    }
+                    pk[d] = pack2<T>(v0, v1);
+                }
+                hreg[ht][mt][b] = __builtin_bit_cast(typename Mma<T>::vec8, pk);
+            }
+}
+
 template <typename T, bool GATED, int BM, int BH>
 __global__ __launch_bounds__(256) void fused_reduce_kernel(FusedArgs a) {
     typedef FirstGemm<T, GATED, BM, BH, 4, 1> G0;
@@ -66,33 +85,22 @@ __global__ __launch_bounds__(256) void fused_reduce_kernel(FusedArgs a) {
     f32x16 acc3[GATED ? HT : 1][GATED ? MT : 1];
     {
         typename G0::Ctx c;
-        G0::init(c, a.X, a.W1, a.W3, a.M, a.K, a.N1, m0, n0, tid);
-        G0::run(smem, c, acc, acc3, tid);
+        G0::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)m0, (uint32_t)a.K, a.K, tid);
+        G0::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1, (uint32_t)n0, tid);
+        G0::init_lds(c, tid);
+        G0::run(smem, c, a.K, acc, acc3, tid);
     }
 
     // ---- activation (and gate) on complete sums; round to the operand type.  Registers
     //      8b..8b+7 of a tile are the 8 k-slots this lane feeds to the second product for
     //      hidden block 16*(2*ht + b): slot e <-> hidden 32*ht + 16*b + 8*(e/4) + 4*(lane/32) + e%4.
     vec8 hreg[HT][MT][2];
-#pragma unroll
-    for (int ht = 0; ht < HT; ++ht)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                u32x4 pk;
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    float v0 = act_rt<T>(a.act, acc[ht][mt][8 * b + 2 * d]);
-                    float v1 = act_rt<T>(a.act, acc[ht][mt][8 * b + 2 * d + 1]);
-                    if (GATED) {
-                        v0 *= acc3[ht][mt][8 * b + 2 * d];
-                        v1 *= acc3[ht][mt][8 * b + 2 * d + 1];
-                    }
-                    pk[d] = pack2<T>(v0, v1);
-                }
-                hreg[ht][mt][b] = __builtin_bit_cast(vec8, pk);
-            }
+    switch (a.act) {
+        case ACT_RELU: make_h<T, GATED, HT, MT, ACT_RELU>(acc, acc3, hreg); break;
+        case ACT_GELU_TANH: make_h<T, GATED, HT, MT, ACT_GELU_TANH>(acc, acc3, hreg); break;
+        case ACT_SILU: make_h<T, GATED, HT, MT, ACT_SILU>(acc, acc3, hreg); break;
+        default: make_h<T, GATED, HT, MT, ACT_IDENTITY>(acc, acc3, hreg); break;
+    }
 
     // ---- second product: for every block of BN2 output columns, H (registers) times the
     //      W2 rows of this hidden slice, then fp32 atomic adds into the sums -------------
@@ -212,43 +220,227 @@ __global__ __launch_bounds__(256) void gemm_act_kernel(GemmArgs a) {
     typedef FirstGemm<T, GATED, BM, BH, 2, 2> G0;
     constexpr int MT = G0::MT, HT = G0::HT;
     __shared__ __attribute__((aligned(16))) char smem[G0::LDS_BYTES];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     const int MB = (int)((a.M + BM - 1) / BM), S = (a.N + BH - 1) / BH;
     int ui, us;
     if (!map_unit(MB, S, a.raster, ui, us)) return;
     const int m0 = ui * BM, n0 = us * BH;
     f32x16 acc[HT][MT];
     f32x16 acc3[GATED ? HT : 1][GATED ? MT : 1];
-    {
-        typename G0::Ctx c;
-        G0::init(c, a.A, a.B, a.B3, a.M, a.K, a.N, m0, n0, tid);
-        G0::run(smem, c, acc, acc3, tid);
+    typename G0::Ctx c;
+    G0::init_a(c, a.A, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)m0, (uint32_t)a.K, a.K, tid);
+    G0::init_b(c, a.B, a.B3, (uint32_t)((uint64_t)a.K * a.N * 2), (uint32_t)a.N, (uint32_t)a.N, (uint32_t)n0, tid);
+    G0::init_lds(c, tid);
+    uint64_t t0 = 0, t1 = 0, t2 = 0;
+    if (a.stats) t0 = wall_clock64();
+    G0::run(smem, c, a.K, acc, acc3, tid, a.stats ? &t1 : nullptr);
+    if (a.stats) t2 = wall_clock64();
+    G0::store_tile_rt(a.act, acc, acc3, reinterpret_cast<char*>(a.C), a.N, m0, n0, a.M, a.N, tid);
+    if (a.stats && tid == 0) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        uint64_t* p = a.stats + 4 * blockIdx.x;
+        p[0] = t1 - t0; p[1] = t2 - t1; p[2] = wall_clock64() - t2; p[3] = (uint64_t)((a.K + 63) / 64);
     }
-    const int wm = wave % 2, wn = wave / 2;
-    const int x = lane & 31, h = lane >> 5;
-    char* C = reinterpret_cast<char*>(a.C);
-#pragma unroll
-    for (int ht = 0; ht < HT; ++ht)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int64_t row = (int64_t)m0 + wm * G0::WMR + 32 * mt + x;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = n0 + wn * G0::WHR + 32 * ht + 8 * q + 4 * h;
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    v[e] = act_rt<T>(a.act, acc[ht][mt][4 * q + e]);
-                    if (GATED) v[e] *= acc3[ht][mt][4 * q + e];
-                }
-                if (row < a.M && col < a.N) {
-                    uint2 o;
-                    o.x = pack2<T>(v[0], v[1]);
-                    o.y = pack2<T>(v[2], v[3]);
-                    *reinterpret_cast<uint2*>(C + (row * a.N + col) * 2) = o;
-                }
+}
+
+// ---------------------------------------------------------------------------------------
+// Fused chain, "exchange" family.  One persistent workgroup per CU, launched cooperatively
+// so that all of them are resident.  The workgroups with blockIdx % 8 == x form group x
+// (one XCD under round-robin dispatch); within a group the first P are producers, the next
+// PG*NCT are consumers:
+//   producer q  : H tile (256 rows x BHP hidden) = act(X W1)[.* X W3] for item o = q, q+P, ...
+//                 written to ring slot o % R in the operand type, then ready[slot] = o + 1
+//   consumer c  : owns output tile (panel pi = c / NCT, 256 columns ct = c % NCT) of the group
+//                 of PG panels in flight; for every hidden tile h it waits for item
+//                 o = (g*NH + h)*PG + pi, multiplies it with W2[h*BHP.., ct*256..] into its
+//                 register accumulators, then done[slot] += 1; after the last h it stores Y.
+// Items are ordered (group of panels g, hidden tile h, panel in group pi); a producer may
+// overwrite slot s only when the NCT consumers of the item that used it R items earlier are
+// done.  Flags are agent-scope release/acquire, so results do not depend on where
+// workgroups land; placement on one XCD only makes the ring traffic L2 hits.
+// All waits are bounded: on expiry the error word is set and every workgroup leaves.
+// ---------------------------------------------------------------------------------------
+static constexpr uint32_t kSpinLimit = 1u << 23;
+
+// Coherence of the ring.  All workgroups of a group run on one XCD and therefore share one
+// L2: a producer's stores are visible to its group as soon as they have completed
+// (s_waitcnt vmcnt(0)), and a consumer only has to drop its CU's own vector L1, which may
+// still hold lines of the slot's previous use (buffer_inv sc0).  Flags are relaxed
+// agent-scope atomics.  No L2 write-back or invalidate is involved: an agent-scope
+// acquire would invalidate the whole L2 of the XCD on every wait.  `coherent` != 0 selects
+// full agent-scope release/acquire instead (correct for any placement, much slower).
+__device__ __forceinline__ void drop_l1() { asm volatile("buffer_inv sc0" ::: "memory"); }
+__device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ bool wait_at_least(uint32_t* flag, uint32_t want, uint32_t* err, uint32_t* sh, int coherent) {
+    // thread 0 polls; the verdict is broadcast through LDS word sh[0]
+    if (threadIdx.x == 0) {
+        uint32_t spins = 0, ok = 1;
+        while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
+            __builtin_amdgcn_s_sleep(2);
+            if ((++spins & 1023u) == 0 &&
+                (spins > kSpinLimit || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+                __hip_atomic_fetch_or(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
+                break;
             }
         }
+        sh[0] = ok;
+    }
+    __syncthreads();
+    const bool ok = sh[0] != 0;
+    if (coherent) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    else drop_l1();
+    __syncthreads();
+    return ok;
+}
+
+// optional per-workgroup timing (args.stats != nullptr): 100 MHz wall-clock ticks
+struct ExchStats {
+    uint64_t t0 = 0, wait = 0, tw = 0;
+    __device__ __forceinline__ void begin_wait(const void* on) { if (on) tw = wall_clock64(); }
+    __device__ __forceinline__ void end_wait(const void* on) { if (on) wait += wall_clock64() - tw; }
+};
+
+template <typename T, bool GATED>
+__global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
+    constexpr int BHP = GATED ? 128 : 256;
+    typedef FirstGemm<T, GATED, 256, BHP, 2, 2> GP;   // producer: X * W1 (, X * W3)
+    typedef FirstGemm<T, false, 256, 256, 2, 2> GC;   // consumer: H * W2
+    constexpr int LDS_BYTES = GP::LDS_BYTES > GC::LDS_BYTES ? GP::LDS_BYTES : GC::LDS_BYTES;
+    constexpr uint32_t SLOT_BYTES = 256u * BHP * 2u;
+    constexpr int SPI = BHP / 64;                     // K steps per item on the consumer side
+    __shared__ __attribute__((aligned(16))) char smem[LDS_BYTES];
+    __shared__ uint32_t verdict[4];
+
+    const int tid = threadIdx.x;
+    const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
+    const int P = a.P, NCT = a.NCT, PG = a.PG, R = a.R, NH = a.NH;
+    const int NP = (int)((a.M + 255) / 256);
+    const int NG = (NP + PG - 1) / PG;                       // groups of panels
+    const int ngx = (NG > xcd) ? (NG - xcd + 7) / 8 : 0;      // groups handled by this XCD
+    const int items = ngx * NH * PG;
+    uint32_t* ready = a.flags + xcd * 2 * R;
+    uint32_t* done = ready + R;
+    uint32_t* err = a.flags + 16 * R;
+    char* ring = a.ring + (size_t)xcd * R * SLOT_BYTES;
+    const int coherent = a.coherent;
+    ExchStats es;
+    if (a.stats) es.t0 = wall_clock64();
+    auto finish = [&](int role, int n) {
+        if (a.stats && tid == 0) {
+            uint64_t* p = a.stats + 4 * blockIdx.x;
+            p[0] = (uint64_t)role; p[1] = wall_clock64() - es.t0; p[2] = es.wait; p[3] = (uint64_t)n;
+        }
+    };
+    if (!coherent) {
+        // the fast protocol needs every workgroup of group x on XCD x
+        uint32_t xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(xcc));
+        if ((int)xcc != xcd) {
+            if (tid == 0) __hip_atomic_fetch_or(err, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+    }
+
+    {
+        // ------------------------------------------------------------------ producer
+        // Round 0: the first E = min(workgroups, ring slots) items are produced by ALL
+        // workgroups of the group (consumers have nothing to multiply yet, and no slot is
+        // being reused, so nobody waits).  After that producer q makes items E + q, E + q + P, ...
+        f32x16 acc[GP::HT][GP::MT];
+        f32x16 acc3[GATED ? GP::HT : 1][GATED ? GP::MT : 1];
+        typename GP::Ctx c;
+        GP::init_lds(c, tid);
+        const int wpx = (int)(gridDim.x >> 3);
+        const int E = min(min(wpx, R), items);
+        int o = (loc < E) ? loc : (loc < P ? E + loc : items);
+        bool first = true;
+        while (o < items) {
+            const int pi = o % PG, t = o / PG, hh = t % NH, gseq = t / NH;
+            const int panel = (xcd + 8 * gseq) * PG + pi;
+            const int slot = o % R;
+            es.begin_wait(a.stats);
+            if (!wait_at_least(done + slot, (uint32_t)(o / R) * NCT, err, verdict, coherent)) return;
+            es.end_wait(a.stats);
+            if (panel < NP) {
+                GP::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)panel * 256u, (uint32_t)a.K, a.K, tid);
+                GP::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1,
+                           (uint32_t)hh * BHP, tid);
+                GP::run(smem, c, a.K, acc, acc3, tid);
+                GP::store_tile_rt(a.act, acc, acc3, ring + (size_t)slot * SLOT_BYTES, BHP, 0, 0, 256, BHP, tid);
+            }
+            stores_done();     // this thread's tile stores have reached L2
+            __syncthreads();   // ... and so have everybody else's
+            if (tid == 0) {
+                if (coherent) __hip_atomic_store(ready + slot, (uint32_t)o + 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                else __hip_atomic_store(ready + slot, (uint32_t)o + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (loc >= P) break;   // consumers and spare workgroups produce one item at most
+            o = (first && loc < E) ? E + loc : o + P;
+            first = false;
+        }
+        if (loc < P) {
+            finish(1, items);
+            return;
+        }
+    }
+    const int cidx = loc - P;
+    if (cidx >= PG * NCT) return;
+    // ---------------------------------------------------------------------- consumer
+    const int pi = cidx / NCT, ct = cidx % NCT;
+    f32x16 acc[GC::HT][GC::MT];
+    f32x16 acc3[1][1];
+    typename GC::Ctx c;
+    GC::init_lds(c, tid);
+    GC::init_b(c, a.W2, nullptr, (uint32_t)((uint64_t)a.N1 * a.N2 * 2), (uint32_t)a.N2, (uint32_t)a.N2, (uint32_t)ct * 256u, tid);
+    typename GC::Stage st;
+    for (int gseq = 0; gseq < ngx; ++gseq) {
+        // a panel past the end (ragged last group) is processed like any other: its producers
+        // publish nothing, its consumers multiply whatever the slot holds and store nothing
+        const int panel = (xcd + 8 * gseq) * PG + pi;
+        GC::zero(acc, acc3);
+        const int o0 = gseq * NH * PG + pi;   // item of hidden tile 0; tile h is o0 + h*PG
+        // A operand = ring slot of the item (256 x BHP, leading dimension BHP); B rows h*BHP + k.
+        // Loads run two K steps ahead, i.e. at most into the next item: item h+1 must be
+        // ready before the steps of item h are issued.
+        es.begin_wait(a.stats);
+        if (!wait_at_least(ready + o0 % R, (uint32_t)o0 + 1u, err, verdict, coherent)) return;
+        es.end_wait(a.stats);
+        GC::init_a(c, ring, (uint32_t)R * SLOT_BYTES, (uint32_t)(o0 % R) * SLOT_BYTES, 0u, BHP, BHP, tid);
+        GC::gload(c, st, 0, 0);
+        GC::store_a(smem, st, tid);
+        GC::store_b(smem, st, tid);
+        GC::gload(c, st, 64, 64);
+        __syncthreads();
+        for (int hh = 0; hh < NH; ++hh) {
+            const int o = o0 + hh * PG, on = o + PG;
+            if (hh + 1 < NH) {
+                es.begin_wait(a.stats);
+                if (!wait_at_least(ready + on % R, (uint32_t)on + 1u, err, verdict, coherent)) return;
+                es.end_wait(a.stats);
+            }
+            const uint32_t base_cur = (uint32_t)(o % R) * SLOT_BYTES;
+            const uint32_t base_nxt = (hh + 1 < NH) ? (uint32_t)(on % R) * SLOT_BYTES : kOob;
+#pragma unroll 1
+            for (int ks = 0; ks < SPI; ++ks) {
+                // step s = hh*SPI + ks multiplies; loads fetch step s + 2
+                const int k2 = (ks + 2) % SPI * 64;
+                const bool wrap = ks + 2 >= SPI;
+                c.abase = wrap ? base_nxt : base_cur;
+                const int kw2 = (wrap ? hh + 1 : hh) * BHP + k2;
+                char* cur = smem + (ks & 1) * GC::STAGE;
+                char* nxt = smem + ((ks + 1) & 1) * GC::STAGE;
+                GC::step(cur, nxt, c, st, k2, kw2, acc, acc3, tid);
+                __syncthreads();
+            }
+            // every wave has multiplied the item's last step: release its slot
+            if (tid == 0) __hip_atomic_fetch_add(done + o % R, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        GC::template store_tile<ACT_IDENTITY>(acc, acc3, reinterpret_cast<char*>(a.Y), a.N2, (int64_t)panel * 256,
+                                              ct * 256, a.M, a.N2, tid);
+    }
+    finish(2, ngx * NH);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -281,11 +473,6 @@ hipError_t launch_fused_reduce(int dtype, const FusedArgs& a, int bm, int bh, hi
     return dtype == 0 ? launch_fused_dt<__bf16>(a, bm, bh, st) : launch_fused_dt<_Float16>(a, bm, bh, st);
 }
 
-bool fused_reduce_supported(int gated, int bm, int bh) {
-    if (!gated) return (bm == 256 && bh == 256) || (bm == 128 && (bh == 256 || bh == 128 || bh == 64));
-    return (bm == 256 && bh == 128) || (bm == 128 && (bh == 128 || bh == 64));
-}
-
 hipError_t launch_finalize(int dtype, float* sums, void* Y, int64_t count, hipStream_t st) {
     const int64_t n8 = count / 8;
     const int blocks = (int)((n8 + 255) / 256);
@@ -307,6 +494,16 @@ template <typename T> static hipError_t launch_gemm_dt(const GemmArgs& a, hipStr
 
 hipError_t launch_gemm_act(int dtype, const GemmArgs& a, hipStream_t st) {
     return dtype == 0 ? launch_gemm_dt<__bf16>(a, st) : launch_gemm_dt<_Float16>(a, st);
+}
+
+hipError_t launch_fused_exchange(int dtype, const ExchangeArgs& a, int wgs_per_group, hipStream_t st) {
+    const void* fn = nullptr;
+    const bool g = a.W3 != nullptr;
+    if (dtype == 0) fn = g ? (const void*)fused_exchange_kernel<__bf16, true> : (const void*)fused_exchange_kernel<__bf16, false>;
+    else fn = g ? (const void*)fused_exchange_kernel<_Float16, true> : (const void*)fused_exchange_kernel<_Float16, false>;
+    ExchangeArgs copy = a;
+    void* params[] = {&copy};
+    return hipLaunchCooperativeKernel(fn, dim3(8 * wgs_per_group), dim3(256), params, 0, st);
 }
 
 }  // namespace ffuse

@@ -27,11 +27,32 @@ struct GemmArgs {
     int K, N;
     int act;
     int raster;
+    uint64_t* stats;  // nullptr, or 4 words per workgroup: ticks of prologue, main loop, epilogue; step count
+};
+
+struct ExchangeArgs {
+    const void* X;
+    const void* W1;
+    const void* W3;  // nullptr: not gated
+    const void* W2;
+    void* Y;
+    char* ring;       // 8 * R slots of 256 x BHP elements (BHP = 256, or 128 when gated)
+    uint32_t* flags;  // per group: ready[R], done[R]; then one error word.  Zero on entry.
+    int64_t M;
+    int K, N1, N2;
+    int act;
+    int P;            // producers per group
+    int NCT;          // 256-wide output column tiles = consumers per panel
+    int PG;           // panels in flight per group
+    int R;            // ring slots per group
+    int NH;           // hidden tiles per panel
+    int coherent;     // 0: XCD-local ring protocol; 1: agent-scope release/acquire
+    uint64_t* stats;  // nullptr, or 4 words per workgroup: role, total ticks, waiting ticks, items
 };
 
 // 16-bit paths (dtype 0 = bf16, 1 = fp16)
+hipError_t launch_fused_exchange(int dtype, const ExchangeArgs& a, int wgs_per_group, hipStream_t st);
 hipError_t launch_fused_reduce(int dtype, const FusedArgs& a, int bm, int bh, hipStream_t st);
-bool fused_reduce_supported(int gated, int bm, int bh);
 hipError_t launch_finalize(int dtype, float* sums, void* Y, int64_t count, hipStream_t st);
 hipError_t launch_gemm_act(int dtype, const GemmArgs& a, hipStream_t st);
 

@@ -33,6 +33,7 @@ const Device kDevice = {
     /*atomic_bw*/ 1.36e12,      // fp32 atomic add, one dword per L2 channel per clock
     /*lds_bytes*/ 160 * 1024, /*acc_regs*/ 256, /*l2_bytes*/ 4.0 * 1024 * 1024,
     /*mall_bytes*/ 256.0 * 1024 * 1024,
+    /*mfma_eff*/ 0.45,          // measured: the register-staged 256x256x64 main loop
     /*launch_s*/ 4e-6};
 
 static double cdiv(double a, double b) { return std::ceil(a / b); }
@@ -45,8 +46,31 @@ bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t 
         case FFUSE_FAMILY_REDUCE:
             if (dtype == FFUSE_DT_F32) return false;
             return fused_reduce_tile_ok(gated, p.bm, p.bh) && p.raster >= 1;
+        case FFUSE_FAMILY_EXCHANGE: {
+            if (dtype == FFUSE_DT_F32) return false;
+            ExchangeGeometry e;
+            return exchange_geometry(p, gated, M, N1, N2, kDevice.cus, &e);
+        }
         default: return false;
     }
+}
+
+// Producers P and consumers share the CUs/8 workgroups of a group.  Every panel of 256 rows
+// needs NCT = ceil(N2/256) consumers; PG panels are in flight per group.
+bool exchange_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, int64_t N2, int cus, ExchangeGeometry* e) {
+    (void)M;
+    const int bhp = gated ? 128 : 256;
+    e->wgs_per_group = cus / 8;
+    e->NCT = (int)((N2 + 255) / 256);
+    e->NH = (int)((N1 + bhp - 1) / bhp);
+    e->P = p.producers > 0 ? p.producers : e->wgs_per_group / 2;
+    e->R = p.ring > 0 ? p.ring : kExchangeMaxRing;
+    if (e->wgs_per_group < 2 || e->P < 1 || e->P >= e->wgs_per_group || p.coherent < 0 || p.coherent > 1) return false;
+    e->PG = (e->wgs_per_group - e->P) / e->NCT;
+    if (e->PG < 1) return false;
+    if (e->R < 2 * e->PG + 2 || e->R > kExchangeMaxRing || 16 * e->R + 4 > (int)(kExchangeFlagBytes / 4)) return false;
+    e->ws_bytes = kExchangeFlagBytes + (size_t)8 * e->R * 256 * bhp * 2;
+    return true;
 }
 
 bool fused_reduce_tile_ok(int gated, int bm, int bh) {
@@ -91,6 +115,29 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         t->lds_used = std::max(2.0 * (bm * 128.0 + g * bh * 128.0), 2.0 * (bh >= 128 ? 2.0 : 1.0) * 128.0 * 128.0);
         t->acc_regs = g * (bh / 32.0) * (bm / 128.0) * 16.0;
         t->feasible = t->lds_used <= d.lds_bytes && t->acc_regs <= d.acc_regs;
+    } else if (p.family == FFUSE_FAMILY_EXCHANGE) {
+        ExchangeGeometry x;
+        t->feasible = exchange_geometry(p, gated, M, N1, N2, d.cus, &x) ? 1 : 0;
+        if (t->feasible) {
+            const double bhp = gated ? 128.0 : 256.0;
+            const double NP = cdiv(m, 256), NG = cdiv(NP, x.PG), gx = cdiv(NG, 8);
+            const double f_cu = d.mfma_flops / d.cus;
+            const double tp = 2.0 * 256 * bhp * g * k / f_cu, tc = 2.0 * 256 * 256 * bhp / f_cu;
+            // per group: producers share gx*NH*PG tiles; every consumer multiplies gx*NH items;
+            // the consumers start one producer tile late
+            const double Tp = cdiv(gx * x.NH * x.PG, x.P) * tp, Tc = gx * x.NH * tc;
+            padded = (std::max(Tp, Tc) + tp) * d.mfma_flops;   // expressed as chip-time x chip-rate
+            t->workgroups = 8 * x.wgs_per_group;
+            t->l2_bytes = NP * x.NH * e * (256 * k + g * k * bhp) + NP * x.NCT * e * (256 * n1 + n1 * 256);
+            // every group streams all weights once per set of PG panels; X and Y once
+            t->fabric_bytes = NG * e * (g * k * n1 + n1 * n2) + e * m * k + e * m * n2;
+            t->lds_bytes = NP * x.NH * 4.0 * 1024.0 * (k / 16.0) * (g * bhp / 64.0 + 4.0) +
+                           NP * x.NCT * 4.0 * 1024.0 * (n1 / 16.0) * 8.0;
+            t->exchange_bytes = e * m * n1 * (1.0 + x.NCT);   // written once, read by NCT consumers (L2)
+            t->hbm_bytes = t->q_min;
+            t->lds_used = 2.0 * (256 * 128.0 + 256 * 128.0);
+            t->acc_regs = 256;
+        }
     } else if (p.family == FFUSE_FAMILY_UNFUSED) {
         const double bm = 256.0, bh0 = gated ? 128.0 : 256.0, bh1 = 256.0;
         const double u0 = cdiv(m, bm) * cdiv(n1, bh0), u1 = cdiv(m, bm) * cdiv(n2, bh1);
@@ -115,7 +162,7 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         t->hbm_bytes = t->q_min;
         t->lds_bytes = t->flops * 2.0;
     }
-    t->t_mfma = padded * waves / mfma_flops;
+    t->t_mfma = padded * waves / (mfma_flops * (p.family == FFUSE_FAMILY_SCALAR ? 1.0 : d.mfma_eff));
     t->t_hbm = t->hbm_bytes / d.hbm_bw;
     t->t_fabric = t->fabric_bytes / d.fabric_bw;
     t->t_l2 = t->l2_bytes / d.l2_bw;
@@ -160,6 +207,18 @@ void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1
             if (!t.feasible) continue;
             if (t.t_pred < best_t) { best_t = t.t_pred; best = p; }
         }
+    }
+    static const int producers[] = {8, 12, 16, 20, 24};
+    for (int pr : producers) {
+        ffuse_plan_t p;
+        std::memset(&p, 0, sizeof(p));
+        p.family = FFUSE_FAMILY_EXCHANGE;
+        p.bm = 256; p.bh = gated ? 128 : 256; p.bn2 = 256; p.bk = 64; p.h_level = 2; p.raster = 1; p.splits = 1;
+        p.producers = pr; p.ring = kExchangeMaxRing;
+        ffuse_traffic_t t;
+        traffic_model(p, dtype, gated, M, K, N1, N2, &t);
+        if (!t.feasible) continue;
+        if (t.t_pred < best_t) { best_t = t.t_pred; best = p; }
     }
     *out = best;
 }

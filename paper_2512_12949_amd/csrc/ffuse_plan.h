@@ -1,5 +1,6 @@
 // Host-side plan chooser / traffic model interface (no device code, no torch types).
 #pragma once
+#include <stddef.h>
 #include <stdint.h>
 
 #include "../../include/ffuse.h"
@@ -17,9 +18,20 @@ struct Device {
     double lds_bytes;    // per workgroup
     double acc_regs;     // accumulator registers per lane at one wave per SIMD
     double l2_bytes, mall_bytes;
+    double mfma_eff;     // fraction of mfma_flops the library's main loop sustains
     double launch_s;     // fixed cost of one kernel launch
 };
 extern const Device kDevice;
+
+// Exchange family: derived launch geometry of a plan for one problem.
+constexpr size_t kExchangeFlagBytes = 8192;
+constexpr int kExchangeMaxRing = 64;
+struct ExchangeGeometry {
+    int wgs_per_group;  // workgroups per XCD group = CUs / 8
+    int P, NCT, PG, R, NH;
+    size_t ws_bytes;    // flags + ring
+};
+bool exchange_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, int64_t N2, int cus, ExchangeGeometry* out);
 
 bool fused_reduce_tile_ok(int gated, int bm, int bh);
 bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2);

@@ -53,6 +53,7 @@ def run(w, dev, unfused=False, plan=None):
     try:
         fn = (ff.UNFUSED if unfused else ff.FUSED)[w.dtype]
         fn(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y)
+        ff.ffuse_sync_status()
         torch.cuda.synchronize()
     finally:
         ff.ffuse_force_plan(None)

@@ -47,7 +47,11 @@ def test_argument_validation_happens_before_any_device_work():
 
 
 def test_workspace_size_formula():
-    assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 4096, 4096, 16384, 4096, False) == 4 * 4096 * 4096
+    # fused: the larger of the fp32 sums (reduce family) and flags + 8 rings of 64 slots (exchange family)
+    ring = 8192 + 8 * 64 * 256 * 256 * 2
+    assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 4096, 4096, 16384, 4096, False) == max(4 * 4096 * 4096, ring)
+    assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 32768, 1024, 8192, 1024, False) == 4 * 32768 * 1024
+    assert ff.ffuse_workspace_bytes(ff.DT_BF16, True, 64, 64, 64, 64, False) == 8192 + 8 * 64 * 256 * 128 * 2
     assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 4096, 4096, 16384, 4096, True) == 2 * 4096 * 16384
     assert ff.ffuse_workspace_bytes(ff.DT_F32, False, 128, 256, 1024, 256, True) == 4 * 128 * 1024
     assert ff.ffuse_workspace_bytes(ff.DT_F32, False, 128, 256, 1024, 256, False) == 0

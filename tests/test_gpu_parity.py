@@ -55,6 +55,26 @@ def test_every_reduce_tile_on_a_ragged_shape(dtype, gated):
     gu.check(gu.run(w, dev, unfused=True), ref, dtype, what="unfused")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("gated", [False, True])
+def test_exchange_family_on_ragged_shapes(dtype, gated):
+    """Producer/consumer ring kernel: ragged last panel, hidden tail, several panel groups,
+    several producer counts and a ring small enough to wrap many times."""
+    act = ACT_SILU if gated else ACT_GELU_TANH
+    cases = [((600, 200, 840, 520), ((16, 32), (8, 20), (24, 8))),
+             ((2300, 136, 392, 264), ((16, 32), (8, 28), (24, 12)))]
+    for (M, K, N1, N2), settings in cases:
+        w, host, dev = _case("exch", M, K, N1, N2, dtype, act, gated)
+        ref = gu.oracle_rows(w, host)
+        for producers, ring in settings:
+            plan = ff.make_plan(ff.FAMILY_EXCHANGE, 256, 128 if gated else 256, bn2=256, producers=producers, ring=ring)
+            print(f"exchange {dtype} gated={gated} shape {(M, K, N1, N2)} P={producers} R={ring}", flush=True)
+            gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"exchange P={producers} R={ring}")
+        # the placement-independent protocol (agent-scope release/acquire)
+        plan = ff.make_plan(ff.FAMILY_EXCHANGE, 256, 128 if gated else 256, bn2=256, producers=16, ring=32, coherent=1)
+        gu.check(gu.run(w, dev, plan=plan), ref, dtype, what="exchange coherent")
+
+
 @pytest.mark.parametrize("act", [ACT_RELU, ACT_GELU_TANH, ACT_SILU, ACT_IDENTITY])
 @pytest.mark.parametrize("gated", [False, True])
 def test_activations_medium(act, gated):
