@@ -145,10 +145,11 @@ def main():
                                "sample": f"{len(rows)} of {w.M} rows, all {w.N2} columns, {t_cpu:.1f} s"}
         out["max_rel_err_vs_oracle"] = rel
     if args.copy_calibration:
+        # one plain elementwise copy kernel of known size: reads 256 MiB, writes 256 MiB
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        dst.copy_(src)
+        torch.mul(src, 1.0, out=dst)
         torch.cuda.synchronize()
     ff.ffuse_set_workspace(None)
     print(json.dumps(out))
