@@ -33,7 +33,7 @@ def main():
     ap.add_argument("--workload", default="gpt")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--oracle-rows", type=int, default=0, help="rows of the CPU-baseline sample (0 = auto)")
-    ap.add_argument("--plan", default="", help="force a plan: family,bm,bh[,raster]")
+    ap.add_argument("--plan", default="", help="force a plan: family,bm,bh[,raster[,splits[,producers[,ring]]]]")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -68,7 +68,9 @@ def main():
     Y = torch.empty((w.M, w.N2), dtype=tdt, device="cuda")
     if args.plan:
         v = [int(x) for x in args.plan.split(",")]
-        ff.ffuse_force_plan(ff.make_plan(v[0], v[1], v[2], raster=v[3] if len(v) > 3 else 4))
+        v += [0] * (7 - len(v))
+        ff.ffuse_force_plan(ff.make_plan(v[0], v[1], v[2], bn2=256 if v[0] == 2 else 128, raster=v[3] or 4, splits=v[4],
+                                         producers=v[5], ring=v[6]))
     fused, unfused = ff.FUSED[w.dtype], ff.UNFUSED[w.dtype]
 
     def step(fn):

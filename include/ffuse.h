@@ -78,7 +78,11 @@ typedef enum {
                                  L2-resident buffer and consume each other's tiles
                                  (Sec. 4.1 "shuffle" strategy, exchange through L2)         */
     FFUSE_FAMILY_UNFUSED = 3, /* two GEMM launches, intermediate in the workspace          */
-    FFUSE_FAMILY_SCALAR = 4   /* fp32 debug kernels (plain FMA, no matrix cores)            */
+    FFUSE_FAMILY_SCALAR = 4,  /* fp32 debug kernels (plain FMA, no matrix cores)            */
+    FFUSE_FAMILY_TWOPHASE = 5 /* small M: every CU computes hidden slices of the intermediate
+                                 into an L2 / Infinity-Cache resident buffer, one device-wide
+                                 barrier, then every CU multiplies it with a block of W2;
+                                 `splits` partial products per output are summed by atomics */
 } ffuse_family_t;
 
 typedef struct {

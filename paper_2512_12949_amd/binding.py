@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libffuse.so")
 
 ACT_IDENTITY, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 DT_BF16, DT_F16, DT_F32 = 0, 1, 2
-FAMILY_AUTO, FAMILY_REDUCE, FAMILY_EXCHANGE, FAMILY_UNFUSED, FAMILY_SCALAR = 0, 1, 2, 3, 4
+FAMILY_AUTO, FAMILY_REDUCE, FAMILY_EXCHANGE, FAMILY_UNFUSED, FAMILY_SCALAR, FAMILY_TWOPHASE = 0, 1, 2, 3, 4, 5
 DTYPE_CODE = {"bf16": DT_BF16, "f16": DT_F16, "f32": DT_F32}
 
 EXPORTS = [

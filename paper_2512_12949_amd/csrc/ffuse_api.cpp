@@ -19,7 +19,8 @@ struct State {
     std::mutex mu;
     void* ws = nullptr;
     size_t ws_bytes = 0;
-    bool ws_dirty = false;   // the fp32 sums region may hold non-zero data
+    size_t ws_zero = 0;      // bytes at the start of the workspace known to be zero
+    uint32_t* small_flags = nullptr;  // where the small-M family last left clean barrier flags
     bool forced = false;
     ffuse_plan_t forced_plan{};
     ffuse_plan_t last_plan{};
@@ -32,6 +33,7 @@ struct State {
     bool log = std::getenv("FFUSE_LOG") != nullptr;  // diagnostics on stderr
     uint64_t* exch_stats = nullptr;
     uint64_t* gemm_stats = nullptr;
+    uint64_t* small_stats = nullptr;
     int exch_wgs = 0;
 };
 State g;
@@ -78,6 +80,14 @@ void read_env_plan() {
         g.forced_plan.producers = v[8]; g.forced_plan.ring = v[9]; g.forced_plan.coherent = v[10];
         g.forced = true;
     }
+}
+
+// makes the first `need` bytes of the workspace zero (they usually already are)
+bool ensure_zero(size_t need, hipStream_t st) {
+    if (g.ws_zero >= need) return true;
+    if (ffuse::launch_zero(g.ws, (need + 15) & ~(size_t)15, st) != hipSuccess) return false;
+    g.ws_zero = need;
+    return true;
 }
 
 struct Timer {  // brackets the dominant kernel with events when profiling is on
@@ -127,7 +137,8 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
         if (!g.ws || g.ws_bytes < e.ws_bytes) return FFUSE_ERR_WORKSPACE;
         char* base = reinterpret_cast<char*>(g.ws);
         if (ffuse::launch_zero(base, ffuse::kExchangeFlagBytes, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
-        g.ws_dirty = true;  // the ring overwrites the region the reduce family keeps at zero
+        g.ws_zero = 0;      // the ring overwrites the region the other families keep at zero
+        g.small_flags = nullptr;
         ffuse::ExchangeArgs x{X, W1, W3, W2, Y, base + ffuse::kExchangeFlagBytes, reinterpret_cast<uint32_t*>(base),
                               M, (int)K, (int)N1, (int)N2, act, e.P, e.NCT, e.PG, e.R, e.NH, plan.coherent, nullptr};
         if (g.log && g.ws_bytes >= e.ws_bytes + 8192 * 4) {
@@ -143,13 +154,37 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
         g.last_plan = plan;
         return FFUSE_OK;
     }
+    if (plan.family == FFUSE_FAMILY_TWOPHASE) {
+        ffuse::SmallMGeometry sg;
+        if (!ffuse::small_m_geometry(plan, M, N1, N2, &sg)) return FFUSE_ERR_PLAN;
+        if (!g.ws || g.ws_bytes < sg.ws_bytes) return FFUSE_ERR_WORKSPACE;
+        char* base = reinterpret_cast<char*>(g.ws);
+        uint32_t* flags = reinterpret_cast<uint32_t*>(base + sg.ysum_bytes + sg.h_bytes);
+        if (g.small_flags != flags) {
+            if (ffuse::launch_zero(flags, 256, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+            g.small_flags = flags;
+        }
+        g.ws_zero = 0;      // the partial-sum planes overwrite the region the reduce family keeps at zero
+        ffuse::SmallMArgs s{X, W1, W3, W2, base + sg.ysum_bytes, reinterpret_cast<float*>(base), flags,
+                            M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, nullptr};
+        if (g.log && g.ws_bytes >= sg.ws_bytes + 32768) {
+            s.stats = reinterpret_cast<uint64_t*>(base + sg.ws_bytes);
+            g.small_stats = s.stats;
+        }
+        g.exch_err = flags + 2;
+        {
+            Timer t(st);
+            if (ffuse::launch_fused_small_m(dtype, s, sg.bm, g.cus, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+            t.stop();
+        }
+        if (ffuse::launch_finalize_planes(dtype, s.part, Y, M * N2, sg.splits, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+        g.last_plan = plan;
+        return FFUSE_OK;
+    }
     if (plan.family != FFUSE_FAMILY_REDUCE) return FFUSE_ERR_PLAN;
     const size_t need = sizeof(float) * (size_t)M * (size_t)N2;
     if (!g.ws || g.ws_bytes < need) return FFUSE_ERR_WORKSPACE;
-    if (g.ws_dirty) {
-        if (ffuse::launch_zero(g.ws, g.ws_bytes, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
-        g.ws_dirty = false;
-    }
+    if (!ensure_zero(need, st)) return FFUSE_ERR_LAUNCH;
     a.Ysum = reinterpret_cast<float*>(g.ws);
     g.exch_err = nullptr;
     {
@@ -174,7 +209,8 @@ int run_unfused(int dtype, const void* X, const void* W1, const void* W3, const 
     const size_t need = (size_t)elem * (size_t)M * (size_t)N1;
     if (!g.ws || g.ws_bytes < need) return FFUSE_ERR_WORKSPACE;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    g.ws_dirty = true;  // H overwrites whatever the fused path kept at zero
+    g.ws_zero = 0;      // H overwrites whatever the fused path kept at zero
+    g.small_flags = nullptr;
     g.exch_err = nullptr;
     ffuse::GemmArgs g0{X, W1, W3, g.ws, M, (int)K, (int)N1, act, 4, nullptr};
     ffuse::GemmArgs g1{g.ws, W2, nullptr, Y, M, (int)N1, (int)N2, FFUSE_ACT_IDENTITY, 4, nullptr};
@@ -231,6 +267,10 @@ size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t
         // room for the exchange family's flags + ring at its largest ring setting
         const size_t ex = ffuse::kExchangeFlagBytes + (size_t)8 * ffuse::kExchangeMaxRing * 256 * (gated ? 128 : 256) * 2;
         if (ex > b) b = ex;
+        if (M <= 128) {   // two-phase small-M family: sums | H | flags
+            const size_t sm = (((size_t)4 * M * N2 * 32 + 255) & ~(size_t)255) + (((size_t)2 * M * N1 + 255) & ~(size_t)255) + 256;  // up to 32 planes
+            if (sm > b) b = sm;
+        }
     }
     return (b + 255) & ~(size_t)255;
 }
@@ -238,13 +278,13 @@ size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t
 int ffuse_set_workspace(void* dev_ptr, size_t bytes, void* stream) {
     std::lock_guard<std::mutex> lock(g.mu);
     if (!dev_ptr) {
-        g.ws = nullptr; g.ws_bytes = 0; g.ws_dirty = false; g.exch_err = nullptr;
+        g.ws = nullptr; g.ws_bytes = 0; g.ws_zero = 0; g.small_flags = nullptr; g.exch_err = nullptr;
         return FFUSE_OK;
     }
     if (!aligned16(dev_ptr)) return FFUSE_ERR_ALIGN;
     if (bytes % 16) return FFUSE_ERR_SHAPE;
     if (ffuse::launch_zero(dev_ptr, bytes, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return FFUSE_ERR_LAUNCH;
-    g.ws = dev_ptr; g.ws_bytes = bytes; g.ws_dirty = false; g.exch_err = nullptr;
+    g.ws = dev_ptr; g.ws_bytes = bytes; g.ws_zero = bytes; g.small_flags = nullptr; g.exch_err = nullptr;
     return FFUSE_OK;
 }
 
@@ -285,6 +325,19 @@ int ffuse_last_plan(ffuse_plan_t* out) {
 int ffuse_sync_status(void* stream) {
     if (hipStreamSynchronize(reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return FFUSE_ERR_LAUNCH;
     std::lock_guard<std::mutex> lock(g.mu);
+    if (g.log && g.small_stats) {
+        std::vector<uint64_t> h(4 * 1024);
+        if (hipMemcpy(h.data(), g.small_stats, h.size() * 8, hipMemcpyDeviceToHost) == hipSuccess) {
+            double p1 = 0, b = 0, p2 = 0, m1 = 0, m2 = 0; int n = 0;
+            for (int i = 0; i < g.cus && i < 1024; ++i) {
+                p1 += h[4 * i]; b += h[4 * i + 1]; p2 += h[4 * i + 2]; ++n;
+                m1 = std::max(m1, (double)h[4 * i]); m2 = std::max(m2, (double)h[4 * i + 2]);
+            }
+            std::fprintf(stderr, "[ffuse] small-M: phase 1 avg %.1f us (max %.1f), barrier wait avg %.1f us, phase 2 avg %.1f us (max %.1f)\n",
+                         p1 / n * 0.01, m1 * 0.01, b / n * 0.01, p2 / n * 0.01, m2 * 0.01);
+        }
+        g.small_stats = nullptr;
+    }
     if (g.log && g.gemm_stats) {
         std::vector<uint64_t> h(8 * 16384);
         if (hipMemcpy(h.data(), g.gemm_stats, h.size() * 8, hipMemcpyDeviceToHost) == hipSuccess) {

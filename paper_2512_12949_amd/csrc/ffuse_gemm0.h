@@ -235,7 +235,7 @@ struct FirstGemm {
                     // first half of the MFMAs: transpose + store the 8*WPT columns of the old
                     // B block(s); second half: refill the same registers (every column needs
                     // all 8 old rows, so no row may be overwritten before the last store)
-                    constexpr int H1 = (NM + 1) / 2, H2 = NM - H1;
+                    constexpr int H1 = (NM + 1) / 2, H2 = NM - H1;   // H2 == 0 only when NM == 1
                     if (i < H1) {
 #pragma unroll
                         for (int e = (i * 8 * WPT) / H1; e < ((i + 1) * 8 * WPT) / H1; ++e) {
@@ -252,6 +252,14 @@ struct FirstGemm {
                         const int i2 = i - H1;
 #pragma unroll
                         for (int e = (i2 * 8 * WPT) / (H2 > 0 ? H2 : 1); e < ((i2 + 1) * 8 * WPT) / (H2 > 0 ? H2 : 1); ++e) {
+                            const int q = e / 8, r = e % 8;
+                            const uint32_t base = c.woff[q];
+                            st.w[q][r] = buf_load16(c.rw[q], (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow);
+                        }
+                    }
+                    if (H2 == 0 && i == NM - 1) {   // a single MFMA per sub-step: refill right after the stores
+#pragma unroll
+                        for (int e = 0; e < 8 * WPT; ++e) {
                             const int q = e / 8, r = e % 8;
                             const uint32_t base = c.woff[q];
                             st.w[q][r] = buf_load16(c.rw[q], (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow);
@@ -277,29 +285,56 @@ struct FirstGemm {
             }
     }
 
-    // Whole K loop over k = 0 .. K-1 (A columns and B rows advance together).  On return
-    // acc[ht][mt][r] holds (A*B)[m][n] with
+    // K loop over k = kbegin .. kend-1 (A columns and B rows advance together; kend - kbegin is
+    // rounded up to whole steps of 64, so a range that is not the tail of the operands must
+    // be a multiple of 64).  On return acc[ht][mt][r] holds the partial (A*B)[m][n] with
     //   m = row0 + wm*WMR + 32*mt + lane%32,
     //   n = n0 + wn*WHR + 32*ht + 8*(r/4) + 4*(lane/32) + r%4,
-    // acc3 the same for B3.  Loads past K return zeros (buffer range check), so the
-    // prefetch needs no tail branch.  Ends with a barrier: LDS may be reused by the caller.
-    static __device__ __forceinline__ void run(char* smem, const Ctx& c, int K, f32x16 (&acc)[HT][MT],
+    // acc3 the same for B3.  Loads past the operands return zeros (buffer range check), so
+    // the prefetch needs no tail branch.  Ends with a barrier: LDS may be reused by the caller.
+    static __device__ __forceinline__ void run(char* smem, const Ctx& c, int kbegin, int kend, f32x16 (&acc)[HT][MT],
                                                f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1], int tid,
                                                uint64_t* t_loop = nullptr) {
         zero(acc, acc3);
-        const int KT = (K + 63) / 64;
+        const int KT = (kend - kbegin + 63) / 64;
         Stage st;
-        gload(c, st, 0, 0);
+        gload(c, st, kbegin, kbegin);
         store_a(smem, st, tid);
         store_b(smem, st, tid);
-        gload(c, st, 64, 64);
+        gload(c, st, kbegin + 64, kbegin + 64);
         __syncthreads();
         if (t_loop) *t_loop = wall_clock64();
         for (int kt = 0; kt < KT; ++kt) {
             char* cur = smem + (kt & 1) * STAGE;
             char* nxt = smem + ((kt + 1) & 1) * STAGE;
-            step(cur, nxt, c, st, (kt + 2) * 64, (kt + 2) * 64, acc, acc3, tid);
+            const int k2 = kbegin + (kt + 2) * 64;
+            step(cur, nxt, c, st, k2, k2, acc, acc3, tid);
             __syncthreads();
+        }
+    }
+
+    // Same K loop with TWO register stages, i.e. prefetch distance three steps: every global
+    // load has two whole steps to land before it is written to LDS, which doubles the bytes in
+    // flight per CU.  For the bandwidth-bound small-M kernels, whose accumulators are small.
+    static __device__ __forceinline__ void run_deep(char* smem, const Ctx& c, int kbegin, int kend, f32x16 (&acc)[HT][MT],
+                                                    f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1], int tid) {
+        zero(acc, acc3);
+        const int KT = (kend - kbegin + 63) / 64;
+        Stage sa, sb;
+        gload(c, sa, kbegin, kbegin);
+        store_a(smem, sa, tid);
+        store_b(smem, sa, tid);
+        gload(c, sa, kbegin + 64, kbegin + 64);
+        gload(c, sb, kbegin + 128, kbegin + 128);
+        __syncthreads();
+        for (int kt = 0; kt < KT; kt += 2) {
+            const int k3 = kbegin + (kt + 3) * 64;
+            step(smem, smem + STAGE, c, sa, k3, k3, acc, acc3, tid);          // multiplies step kt, stores kt+1, loads kt+3
+            __syncthreads();
+            if (kt + 1 < KT) {
+                step(smem + STAGE, smem, c, sb, k3 + 64, k3 + 64, acc, acc3, tid);  // step kt+1, stores kt+2, loads kt+4
+                __syncthreads();
+            }
         }
     }
 

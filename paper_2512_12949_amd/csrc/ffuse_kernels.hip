@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void fused_reduce_kernel(FusedArgs a) {
         G0::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)m0, (uint32_t)a.K, a.K, tid);
         G0::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1, (uint32_t)n0, tid);
         G0::init_lds(c, tid);
-        G0::run(smem, c, a.K, acc, acc3, tid);
+        G0::run(smem, c, 0, a.K, acc, acc3, tid);
     }
 
     // ---- activation (and gate) on complete sums; round to the operand type.  Registers
@@ -233,7 +233,7 @@ __global__ __launch_bounds__(256) void gemm_act_kernel(GemmArgs a) {
     G0::init_lds(c, tid);
     uint64_t t0 = 0, t1 = 0, t2 = 0;
     if (a.stats) t0 = wall_clock64();
-    G0::run(smem, c, a.K, acc, acc3, tid, a.stats ? &t1 : nullptr);
+    G0::run(smem, c, 0, a.K, acc, acc3, tid, a.stats ? &t1 : nullptr);
     if (a.stats) t2 = wall_clock64();
     G0::store_tile_rt(a.act, acc, acc3, reinterpret_cast<char*>(a.C), a.N, m0, n0, a.M, a.N, tid);
     if (a.stats && tid == 0) {
@@ -367,7 +367,7 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
                 GP::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)panel * 256u, (uint32_t)a.K, a.K, tid);
                 GP::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1,
                            (uint32_t)hh * BHP, tid);
-                GP::run(smem, c, a.K, acc, acc3, tid);
+                GP::run(smem, c, 0, a.K, acc, acc3, tid);
                 GP::store_tile_rt(a.act, acc, acc3, ring + (size_t)slot * SLOT_BYTES, BHP, 0, 0, 256, BHP, tid);
             }
             stores_done();     // this thread's tile stores have reached L2
@@ -503,7 +503,7 @@ hipError_t launch_fused_exchange(int dtype, const ExchangeArgs& a, int wgs_per_g
     else fn = g ? (const void*)fused_exchange_kernel<_Float16, true> : (const void*)fused_exchange_kernel<_Float16, false>;
     ExchangeArgs copy = a;
     void* params[] = {&copy};
-    return hipLaunchCooperativeKernel(fn, dim3(8 * wgs_per_group), dim3(256), params, 0, st);
+    return launch_resident(fn, 8 * wgs_per_group, params, st);
 }
 
 }  // namespace ffuse

@@ -5,6 +5,8 @@
 #include "ffuse_dev.h"
 #include "ffuse_launch.h"
 
+#include <cstdlib>
+
 namespace ffuse {
 
 static __device__ __forceinline__ float act_f32(int act, float x) {
@@ -120,6 +122,18 @@ hipError_t launch_zero(void* p, size_t bytes, hipStream_t st) {
     const int blocks = (int)(want < 4096 ? want : 4096);
     hipLaunchKernelGGL(zero_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<u32x4*>(p), n16);
     return hipGetLastError();
+}
+
+hipError_t launch_resident(const void* fn, int grid, void** params, hipStream_t st) {
+    static const bool cooperative = getenv("FFUSE_COOPERATIVE_LAUNCH") != nullptr;
+    if (cooperative) return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, st);
+    int per_cu = 0, dev = 0, cus = 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, 0);
+    if (e != hipSuccess) return e;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    if (grid > per_cu * cus) return hipErrorCooperativeLaunchTooLarge;
+    return hipLaunchKernel(fn, dim3(grid), dim3(256), params, 0, st);
 }
 
 hipError_t launch_fused_f32(const FusedArgs& a, float* Y, hipStream_t st) {

@@ -50,11 +50,37 @@ struct ExchangeArgs {
     uint64_t* stats;  // nullptr, or 4 words per workgroup: role, total ticks, waiting ticks, items
 };
 
+struct SmallMArgs {
+    const void* X;
+    const void* W1;
+    const void* W3;   // nullptr: not gated
+    const void* W2;
+    void* H;          // [M][N1] intermediate in the operand type (L2 / Infinity Cache resident)
+    float* part;      // fp32 partial sums [splits][M][N2], fully overwritten
+    uint32_t* flags;  // [0] barrier arrivals, [1] exits, [2] error; [0..1] zero on entry and on exit
+    int64_t M;
+    int K, N1, N2;
+    int act;
+    int splits;       // ranges of the hidden dimension summed per output element
+    int ksplit;       // hidden columns per range (multiple of 64)
+    uint64_t* stats;  // nullptr, or 4 words per workgroup: ticks of phase 1, barrier, phase 2
+};
+
 // 16-bit paths (dtype 0 = bf16, 1 = fp16)
+hipError_t launch_fused_small_m(int dtype, const SmallMArgs& a, int bm, int grid, hipStream_t st);
+hipError_t launch_finalize_planes(int dtype, const float* part, void* Y, int64_t count, int planes, hipStream_t st);
 hipError_t launch_fused_exchange(int dtype, const ExchangeArgs& a, int wgs_per_group, hipStream_t st);
 hipError_t launch_fused_reduce(int dtype, const FusedArgs& a, int bm, int bh, hipStream_t st);
 hipError_t launch_finalize(int dtype, float* sums, void* Y, int64_t count, hipStream_t st);
 hipError_t launch_gemm_act(int dtype, const GemmArgs& a, hipStream_t st);
+
+// Launch of a persistent kernel whose workgroups wait for each other: every workgroup must
+// be resident at once.  The grid is checked against the occupancy the runtime reports
+// (hipErrorCooperativeLaunchTooLarge otherwise) and then launched as an ordinary kernel,
+// which costs ~17 us less per call than hipLaunchCooperativeKernel; all in-kernel waits are
+// bounded, so foreign work occupying compute units surfaces as FFUSE_ERR_TIMEOUT, not as a
+// hang.  FFUSE_COOPERATIVE_LAUNCH=1 selects the runtime's cooperative launch instead.
+hipError_t launch_resident(const void* fn, int grid, void** params, hipStream_t st);
 
 // zero fill with a kernel (safe to record into a captured graph, unlike a memset node);
 // bytes must be a multiple of 16

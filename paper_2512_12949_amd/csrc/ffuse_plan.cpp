@@ -46,6 +46,11 @@ bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t 
         case FFUSE_FAMILY_REDUCE:
             if (dtype == FFUSE_DT_F32) return false;
             return fused_reduce_tile_ok(gated, p.bm, p.bh) && p.raster >= 1;
+        case FFUSE_FAMILY_TWOPHASE: {
+            if (dtype == FFUSE_DT_F32) return false;
+            SmallMGeometry sg;
+            return small_m_geometry(p, M, N1, N2, &sg);
+        }
         case FFUSE_FAMILY_EXCHANGE: {
             if (dtype == FFUSE_DT_F32) return false;
             ExchangeGeometry e;
@@ -70,6 +75,19 @@ bool exchange_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, 
     if (e->PG < 1) return false;
     if (e->R < 2 * e->PG + 2 || e->R > kExchangeMaxRing || 16 * e->R + 4 > (int)(kExchangeFlagBytes / 4)) return false;
     e->ws_bytes = kExchangeFlagBytes + (size_t)8 * e->R * 256 * bhp * 2;
+    return true;
+}
+
+bool small_m_geometry(const ffuse_plan_t& p, int64_t M, int64_t N1, int64_t N2, SmallMGeometry* g) {
+    if (M > 128) return false;
+    g->bm = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
+    int splits = p.splits > 0 ? p.splits : 8;
+    if (splits > 32) return false;
+    g->ksplit = (int)(((N1 + splits - 1) / splits + 63) / 64 * 64);
+    g->splits = (int)((N1 + g->ksplit - 1) / g->ksplit);
+    g->ysum_bytes = ((size_t)4 * M * N2 * g->splits + 255) & ~(size_t)255;
+    g->h_bytes = ((size_t)2 * M * N1 + 255) & ~(size_t)255;
+    g->ws_bytes = g->ysum_bytes + g->h_bytes + 256;
     return true;
 }
 
@@ -115,6 +133,25 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         t->lds_used = std::max(2.0 * (bm * 128.0 + g * bh * 128.0), 2.0 * (bh >= 128 ? 2.0 : 1.0) * 128.0 * 128.0);
         t->acc_regs = g * (bh / 32.0) * (bm / 128.0) * 16.0;
         t->feasible = t->lds_used <= d.lds_bytes && t->acc_regs <= d.acc_regs;
+    } else if (p.family == FFUSE_FAMILY_TWOPHASE) {
+        SmallMGeometry sg;
+        t->feasible = small_m_geometry(p, M, N1, N2, &sg) ? 1 : 0;
+        if (t->feasible) {
+            const double bh1 = gated ? 128.0 : 256.0;
+            const double bm = sg.bm, ns = cdiv(n1, bh1), items = cdiv(n2, 256) * sg.splits;
+            t->workgroups = d.cus;
+            // small tiles keep the matrix cores mostly idle: a few MFMAs per 64-deep step
+            padded = (ns * 2.0 * bm * bh1 * g * k + items * 2.0 * bm * 256 * sg.ksplit) / 0.25;
+            waves = std::max(cdiv(ns, d.cus) * d.cus / ns, cdiv(items, d.cus) * d.cus / items);
+            t->l2_bytes = ns * e * (bm * k + g * k * bh1) + items * e * (bm * sg.ksplit + sg.ksplit * 256.0);
+            t->fabric_bytes = t->q_min + 8.0 * e * (m * k + m * n1);   // X and H fill each XCD's L2 once
+            t->lds_bytes = t->l2_bytes * 2.0;
+            t->exchange_bytes = 2.0 * e * m * n1;
+            t->reduce_bytes = 4.0 * m * n2 * sg.splits;
+            t->hbm_bytes = t->q_min;
+            t->lds_used = 2.0 * (bm * 128.0 + 256 * 128.0);
+            t->acc_regs = 2.0 * (bm / 32.0) * 16.0;
+        }
     } else if (p.family == FFUSE_FAMILY_EXCHANGE) {
         ExchangeGeometry x;
         t->feasible = exchange_geometry(p, gated, M, N1, N2, d.cus, &x) ? 1 : 0;
@@ -162,18 +199,43 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         t->hbm_bytes = t->q_min;
         t->lds_bytes = t->flops * 2.0;
     }
-    t->t_mfma = padded * waves / (mfma_flops * (p.family == FFUSE_FAMILY_SCALAR ? 1.0 : d.mfma_eff));
+    // the reduce family's 4x1 wave layout and 128-row tiles run the matrix cores at ~2/3 of the
+    // 256x256 main loop's efficiency (measured on the m = 128 shapes)
+    const double eff = p.family == FFUSE_FAMILY_SCALAR ? 1.0 : (p.family == FFUSE_FAMILY_REDUCE ? 0.67 * d.mfma_eff : d.mfma_eff);
+    t->t_mfma = padded * waves / (mfma_flops * eff);
     t->t_hbm = t->hbm_bytes / d.hbm_bw;
     t->t_fabric = t->fabric_bytes / d.fabric_bw;
     t->t_l2 = t->l2_bytes / d.l2_bw;
     t->t_lds = t->lds_bytes / d.lds_bw;
     t->t_reduce = t->reduce_bytes / d.atomic_bw;
     double worst = std::max({t->t_mfma, t->t_hbm, t->t_fabric, t->t_l2, t->t_lds});
-    // atomics of one unit are issued after its matrix work, so they add rather than overlap
-    // unless other units are still computing; model: half overlaps
-    worst = std::max(worst, t->t_reduce) + 0.5 * std::min(worst, t->t_reduce);
+    // atomics of one unit are issued after its matrix work: with a single round of units
+    // nothing overlaps them; with several rounds about half does
+    const double overlap = (t->workgroups <= d.cus) ? 0.0 : 0.5;
+    worst = std::max(worst, t->t_reduce) + (1.0 - overlap) * std::min(worst, t->t_reduce);
     const double launches = 2.0;  // main kernel + finalise / second GEMM / zero fill
     t->t_pred = worst + launches * d.launch_s;
+    if (p.family == FFUSE_FAMILY_TWOPHASE && t->feasible) {
+        // two streaming phases back to back.  A workgroup of this kernel keeps ~64 KB in flight
+        // and sustains ~25 GB/s on its own (measured), so a phase with few work items is
+        // bounded by items x 25 GB/s rather than by HBM; every item also pays ~3 us of
+        // pipeline fill and epilogue.  Fixed: launch, one device-wide barrier, finalize (~25 us).
+        SmallMGeometry sg;
+        small_m_geometry(p, M, N1, N2, &sg);
+        const double per_wg = 25e9, bh1 = gated ? 128.0 : 256.0;
+        const double n_s = cdiv(n1, bh1), items = cdiv(n2, 256) * sg.splits;
+        const double b1 = e * g * k * n1, b2 = e * n1 * n2;
+        const double t1 = b1 / std::min(d.hbm_bw, std::min(n_s, (double)d.cus) * per_wg) + 3e-6 * cdiv(n_s, d.cus);
+        const double t2 = b2 / std::min(d.hbm_bw, std::min(items, (double)d.cus) * per_wg) + 3e-6 * cdiv(items, d.cus);
+        const double planes = 2.0 * 4.0 * m * n2 * sg.splits / d.fabric_bw;
+        // matrix-core time of each phase: items run one per CU, at the main loop's efficiency
+        const double f_cu = d.mfma_flops * d.mfma_eff / d.cus;
+        const double m1 = 2.0 * sg.bm * bh1 * g * k / f_cu * cdiv(n_s, d.cus);
+        const double m2 = 2.0 * sg.bm * 256.0 * sg.ksplit / f_cu * cdiv(items, d.cus);
+        t->t_hbm = t1 + t2;
+        t->t_mfma = m1 + m2;
+        t->t_pred = std::max(t1, m1) + std::max(t2, m2) + planes + 25e-6;
+    }
 }
 
 // Enumerates the plans the kernels implement, discards infeasible ones and returns the one
@@ -202,6 +264,20 @@ void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1
             p.bm = tl[0]; p.bh = tl[1]; p.bn2 = 128; p.bk = 64; p.h_level = 0; p.raster = r;
             p.splits = (int)((N1 + p.bh - 1) / p.bh);
             if (r > 1 && r > (M + p.bm - 1) / p.bm) continue;
+            ffuse_traffic_t t;
+            traffic_model(p, dtype, gated, M, K, N1, N2, &t);
+            if (!t.feasible) continue;
+            if (t.t_pred < best_t) { best_t = t.t_pred; best = p; }
+        }
+    }
+    if (M <= 128) {
+        static const int splits[] = {2, 4, 8, 16, 32};
+        for (int sp : splits) {
+            ffuse_plan_t p;
+            std::memset(&p, 0, sizeof(p));
+            p.family = FFUSE_FAMILY_TWOPHASE;
+            p.bm = M <= 32 ? 32 : (M <= 64 ? 64 : 128); p.bh = 128; p.bn2 = 128; p.bk = 64; p.h_level = 2; p.raster = 1;
+            p.splits = sp;
             ffuse_traffic_t t;
             traffic_model(p, dtype, gated, M, K, N1, N2, &t);
             if (!t.feasible) continue;

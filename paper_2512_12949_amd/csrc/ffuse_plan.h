@@ -33,6 +33,14 @@ struct ExchangeGeometry {
 };
 bool exchange_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, int64_t N2, int cus, ExchangeGeometry* out);
 
+// Two-phase small-M family: derived geometry.
+struct SmallMGeometry {
+    int bm;             // padded rows: 32, 64 or 128
+    int splits, ksplit; // phase-2 ranges of the hidden dimension
+    size_t ysum_bytes, h_bytes, ws_bytes;   // workspace layout: partial-sum planes | H | 256 bytes of flags
+};
+bool small_m_geometry(const ffuse_plan_t& p, int64_t M, int64_t N1, int64_t N2, SmallMGeometry* out);
+
 bool fused_reduce_tile_ok(int gated, int bm, int bh);
 bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2);
 void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,

@@ -75,6 +75,24 @@ def test_exchange_family_on_ragged_shapes(dtype, gated):
         gu.check(gu.run(w, dev, plan=plan), ref, dtype, what="exchange coherent")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("gated", [False, True])
+def test_two_phase_small_m_family(dtype, gated):
+    """Small-M kernel: every row padding (32 / 64 / 128), ragged K / N1 / N2, several splits,
+    more hidden slices and output blocks than workgroups, and back-to-back launches that
+    rely on the kernel leaving its barrier flags clean."""
+    act = ACT_SILU if gated else ACT_GELU_TANH
+    for (M, K, N1, N2) in [(1, 72, 136, 72), (16, 200, 840, 264), (50, 136, 392, 520), (128, 64, 33000, 136),
+                           (7, 64, 256, 33000)]:
+        w, host, dev = _case("small", M, K, N1, N2, dtype, act, gated)
+        ref = gu.oracle_rows(w, host)
+        for splits in (1, 3, 8):
+            plan = ff.make_plan(ff.FAMILY_TWOPHASE, splits=splits)
+            print(f"two-phase {dtype} gated={gated} shape {(M, K, N1, N2)} splits={splits}", flush=True)
+            gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase splits={splits}")
+            gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase splits={splits} again")
+
+
 @pytest.mark.parametrize("act", [ACT_RELU, ACT_GELU_TANH, ACT_SILU, ACT_IDENTITY])
 @pytest.mark.parametrize("gated", [False, True])
 def test_activations_medium(act, gated):
