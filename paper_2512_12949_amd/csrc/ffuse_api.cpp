@@ -342,13 +342,13 @@ int ffuse_sync_status(void* stream) {
         std::vector<uint64_t> h(8 * 16384);
         if (hipMemcpy(h.data(), g.gemm_stats, h.size() * 8, hipMemcpyDeviceToHost) == hipSuccess) {
             for (int k = 0; k < 2; ++k) {
-                double p = 0, l = 0, e = 0, st = 0; int n = 0;
+                double p = 0, l = 0, e = 0, st = 0, lmax = 0; int n = 0;
                 for (int i = 0; i < 16384; ++i) {
                     const uint64_t* q = &h[(size_t)k * 4 * 16384 + 4 * i];
-                    if (q[3]) { p += q[0]; l += q[1]; e += q[2]; st += q[3]; ++n; }
+                    if (q[3]) { p += q[0]; l += q[1]; e += q[2]; st += q[3]; ++n; if ((double)q[1] > lmax) lmax = (double)q[1]; }
                 }
-                if (n) std::fprintf(stderr, "[ffuse] gemm %d: %d tiles, prologue %.2f us, loop %.2f us (%.3f us/step), epilogue %.2f us\n",
-                                    k, n, p / n * 0.01, l / n * 0.01, l / st * 0.01, e / n * 0.01);
+                if (n) std::fprintf(stderr, "[ffuse] gemm %d: %d tiles, loop %.2f us avg, %.2f max (%.3f us/step, %.0f cycles/step at %.0f MHz), epilogue %.2f us\n",
+                                    k, n, l / n * 0.01, lmax * 0.01, l / st * 0.01, p / st, p / l * 100.0, e / n * 0.01);
             }
         }
         g.gemm_stats = nullptr;

@@ -10,7 +10,7 @@
 //   * finalize_kernel       -- fp32 sums -> Y in the operand type, workspace back to zero.
 //   * gemm_act_kernel       -- plain GEMM with the activation/gate epilogue: the two launches
 //     of the unfused comparison path.
-#include "ffuse_gemm0.h"
+#include "ffuse_gemm1.h"
 #include "ffuse_launch.h"
 
 namespace ffuse {
@@ -217,7 +217,7 @@ template <typename T> __global__ __launch_bounds__(256) void finalize_kernel(flo
 // ---------------------------------------------------------------------------------------
 template <typename T, bool GATED, int BM, int BH>
 __global__ __launch_bounds__(256) void gemm_act_kernel(GemmArgs a) {
-    typedef FirstGemm<T, GATED, BM, BH, 2, 2> G0;
+    typedef DeepGemm<T, GATED, BM, BH, 2, 2> G0;
     constexpr int MT = G0::MT, HT = G0::HT;
     __shared__ __attribute__((aligned(16))) char smem[G0::LDS_BYTES];
     const int tid = threadIdx.x;
@@ -231,15 +231,16 @@ __global__ __launch_bounds__(256) void gemm_act_kernel(GemmArgs a) {
     G0::init_a(c, a.A, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)m0, (uint32_t)a.K, a.K, tid);
     G0::init_b(c, a.B, a.B3, (uint32_t)((uint64_t)a.K * a.N * 2), (uint32_t)a.N, (uint32_t)a.N, (uint32_t)n0, tid);
     G0::init_lds(c, tid);
-    uint64_t t0 = 0, t1 = 0, t2 = 0;
-    if (a.stats) t0 = wall_clock64();
+    uint64_t t0 = 0, t1 = 0, t2 = 0, c0 = 0, c1 = 0;
+    if (a.stats) { t0 = wall_clock64(); c0 = clock64(); }
     G0::run(smem, c, 0, a.K, acc, acc3, tid, a.stats ? &t1 : nullptr);
-    if (a.stats) t2 = wall_clock64();
+    if (a.stats) { t2 = wall_clock64(); c1 = clock64(); }
     G0::store_tile_rt(a.act, acc, acc3, reinterpret_cast<char*>(a.C), a.N, m0, n0, a.M, a.N, tid);
     if (a.stats && tid == 0) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         uint64_t* p = a.stats + 4 * blockIdx.x;
-        p[0] = t1 - t0; p[1] = t2 - t1; p[2] = wall_clock64() - t2; p[3] = (uint64_t)((a.K + 63) / 64);
+        // p[0]: core-clock cycles from kernel start to loop end (with p[1]: the sustained clock)
+        p[0] = c1 - c0; p[1] = t2 - t0; p[2] = wall_clock64() - t2; p[3] = (uint64_t)((a.K + 63) / 64);
     }
 }
 
