@@ -382,6 +382,80 @@ struct FirstGemm {
             default: store_tile<ACT_IDENTITY>(acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
         }
     }
+
+    // Same result as store_tile, but through LDS so that the global stores are coalesced: in
+    // the accumulator layout a lane owns 4 consecutive columns of ONE row and the 64 lanes of a
+    // store instruction touch 64 different rows (64 cache lines, 8 bytes each); after the
+    // detour each lane stores 16 bytes and 16 lanes cover 256 contiguous bytes of a row.
+    // Every wave stages its own WMR x WHR block in its own region of `smem` (BM*BH*2 bytes in
+    // all, never more than LDS_BYTES), so no workgroup barrier is needed -- but the caller
+    // must make sure that no wave still reads the stages and that no load is still in flight
+    // to them.  8-byte slots of a row are XOR-swizzled with the row so that both the 8-byte
+    // writes (32 rows per instruction) and the 16-byte reads are free of bank conflicts.
+    // Requires ldc, col0 and col_lim to be multiples of 8 (16-byte aligned chunks).
+    static constexpr int EPI_RB = WHR * 2;                    // bytes per staged row
+    static constexpr int EPI_SLOTS = EPI_RB / 8;
+    static constexpr int EPI_SHIFT = EPI_RB >= 256 ? 0 : (EPI_RB == 128 ? 1 : 2);
+    static constexpr int EPI_LPR = EPI_RB / 16;               // lanes per row on the way out
+    static constexpr int EPI_RPI = 64 / EPI_LPR;              // rows per store instruction
+    static_assert(EPI_RB == 64 || EPI_RB == 128 || EPI_RB == 256 || EPI_RB == 512, "staged row size");
+    static __device__ __forceinline__ uint32_t epi_key(uint32_t row) {
+        return (row >> EPI_SHIFT) & (uint32_t)((EPI_SLOTS < 32 ? EPI_SLOTS : 32) - 1);
+    }
+    template <int ACT>
+    static __device__ __forceinline__ void store_tile_lds(char* smem, const f32x16 (&acc)[HT][MT],
+                                                          const f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
+                                                          char* C, int64_t ldc, int64_t row0, int col0,
+                                                          int64_t row_lim, int col_lim, int tid) {
+        const int wave = tid >> 6, lane = tid & 63;
+        const int wm = wave % WM, wn = wave / WM;
+        const uint32_t x = lane & 31, h = lane >> 5;
+        char* mine = smem + wave * (WMR * EPI_RB);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const uint32_t row = 32 * mt + x;
+            const uint32_t key = epi_key(row);
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = activate<ACT>(acc[ht][mt][4 * q + e]);
+                        if (GATED) v[e] *= acc3[ht][mt][4 * q + e];
+                    }
+                    uint2 o;
+                    o.x = pack2<T>(v[0], v[1]);
+                    o.y = pack2<T>(v[2], v[3]);
+                    const uint32_t slot = (uint32_t)(8 * ht + 2 * q) + h;
+                    *reinterpret_cast<uint2*>(mine + row * EPI_RB + ((slot ^ key) << 3)) = o;
+                }
+        }
+        // wave-private region: LDS operations of one wave complete in order
+        const uint32_t rin = lane / EPI_LPR, ch = lane % EPI_LPR;
+        const int col = col0 + wn * WHR + 8 * (int)ch;
+#pragma unroll
+        for (int i = 0; i < WMR / EPI_RPI; ++i) {
+            const uint32_t row = (uint32_t)(i * EPI_RPI) + rin;
+            const uint32_t key = epi_key(row);
+            u32x4 v = *reinterpret_cast<const u32x4*>(mine + row * EPI_RB + ((ch ^ (key >> 1)) << 4));
+            if (key & 1u) { u32x4 w = {v[2], v[3], v[0], v[1]}; v = w; }
+            const int64_t grow = row0 + wm * WMR + row;
+            if (grow < row_lim && col < col_lim) *reinterpret_cast<u32x4*>(C + (grow * ldc + col) * 2) = v;
+        }
+    }
+    static __device__ __forceinline__ void store_tile_lds_rt(char* smem, int act, const f32x16 (&acc)[HT][MT],
+                                                             const f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
+                                                             char* C, int64_t ldc, int64_t row0, int col0,
+                                                             int64_t row_lim, int col_lim, int tid) {
+        switch (act) {
+            case ACT_RELU: store_tile_lds<ACT_RELU>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
+            case ACT_GELU_TANH: store_tile_lds<ACT_GELU_TANH>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
+            case ACT_SILU: store_tile_lds<ACT_SILU>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
+            default: store_tile_lds<ACT_IDENTITY>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
+        }
+    }
 };
 
 }  // namespace ffuse

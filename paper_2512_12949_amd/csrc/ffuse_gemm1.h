@@ -335,23 +335,25 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         asm volatile("s_mov_b32 m0, %1\n\tbuffer_load_dwordx4 %0, %2, 0 offen lds"
                      :: "v"(voff), "s"(lds), "s"(r) : "memory", "m0");
     }
-    // load instruction i of the step whose k range starts at k (steps at or past klim load
-    // nothing from memory: out-of-range offsets, LDS receives zeros)
-    static __device__ __forceinline__ void issue_one(char* stage, const Ctx& c, int k, int klim, int i) {
+    // load instruction i of the step whose A columns start at kx and whose B rows start at kw.
+    // A chunks at or past column xlim, and everything when `valid` is false, load nothing from
+    // memory (out-of-range offsets: LDS receives zeros) -- the instruction is issued all the
+    // same so that every step puts the same number of loads in flight.
+    static __device__ __forceinline__ void issue_one(char* stage, const Ctx& c, int kx, int kw, int xlim, bool valid, int i) {
         if (i < XI) {
-            const bool ok = (k + (int)c.xk) < klim && c.abase != kOob;
-            lds_dma16(c.rx, ok ? c.xoff[i] + c.abase + (uint32_t)k * 2u : kOob,
+            const bool ok = valid && (kx + (int)c.xk) < xlim && c.abase != kOob;
+            lds_dma16(c.rx, ok ? c.xoff[i] + c.abase + (uint32_t)kx * 2u : kOob,
                       (uint32_t)(uintptr_t)stage + c.lds_a + (uint32_t)i * 1024u);
         } else {
             const int which = (i - XI) / BI, j = (i - XI) % BI;
             const uint32_t off = c.boff[j];
-            lds_dma16(c.rw[which], (off == kOob || k >= klim) ? kOob : off + (uint32_t)k * c.brow,
+            lds_dma16(c.rw[which], (off == kOob || !valid) ? kOob : off + (uint32_t)kw * c.brow,
                       (uint32_t)(uintptr_t)stage + c.lds_b + (uint32_t)which * WB + (uint32_t)j * 1024u);
         }
     }
-    static __device__ __forceinline__ void issue(char* stage, const Ctx& c, int k, int klim) {
+    static __device__ __forceinline__ void issue(char* stage, const Ctx& c, int kx, int kw, int xlim, bool valid) {
 #pragma unroll
-        for (int i = 0; i < NLOAD; ++i) issue_one(stage, c, k, klim, i);
+        for (int i = 0; i < NLOAD; ++i) issue_one(stage, c, kx, kw, xlim, valid, i);
     }
     template <int N> static __device__ __forceinline__ void loads_in_flight_at_most() {
         asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
@@ -393,8 +395,10 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     }
 
     // One step of 32 k (see the struct comment): multiplies `cur`, leaves the first fragments
-    // of `nxt` in f[0], issues the loads of the step starting at k = kld into `ld`.
-    static __device__ __forceinline__ void step(const char* cur, const char* nxt, char* ld, const Ctx& c, int kld, int klim,
+    // of `nxt` in f[0], issues the loads of a later step (A columns from kx, B rows from kw)
+    // into `ld`.
+    static __device__ __forceinline__ void step(const char* cur, const char* nxt, char* ld, const Ctx& c,
+                                                int kx, int kw, int xlim, bool valid,
                                                 Frags (&f)[2], f32x16 (&acc)[HT][MT],
                                                 f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1]) {
 #pragma unroll
@@ -403,10 +407,10 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
 #pragma unroll
             for (int e = (i * NR) / NM; e < ((i + 1) * NR) / NM; ++e) read_one(cur, c, 1, e, f[1]);
 #pragma unroll
-            for (int e = (i * NLOAD) / NM; e < ((i + 1) * NLOAD) / NM; ++e) issue_one(ld, c, kld, klim, e);
+            for (int e = (i * NLOAD) / NM; e < ((i + 1) * NLOAD) / NM; ++e) issue_one(ld, c, kx, kw, xlim, valid, e);
             __builtin_amdgcn_sched_barrier(0);
         }
-        loads_in_flight_at_most<2 * NLOAD>();   // steps s+2 and s+3 may still be on their way
+        loads_in_flight_at_most<2 * NLOAD>();   // the two youngest steps may still be on their way
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
@@ -417,32 +421,42 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         }
     }
 
+    // Fills the ring for a stream of steps that starts at (kx, kw): stages 0..2 <- steps 0..2,
+    // and leaves the fragments of step 0 in f[0].  `valid3` says which of the three exist.
+    static __device__ __forceinline__ void prime(char* smem, const Ctx& c, int kx, int kw, int xlim, int nvalid, Frags (&f)[2]) {
+        issue(smem, c, kx, kw, xlim, nvalid > 0);
+        issue(smem + STAGE, c, kx + 32, kw + 32, xlim, nvalid > 1);
+        issue(smem + 2 * STAGE, c, kx + 64, kw + 64, xlim, nvalid > 2);
+        loads_in_flight_at_most<2 * NLOAD>();
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NR; ++i) read_one(smem, c, 0, i, f[0]);
+    }
+    // After the last step: the loads still in flight target stages nobody reads any more, but
+    // LDS must be quiet, and every wave done with it, before anybody reuses it.
+    static __device__ __forceinline__ void drain() {
+        loads_in_flight_at_most<0>();
+        __syncthreads();
+    }
+
     static __device__ __forceinline__ void run(char* smem, const Ctx& c, int kbegin, int kend, f32x16 (&acc)[HT][MT],
                                                f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1], int tid,
                                                uint64_t* t_loop = nullptr) {
         (void)tid;
         Base::zero(acc, acc3);
         const int KT = (kend - kbegin + 31) / 32;
-        const int klim = kend < c.KX ? kend : c.KX;
-        issue(smem, c, kbegin, klim);
-        issue(smem + STAGE, c, kbegin + 32, klim);
-        issue(smem + 2 * STAGE, c, kbegin + 64, klim);
-        loads_in_flight_at_most<2 * NLOAD>();
-        __syncthreads();
+        const int xlim = kend < c.KX ? kend : c.KX;
         Frags f[2];
-#pragma unroll
-        for (int i = 0; i < NR; ++i) read_one(smem, c, 0, i, f[0]);
+        prime(smem, c, kbegin, kbegin, xlim, KT, f);
         if (t_loop) *t_loop = wall_clock64();
         for (int s = 0; s < KT; ++s) {
             const char* cur = smem + (s & 3) * STAGE;
             const char* nxt = smem + ((s + 1) & 3) * STAGE;
             char* ld = smem + ((s + 3) & 3) * STAGE;
-            step(cur, nxt, ld, c, kbegin + (s + 3) * 32, klim, f, acc, acc3);
+            const int k3 = kbegin + (s + 3) * 32;
+            step(cur, nxt, ld, c, k3, k3, xlim, s + 3 < KT, f, acc, acc3);
         }
-        // drain: the loads still in flight target stages nobody reads any more, but LDS must be
-        // quiet before the caller reuses it
-        loads_in_flight_at_most<0>();
-        __syncthreads();
+        drain();
     }
 };
 

@@ -235,7 +235,7 @@ __global__ __launch_bounds__(256) void gemm_act_kernel(GemmArgs a) {
     if (a.stats) { t0 = wall_clock64(); c0 = clock64(); }
     G0::run(smem, c, 0, a.K, acc, acc3, tid, a.stats ? &t1 : nullptr);
     if (a.stats) { t2 = wall_clock64(); c1 = clock64(); }
-    G0::store_tile_rt(a.act, acc, acc3, reinterpret_cast<char*>(a.C), a.N, m0, n0, a.M, a.N, tid);
+    G0::store_tile_lds_rt(smem, a.act, acc, acc3, reinterpret_cast<char*>(a.C), a.N, m0, n0, a.M, a.N, tid);
     if (a.stats && tid == 0) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         uint64_t* p = a.stats + 4 * blockIdx.x;
@@ -306,11 +306,12 @@ struct ExchStats {
 template <typename T, bool GATED>
 __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
     constexpr int BHP = GATED ? 128 : 256;
-    typedef FirstGemm<T, GATED, 256, BHP, 2, 2> GP;   // producer: X * W1 (, X * W3)
-    typedef FirstGemm<T, false, 256, 256, 2, 2> GC;   // consumer: H * W2
+    typedef DeepGemm<T, GATED, 256, BHP, 2, 2> GP;    // producer: X * W1 (, X * W3)
+    typedef DeepGemm<T, false, 256, 256, 2, 2> GC;    // consumer: H * W2
     constexpr int LDS_BYTES = GP::LDS_BYTES > GC::LDS_BYTES ? GP::LDS_BYTES : GC::LDS_BYTES;
     constexpr uint32_t SLOT_BYTES = 256u * BHP * 2u;
-    constexpr int SPI = BHP / 64;                     // K steps per item on the consumer side
+    constexpr int SPI = BHP / 32;                     // steps of 32 k per item on the consumer side
+    static_assert(SPI % GC::NS == 0 && SPI > 3, "an item is a whole number of turns of the stage ring");
     __shared__ __attribute__((aligned(16))) char smem[LDS_BYTES];
     __shared__ uint32_t verdict[4];
 
@@ -369,10 +370,10 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
                 GP::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1,
                            (uint32_t)hh * BHP, tid);
                 GP::run(smem, c, 0, a.K, acc, acc3, tid);
-                GP::store_tile_rt(a.act, acc, acc3, ring + (size_t)slot * SLOT_BYTES, BHP, 0, 0, 256, BHP, tid);
+                GP::store_tile_lds_rt(smem, a.act, acc, acc3, ring + (size_t)slot * SLOT_BYTES, BHP, 0, 0, 256, BHP, tid);
             }
             stores_done();     // this thread's tile stores have reached L2
-            __syncthreads();   // ... and so have everybody else's
+            __syncthreads();   // ... and so have everybody else's (and LDS is free again)
             if (tid == 0) {
                 if (coherent) __hip_atomic_store(ready + slot, (uint32_t)o + 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
                 else __hip_atomic_store(ready + slot, (uint32_t)o + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -395,7 +396,7 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
     typename GC::Ctx c;
     GC::init_lds(c, tid);
     GC::init_b(c, a.W2, nullptr, (uint32_t)((uint64_t)a.N1 * a.N2 * 2), (uint32_t)a.N2, (uint32_t)a.N2, (uint32_t)ct * 256u, tid);
-    typename GC::Stage st;
+    typename GC::Frags f[2];
     for (int gseq = 0; gseq < ngx; ++gseq) {
         // a panel past the end (ragged last group) is processed like any other: its producers
         // publish nothing, its consumers multiply whatever the slot holds and store nothing
@@ -403,43 +404,44 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
         GC::zero(acc, acc3);
         const int o0 = gseq * NH * PG + pi;   // item of hidden tile 0; tile h is o0 + h*PG
         // A operand = ring slot of the item (256 x BHP, leading dimension BHP); B rows h*BHP + k.
-        // Loads run two K steps ahead, i.e. at most into the next item: item h+1 must be
-        // ready before the steps of item h are issued.
+        // The items of a panel form ONE stream of steps of 32 k through the stage ring.  Loads
+        // run three steps ahead, i.e. at most into the next item: item h+1 must be ready
+        // before the steps of item h are issued.
         es.begin_wait(a.stats);
         if (!wait_at_least(ready + o0 % R, (uint32_t)o0 + 1u, err, verdict, coherent)) return;
         es.end_wait(a.stats);
         GC::init_a(c, ring, (uint32_t)R * SLOT_BYTES, (uint32_t)(o0 % R) * SLOT_BYTES, 0u, BHP, BHP, tid);
-        GC::gload(c, st, 0, 0);
-        GC::store_a(smem, st, tid);
-        GC::store_b(smem, st, tid);
-        GC::gload(c, st, 64, 64);
-        __syncthreads();
+        GC::prime(smem, c, 0, 0, BHP, 3, f);
         for (int hh = 0; hh < NH; ++hh) {
             const int o = o0 + hh * PG, on = o + PG;
-            if (hh + 1 < NH) {
+            const bool more = hh + 1 < NH;
+            if (more) {
                 es.begin_wait(a.stats);
                 if (!wait_at_least(ready + on % R, (uint32_t)on + 1u, err, verdict, coherent)) return;
                 es.end_wait(a.stats);
             }
             const uint32_t base_cur = (uint32_t)(o % R) * SLOT_BYTES;
-            const uint32_t base_nxt = (hh + 1 < NH) ? (uint32_t)(on % R) * SLOT_BYTES : kOob;
+            const uint32_t base_nxt = more ? (uint32_t)(on % R) * SLOT_BYTES : kOob;
 #pragma unroll 1
             for (int ks = 0; ks < SPI; ++ks) {
-                // step s = hh*SPI + ks multiplies; loads fetch step s + 2
-                const int k2 = (ks + 2) % SPI * 64;
-                const bool wrap = ks + 2 >= SPI;
+                // step hh*SPI + ks multiplies; its loads fetch the step three later
+                const int k3 = (ks + 3) % SPI * 32;
+                const bool wrap = ks + 3 >= SPI;
                 c.abase = wrap ? base_nxt : base_cur;
-                const int kw2 = (wrap ? hh + 1 : hh) * BHP + k2;
-                char* cur = smem + (ks & 1) * GC::STAGE;
-                char* nxt = smem + ((ks + 1) & 1) * GC::STAGE;
-                GC::step(cur, nxt, c, st, k2, kw2, acc, acc3, tid);
-                __syncthreads();
+                const int kw3 = (wrap ? hh + 1 : hh) * BHP + k3;
+                const char* cur = smem + (ks & 3) * GC::STAGE;
+                const char* nxt = smem + ((ks + 1) & 3) * GC::STAGE;
+                char* ld = smem + ((ks + 3) & 3) * GC::STAGE;
+                GC::step(cur, nxt, ld, c, k3, kw3, BHP, !wrap || more, f, acc, acc3);
             }
-            // every wave has multiplied the item's last step: release its slot
+            // past the barrier of the item's last step every wave's loads from the slot have
+            // landed in LDS: release the slot
             if (tid == 0) __hip_atomic_fetch_add(done + o % R, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        GC::template store_tile<ACT_IDENTITY>(acc, acc3, reinterpret_cast<char*>(a.Y), a.N2, (int64_t)panel * 256,
-                                              ct * 256, a.M, a.N2, tid);
+        GC::drain();
+        GC::template store_tile_lds<ACT_IDENTITY>(smem, acc, acc3, reinterpret_cast<char*>(a.Y), a.N2, (int64_t)panel * 256,
+                                                  ct * 256, a.M, a.N2, tid);
+        __syncthreads();   // LDS is free again before the next panel's loads
     }
     finish(2, ngx * NH);
 }
