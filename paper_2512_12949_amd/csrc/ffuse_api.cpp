@@ -360,11 +360,14 @@ int ffuse_sync_status(void* stream) {
         std::vector<uint64_t> h(4 * (size_t)g.exch_wgs);
         if (hipMemcpy(h.data(), g.exch_stats, h.size() * 8, hipMemcpyDeviceToHost) == hipSuccess) {
             for (int role = 1; role <= 2; ++role) {
-                double tot = 0, wt = 0, mx = 0, mxw = 0; int n = 0;
+                double tot = 0, wt = 0, mx = 0, mxw = 0, gm = 0, ep = 0; int n = 0;
                 for (int i = 0; i < g.exch_wgs; ++i)
-                    if ((int)h[4 * i] == role) { tot += h[4 * i + 1]; wt += h[4 * i + 2]; mx = std::max(mx, (double)h[4 * i + 1]); mxw = std::max(mxw, (double)h[4 * i + 2]); ++n; }
-                if (n) std::fprintf(stderr, "[ffuse] exchange %s: %d wgs, busy+wait avg %.1f us (max %.1f), waiting avg %.1f us (max %.1f)\n",
-                                    role == 1 ? "producers" : "consumers", n, tot / n * 0.01, mx * 0.01, wt / n * 0.01, mxw * 0.01);
+                    if ((int)(h[4 * i] & 255u) == role) {
+                        tot += h[4 * i + 1]; wt += h[4 * i + 2]; mx = std::max(mx, (double)h[4 * i + 1]); mxw = std::max(mxw, (double)h[4 * i + 2]);
+                        gm += (double)(h[4 * i] >> 8); ep += (double)(h[4 * i + 3] >> 32); ++n;
+                    }
+                if (n) std::fprintf(stderr, "[ffuse] exchange %s: %d wgs, busy+wait avg %.1f us (max %.1f), waiting avg %.1f us (max %.1f), producing: GEMM avg %.1f us, epilogue+publish avg %.1f us\n",
+                                    role == 1 ? "producers" : "consumers", n, tot / n * 0.01, mx * 0.01, wt / n * 0.01, mxw * 0.01, gm / n * 0.01, ep / n * 0.01);
             }
         }
     }

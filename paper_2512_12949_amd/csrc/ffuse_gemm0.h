@@ -407,7 +407,11 @@ struct FirstGemm {
                                                           const f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
                                                           char* C, int64_t ldc, int64_t row0, int col0,
                                                           int64_t row_lim, int col_lim, int tid) {
-        const int wave = tid >> 6, lane = tid & 63;
+        const int wave = tid >> 6;
+        int lane = tid & 63;
+        // opaque to the optimiser: otherwise the per-row LDS addresses below are hoisted out of
+        // the caller's tile loop and live (spilled) across its main loop
+        asm volatile("" : "+v"(lane));
         const int wm = wave % WM, wn = wave / WM;
         const uint32_t x = lane & 31, h = lane >> 5;
         char* mine = smem + wave * (WMR * EPI_RB);
@@ -435,14 +439,25 @@ struct FirstGemm {
         // wave-private region: LDS operations of one wave complete in order
         const uint32_t rin = lane / EPI_LPR, ch = lane % EPI_LPR;
         const int col = col0 + wn * WHR + 8 * (int)ch;
+        // in batches of 8 rows-per-lane, fenced: left alone the compiler hoists all the LDS
+        // reads above the stores and runs out of registers
+        constexpr int NOUT = WMR / EPI_RPI, BATCH = NOUT < 8 ? NOUT : 8;
 #pragma unroll
-        for (int i = 0; i < WMR / EPI_RPI; ++i) {
-            const uint32_t row = (uint32_t)(i * EPI_RPI) + rin;
-            const uint32_t key = epi_key(row);
-            u32x4 v = *reinterpret_cast<const u32x4*>(mine + row * EPI_RB + ((ch ^ (key >> 1)) << 4));
-            if (key & 1u) { u32x4 w = {v[2], v[3], v[0], v[1]}; v = w; }
-            const int64_t grow = row0 + wm * WMR + row;
-            if (grow < row_lim && col < col_lim) *reinterpret_cast<u32x4*>(C + (grow * ldc + col) * 2) = v;
+        for (int i0 = 0; i0 < NOUT; i0 += BATCH) {
+            u32x4 v[BATCH];
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i) {
+                const uint32_t row = (uint32_t)((i0 + i) * EPI_RPI) + rin;
+                const uint32_t key = epi_key(row);
+                v[i] = *reinterpret_cast<const u32x4*>(mine + row * EPI_RB + ((ch ^ (key >> 1)) << 4));
+                if (key & 1u) { u32x4 w = {v[i][2], v[i][3], v[i][0], v[i][1]}; v[i] = w; }
+            }
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i) {
+                const int64_t grow = row0 + wm * WMR + (i0 + i) * EPI_RPI + rin;
+                if (grow < row_lim && col < col_lim) *reinterpret_cast<u32x4*>(C + (grow * ldc + col) * 2) = v[i];
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     static __device__ __forceinline__ void store_tile_lds_rt(char* smem, int act, const f32x16 (&acc)[HT][MT],

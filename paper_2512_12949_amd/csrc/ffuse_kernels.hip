@@ -273,32 +273,40 @@ static constexpr uint32_t kSpinLimit = 1u << 23;
 __device__ __forceinline__ void drop_l1() { asm volatile("buffer_inv sc0" ::: "memory"); }
 __device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-__device__ __forceinline__ bool wait_at_least(uint32_t* flag, uint32_t want, uint32_t* err, uint32_t* sh, int coherent) {
-    // thread 0 polls; the verdict is broadcast through LDS word sh[0]
-    if (threadIdx.x == 0) {
-        uint32_t spins = 0, ok = 1;
-        while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
-            __builtin_amdgcn_s_sleep(2);
-            if ((++spins & 1023u) == 0 &&
-                (spins > kSpinLimit || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-                __hip_atomic_fetch_or(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ok = 0;
-                break;
-            }
+// Flag polling.  Flags are read with SCALAR loads that bypass the scalar cache (glc): scalar
+// loads are counted by lgkmcnt, so waiting for one does not wait for the LDS-direct vector
+// loads the wave has in flight (vector loads return in order: a vector-load poll would drain
+// the whole prefetch pipeline every time).  Every wave polls for itself -- the address is
+// uniform, there is no broadcast and no barrier.
+__device__ __forceinline__ uint32_t peek(const uint32_t* flag) {
+    // the address is uniform by construction; say so, or it may sit in vector registers
+    const uint64_t p = (uint64_t)flag;
+    const uint64_t u = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(p >> 32)) << 32) |
+                       (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+    uint32_t v;
+    asm volatile("s_load_dword %0, %1, 0x0 glc\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(u) : "memory");
+    return v;
+}
+// Waits until *flag >= want; bounded: on expiry (or when another workgroup has given up) the
+// error word is set and the wave returns false.  Then drops the CU's vector L1 (or, with
+// `coherent`, does a full agent-scope acquire).
+__device__ __forceinline__ bool wait_at_least(const uint32_t* flag, uint32_t want, uint32_t* err, int coherent) {
+    uint32_t spins = 0;
+    while (peek(flag) < want) {
+        __builtin_amdgcn_s_sleep(2);
+        if ((++spins & 1023u) == 0 && (spins > kSpinLimit || peek(err) != 0)) {
+            if ((threadIdx.x & 63) == 0) __hip_atomic_fetch_or(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return false;
         }
-        sh[0] = ok;
     }
-    __syncthreads();
-    const bool ok = sh[0] != 0;
     if (coherent) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     else drop_l1();
-    __syncthreads();
-    return ok;
+    return true;
 }
 
 // optional per-workgroup timing (args.stats != nullptr): 100 MHz wall-clock ticks
 struct ExchStats {
-    uint64_t t0 = 0, wait = 0, tw = 0;
+    uint64_t t0 = 0, wait = 0, tw = 0, gemm = 0, epi = 0, tg = 0;
     __device__ __forceinline__ void begin_wait(const void* on) { if (on) tw = wall_clock64(); }
     __device__ __forceinline__ void end_wait(const void* on) { if (on) wait += wall_clock64() - tw; }
 };
@@ -313,8 +321,6 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
     constexpr int SPI = BHP / 32;                     // steps of 32 k per item on the consumer side
     static_assert(SPI % GC::NS == 0 && SPI > 3, "an item is a whole number of turns of the stage ring");
     __shared__ __attribute__((aligned(16))) char smem[LDS_BYTES];
-    __shared__ uint32_t verdict[4];
-
     const int tid = threadIdx.x;
     const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
     const int P = a.P, NCT = a.NCT, PG = a.PG, R = a.R, NH = a.NH;
@@ -332,7 +338,7 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
     auto finish = [&](int role, int n) {
         if (a.stats && tid == 0) {
             uint64_t* p = a.stats + 4 * blockIdx.x;
-            p[0] = (uint64_t)role; p[1] = wall_clock64() - es.t0; p[2] = es.wait; p[3] = (uint64_t)n;
+            p[0] = (uint64_t)role | (es.gemm << 8); p[1] = wall_clock64() - es.t0; p[2] = es.wait; p[3] = (uint64_t)n | (es.epi << 32);
         }
     };
     if (!coherent) {
@@ -363,17 +369,20 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
             const int panel = (xcd + 8 * gseq) * PG + pi;
             const int slot = o % R;
             es.begin_wait(a.stats);
-            if (!wait_at_least(done + slot, (uint32_t)(o / R) * NCT, err, verdict, coherent)) return;
+            if (!wait_at_least(done + slot, (uint32_t)(o / R) * NCT, err, coherent)) return;
             es.end_wait(a.stats);
             if (panel < NP) {
                 GP::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)panel * 256u, (uint32_t)a.K, a.K, tid);
                 GP::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1,
                            (uint32_t)hh * BHP, tid);
+                if (a.stats) es.tg = wall_clock64();
                 GP::run(smem, c, 0, a.K, acc, acc3, tid);
+                if (a.stats) { const uint64_t t = wall_clock64(); es.gemm += t - es.tg; es.tg = t; }
                 GP::store_tile_lds_rt(smem, a.act, acc, acc3, ring + (size_t)slot * SLOT_BYTES, BHP, 0, 0, 256, BHP, tid);
             }
             stores_done();     // this thread's tile stores have reached L2
             __syncthreads();   // ... and so have everybody else's (and LDS is free again)
+            if (a.stats && panel < NP) es.epi += wall_clock64() - es.tg;
             if (tid == 0) {
                 if (coherent) __hip_atomic_store(ready + slot, (uint32_t)o + 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
                 else __hip_atomic_store(ready + slot, (uint32_t)o + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -408,7 +417,7 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
         // run three steps ahead, i.e. at most into the next item: item h+1 must be ready
         // before the steps of item h are issued.
         es.begin_wait(a.stats);
-        if (!wait_at_least(ready + o0 % R, (uint32_t)o0 + 1u, err, verdict, coherent)) return;
+        if (!wait_at_least(ready + o0 % R, (uint32_t)o0 + 1u, err, coherent)) return;
         es.end_wait(a.stats);
         GC::init_a(c, ring, (uint32_t)R * SLOT_BYTES, (uint32_t)(o0 % R) * SLOT_BYTES, 0u, BHP, BHP, tid);
         GC::prime(smem, c, 0, 0, BHP, 3, f);
@@ -417,7 +426,7 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
             const bool more = hh + 1 < NH;
             if (more) {
                 es.begin_wait(a.stats);
-                if (!wait_at_least(ready + on % R, (uint32_t)on + 1u, err, verdict, coherent)) return;
+                if (!wait_at_least(ready + on % R, (uint32_t)on + 1u, err, coherent)) return;
                 es.end_wait(a.stats);
             }
             const uint32_t base_cur = (uint32_t)(o % R) * SLOT_BYTES;
