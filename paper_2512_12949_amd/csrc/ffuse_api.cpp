@@ -155,8 +155,8 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
         return FFUSE_OK;
     }
     if (plan.family == FFUSE_FAMILY_TWOPHASE) {
-        ffuse::SmallMGeometry sg;
-        if (!ffuse::small_m_geometry(plan, M, N1, N2, &sg)) return FFUSE_ERR_PLAN;
+        ffuse::TwoPhaseGeometry sg;
+        if (!ffuse::two_phase_geometry(plan, M, N1, N2, &sg)) return FFUSE_ERR_PLAN;
         if (!g.ws || g.ws_bytes < sg.ws_bytes) return FFUSE_ERR_WORKSPACE;
         char* base = reinterpret_cast<char*>(g.ws);
         uint32_t* flags = reinterpret_cast<uint32_t*>(base + sg.ysum_bytes + sg.h_bytes);
@@ -164,9 +164,9 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
             if (ffuse::launch_zero(flags, 256, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
             g.small_flags = flags;
         }
-        g.ws_zero = 0;      // the partial-sum planes overwrite the region the reduce family keeps at zero
-        ffuse::SmallMArgs s{X, W1, W3, W2, base + sg.ysum_bytes, reinterpret_cast<float*>(base), flags,
-                            M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, nullptr};
+        g.ws_zero = 0;      // planes and H overwrite the region the reduce family keeps at zero
+        ffuse::TwoPhaseArgs s{X, W1, W3, W2, base + sg.ysum_bytes, Y, reinterpret_cast<float*>(base), flags,
+                              M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, sg.raster, nullptr};
         if (g.log && g.ws_bytes >= sg.ws_bytes + 32768) {
             s.stats = reinterpret_cast<uint64_t*>(base + sg.ws_bytes);
             g.small_stats = s.stats;
@@ -174,10 +174,10 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
         g.exch_err = flags + 2;
         {
             Timer t(st);
-            if (ffuse::launch_fused_small_m(dtype, s, sg.bm, g.cus, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+            if (ffuse::launch_fused_two_phase(dtype, s, sg.bm, g.cus, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
             t.stop();
         }
-        if (ffuse::launch_finalize_planes(dtype, s.part, Y, M * N2, sg.splits, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+        if (sg.splits > 1 && ffuse::launch_finalize_planes(dtype, s.part, Y, M * N2, sg.splits, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
         g.last_plan = plan;
         return FFUSE_OK;
     }
@@ -267,10 +267,11 @@ size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t
         // room for the exchange family's flags + ring at its largest ring setting
         const size_t ex = ffuse::kExchangeFlagBytes + (size_t)8 * ffuse::kExchangeMaxRing * 256 * (gated ? 128 : 256) * 2;
         if (ex > b) b = ex;
-        if (M <= 128) {   // two-phase small-M family: sums | H | flags
-            const size_t sm = (((size_t)4 * M * N2 * 32 + 255) & ~(size_t)255) + (((size_t)2 * M * N1 + 255) & ~(size_t)255) + 256;  // up to 32 planes
-            if (sm > b) b = sm;
-        }
+        // two-phase family: partial-sum planes (at the most splits the chooser uses for this M) | H | flags
+        const int sp = ffuse::two_phase_max_splits(M);
+        const size_t planes = sp > 1 ? (((size_t)4 * M * N2 * sp + 255) & ~(size_t)255) : 0;
+        const size_t tp = planes + (((size_t)2 * M * N1 + 255) & ~(size_t)255) + 256;
+        if (tp > b) b = tp;
     }
     return (b + 255) & ~(size_t)255;
 }

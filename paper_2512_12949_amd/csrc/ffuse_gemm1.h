@@ -1,240 +1,25 @@
-// Block GEMM, second generation: same contract and accumulator layout as FirstGemm
+// Block GEMM with LDS-direct loads: same contract and accumulator layout as FirstGemm
 // (ffuse_gemm0.h), but operand tiles go from global memory STRAIGHT into LDS
 // (buffer_load_dwordx4 ... lds, 16 bytes per lane, no staging registers, no LDS store
-// instructions) and the weight operand is transposed on the way OUT of LDS by
-// ds_read_b64_tr_b16 instead of by a register transpose on the way in.
+// instructions), the weight operand is transposed on the way OUT of LDS by
+// ds_read_b64_tr_b16 instead of by a register transpose on the way in, and the stages form
+// a ring of FOUR stages of 32 k each, so that loads are issued three stages (1.5 K steps of
+// 64) before their data is multiplied.
 //
-//   A tile [BM][64 k]  : LDS rows of 128 bytes, XOR chunk swizzle (as in FirstGemm); the
-//                        swizzle is realised by WHICH global chunk each lane fetches, because
-//                        an LDS-direct load writes lane i's 16 bytes at base + 16*i.
-//   B tile [64 k][BH n]: kept in its global orientation, rows of BH*2 bytes; 32-byte units
+// Why so deep: measured on this chip the L2 delivers about 30 bytes per clock per CU, which
+// for a 256 x 256 tile is the same time as the tile's MFMAs.  With both units near saturation
+// the L2 queues are long (over 1500 clocks) and only a deep ring keeps the matrix cores fed.
+//
+//   A stage [BM][32 k] : rows of 64 bytes; 16-byte slot c of row r sits at position
+//                        c ^ ((r >> 2) & 3) (rows r, r+4, r+8, r+12 share banks).  The swizzle
+//                        is realised by WHICH global chunk each lane fetches, because an
+//                        LDS-direct load writes lane i's 16 bytes at base + 16*i.
+//   B stage [32 k][BH] : kept in its global orientation, rows of BH*2 bytes; 32-byte units
 //                        within a row are XOR-swizzled with (k & 3) << 1 so that the four
 //                        k-rows one transposing read touches fall into different banks.
 //   ds_read_b64_tr_b16 : in every group of 16 lanes, lanes 4j..4j+3 supply the address of 16
 //                        consecutive n of row k0 + j; lane L receives (k0..k0+3, n0 + L).
 //                        Two of them give the 8 consecutive k an MFMA operand register holds.
-//
-// Per K step of 64: the loads of step i+1 are issued right after the barrier that ends step
-// i-1 (their LDS buffer was last read in step i-1) and have the whole of step i to land.
-#pragma once
-#include "ffuse_gemm0.h"
-
-namespace ffuse {
-
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((address_space(3))) void lds_void;
-
-template <typename T, bool GATED, int BM, int BH, int WM, int WN>
-struct DirectGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
-    typedef FirstGemm<T, GATED, BM, BH, WM, WN> Base;
-    typedef typename Base::vec8 vec8;
-    using Base::G; using Base::HT; using Base::MT; using Base::WHR; using Base::WMR;
-    using Base::XB; using Base::WB; using Base::STAGE; using Base::LDS_BYTES;
-    static_assert(BH == 128 || BH == 256, "unit swizzle needs 8 or 16 units of 32 bytes per row");
-    static constexpr int XI = BM / 32;                 // A load instructions per wave per stage
-    static constexpr int ROWB = BH * 2;                // bytes of one B row in LDS
-    static constexpr int RPI = 1024 / ROWB;            // B rows per load instruction
-    static constexpr int BI = 64 / RPI / 4;            // B load instructions per wave per matrix
-
-    struct Ctx {
-        __amdgpu_buffer_rsrc_t rx, rw[G];
-        uint32_t xoff[XI];      // global byte offset of this lane's A chunk, per instruction, at k = 0
-        uint32_t xk[2];         // k of this lane's A chunk within the step (even / odd instruction)
-        uint32_t boff[BI];      // global byte offset of this lane's B chunk, per instruction, at k = 0
-        uint32_t abase;         // uniform byte offset added to A offsets (kOob: reads as zero)
-        uint32_t brow;          // bytes per global B row
-        int KX;                 // extent of A along k
-        uint32_t lds_a, lds_b;  // uniform LDS byte offsets of this wave's first A / B instruction
-        uint32_t rdx[MT];       // LDS read offsets: A fragments (sub-step 0)
-        uint32_t rdw[HT];       //                   B fragments (sub-step 0, first half)
-    };
-
-    static __device__ __forceinline__ void init_a(Ctx& c, const void* A, uint32_t a_bytes, uint32_t base_bytes,
-                                                  uint32_t row0, uint32_t lda, int kx, int tid) {
-        const int wave = tid >> 6, lane = tid & 63;
-        c.rx = make_rsrc(A, a_bytes);
-        c.KX = kx;
-        c.abase = base_bytes;
-#pragma unroll
-        for (int j = 0; j < XI; ++j) {
-            const uint32_t row = (uint32_t)(wave * XI + j) * 8u + (lane >> 3);
-            const uint32_t chunk = (lane & 7) ^ ((row >> 1) & 7u);   // LDS position lane&7 holds this chunk
-            c.xoff[j] = ((row0 + row) * lda + 8u * chunk) * 2u;
-            if (j < 2) c.xk[j] = 8u * chunk;
-        }
-    }
-    static __device__ __forceinline__ void init_b(Ctx& c, const void* B, const void* B3, uint32_t b_bytes,
-                                                  uint32_t ldb, uint32_t ncols, uint32_t n0, int tid) {
-        const int wave = tid >> 6, lane = tid & 63;
-        c.rw[0] = make_rsrc(B, b_bytes);
-        if (GATED) c.rw[G - 1] = make_rsrc(B3, b_bytes);
-        c.brow = ldb * 2u;
-#pragma unroll
-        for (int j = 0; j < BI; ++j) {
-            const uint32_t byte = (uint32_t)(wave * BI + j) * 1024u + 16u * lane;   // within the B tile
-            const uint32_t k = byte / ROWB, pp = (byte % ROWB) / 16u;             // row, 16-byte position
-            const uint32_t p = ((((pp >> 1) ^ ((k & 3u) << 1)) << 1) | (pp & 1u));   // global chunk stored there
-            const uint32_t col = n0 + 8u * p;
-            c.boff[j] = col < ncols ? (k * ldb + col) * 2u : kOob;
-        }
-    }
-    static __device__ __forceinline__ void init_lds(Ctx& c, int tid) {
-        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // uniform: feeds M0
-        const int wm = wave % WM, wn = wave / WM;
-        const uint32_t x = lane & 31, h = lane >> 5;
-        c.lds_a = (uint32_t)(wave * XI) * 1024u;
-        c.lds_b = XB + (uint32_t)(wave * BI) * 1024u;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) c.rdx[mt] = lds_row_off(wm * WMR + 32 * mt + x, h);
-        const uint32_t gidx = lane >> 4, jj = (lane >> 2) & 3u, q = lane & 3u;
-#pragma unroll
-        for (int ht = 0; ht < HT; ++ht) {
-            const uint32_t u = (uint32_t)(wn * WHR + 32 * ht) / 16u + (gidx & 1u);
-            c.rdw[ht] = XB + (8u * (gidx >> 1) + jj) * ROWB + ((u ^ (jj << 1)) * 32u) + 8u * q;
-        }
-    }
-
-    // One LDS-direct load: 16 bytes per lane from buffer `r` at byte offset `voff` to LDS bytes
-    // [lds, lds + 1024).  Written as inline assembly on purpose: with the compiler's own
-    // builtin every transposing LDS read is preceded by a conservative s_waitcnt vmcnt(0) (it
-    // cannot see that the read and the DMA target different stages), which would serialise
-    // the loop.  The kernel waits for these loads itself (loads_landed) before each barrier.
-    static __device__ __forceinline__ void lds_dma16(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t lds) {
-        asm volatile("s_mov_b32 m0, %1\n\tbuffer_load_dwordx4 %0, %2, 0 offen lds"
-                     :: "v"(voff), "s"(lds), "s"(r) : "memory", "m0");
-    }
-    // global -> LDS for the K step whose A columns start at kx and B rows at kw
-    static __device__ __forceinline__ void issue_a(char* stage, const Ctx& c, int kx, int j) {
-        const bool ok = (kx + (int)c.xk[j & 1]) < c.KX && c.abase != kOob;
-        lds_dma16(c.rx, ok ? c.xoff[j] + c.abase + (uint32_t)kx * 2u : kOob,
-                  (uint32_t)(uintptr_t)stage + c.lds_a + (uint32_t)j * 1024u);
-    }
-    static __device__ __forceinline__ void issue_b(char* stage, const Ctx& c, int kw, int which, int j) {
-        const uint32_t off = c.boff[j];
-        lds_dma16(c.rw[which], off == kOob ? kOob : off + (uint32_t)kw * c.brow,
-                  (uint32_t)(uintptr_t)stage + c.lds_b + (uint32_t)which * WB + (uint32_t)j * 1024u);
-    }
-    static constexpr int NLOAD = XI + G * BI;   // load instructions per wave per stage
-    static __device__ __forceinline__ void issue_one(char* stage, const Ctx& c, int kx, int kw, int i) {
-        if (i < XI) issue_a(stage, c, kx, i);
-        else issue_b(stage, c, kw, (i - XI) / BI, (i - XI) % BI);
-    }
-    static __device__ __forceinline__ void issue(char* stage, const Ctx& c, int kx, int kw) {
-#pragma unroll
-        for (int i = 0; i < NLOAD; ++i) issue_one(stage, c, kx, kw, i);
-    }
-    static __device__ __forceinline__ void loads_landed() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-    struct Frags {
-        vec8 b[MT];
-        vec8 a[HT];
-        vec8 a3[GATED ? HT : 1];
-    };
-    static __device__ __forceinline__ vec8 read_b_frag(const char* smem, uint32_t off) {
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(smem + off));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(smem + off + 4 * ROWB));
-        typedef __attribute__((ext_vector_type(8))) short s16x8;
-        const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        return __builtin_bit_cast(vec8, v);
-    }
-    // fragment read number i of sub-step ks, in the order the MFMAs need them
-    static __device__ __forceinline__ void read_one(const char* smem, const Ctx& c, int ks, int i, Frags& f) {
-        const uint32_t kxor = (uint32_t)(ks << 5), kadd = (uint32_t)(16 * ks) * ROWB;
-        if (i == 0) { f.b[0] = lds_read16<vec8>(smem, c.rdx[0] ^ kxor); return; }
-        if (i == 1) { f.a[0] = read_b_frag(smem, c.rdw[0] + kadd); return; }
-        int j = i - 2;
-        if (GATED) {
-            if (j == 0) { f.a3[0] = read_b_frag(smem + WB, c.rdw[0] + kadd); return; }
-            j -= 1;
-        }
-        if (j < MT - 1) { f.b[j + 1] = lds_read16<vec8>(smem, c.rdx[j + 1] ^ kxor); return; }
-        j -= MT - 1;
-        const int ht = 1 + j / G;
-        if (!GATED || (j % G) == 0) f.a[ht] = read_b_frag(smem, c.rdw[ht] + kadd);
-        else f.a3[ht] = read_b_frag(smem + WB, c.rdw[ht] + kadd);
-    }
-    static __device__ __forceinline__ void mma_one(const Frags& f, int i, f32x16 (&acc)[HT][MT],
-                                                   f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1]) {
-        const int ht = i / (MT * G), r = i % (MT * G);
-        if (!GATED || r < MT) acc[ht][r % MT] = Mma<T>::mma(f.a[ht], f.b[r % MT], acc[ht][r % MT]);
-        else acc3[GATED ? ht : 0][GATED ? r - MT : 0] = Mma<T>::mma(f.a3[GATED ? ht : 0], f.b[r - MT], acc3[GATED ? ht : 0][GATED ? r - MT : 0]);
-    }
-
-    // One K step on the stage at `cur`, entered with the fragments of sub-step 0 already in
-    // f[0].  The loads of the NEXT step (kx, kw) go into the stage at `nxt` under the first
-    // two sub-steps; the step's only barrier sits BEFORE the last sub-step, so that the last
-    // sub-step's MFMAs cover the reads of the next step's first fragments (left in f[0]) and
-    // no LDS latency is exposed at the step boundary.  Micro-chunks of one MFMA plus a little
-    // other work, fenced so that the issue order survives the compiler.
-    //
-    // Why one barrier is enough: when a wave passes it, every wave has finished reading `cur`
-    // (the last fragments were fetched under sub-step 2 and waited for) and every wave's
-    // loads into `nxt` have landed.  `cur` is next written by the loads of the following
-    // step, which are issued after this barrier; `nxt` is next read after it.
-    static __device__ __forceinline__ void step(const char* cur, char* nxt, const Ctx& c, int kx, int kw,
-                                                Frags (&f)[2], f32x16 (&acc)[HT][MT],
-                                                f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1]) {
-        constexpr int NM = HT * MT * G;
-        constexpr int NR = MT + HT * G;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks == 3) {
-                loads_landed();
-                __syncthreads();
-            }
-#pragma unroll
-            for (int i = 0; i < NM; ++i) {
-                mma_one(f[ks & 1], i, acc, acc3);
-#pragma unroll
-                for (int e = (i * NR) / NM; e < ((i + 1) * NR) / NM; ++e)
-                    read_one(ks < 3 ? cur : nxt, c, (ks + 1) & 3, e, f[(ks + 1) & 1]);
-                if (ks < 2) {   // the next stage's loads ride under the first two sub-steps
-                    constexpr int NM2 = 2 * NM;
-                    const int i2 = ks * NM + i;
-#pragma unroll
-                    for (int e = (i2 * NLOAD) / NM2; e < ((i2 + 1) * NLOAD) / NM2; ++e) issue_one(nxt, c, kx, kw, e);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-    }
-
-    static __device__ __forceinline__ void run(char* smem, const Ctx& c, int kbegin, int kend, f32x16 (&acc)[HT][MT],
-                                               f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1], int tid,
-                                               uint64_t* t_loop = nullptr) {
-        (void)tid;
-        constexpr int NR = MT + HT * G;
-        Base::zero(acc, acc3);
-        const int KT = (kend - kbegin + 63) / 64;
-        issue(smem, c, kbegin, kbegin);
-        loads_landed();
-        __syncthreads();
-        Frags f[2];
-#pragma unroll
-        for (int i = 0; i < NR; ++i) read_one(smem, c, 0, i, f[0]);
-        if (t_loop) *t_loop = wall_clock64();
-        for (int kt = 0; kt < KT; ++kt) {
-            char* cur = smem + (kt & 1) * STAGE;
-            char* nxt = smem + ((kt + 1) & 1) * STAGE;
-            const int k1 = kbegin + (kt + 1) * 64;
-            step(cur, nxt, c, k1, k1, f, acc, acc3);
-        }
-        // the last step's barrier leaves every wave done with the stage it multiplied; the
-        // other stage holds zero-filled or unused data that only this wave's f[0] has read
-        __syncthreads();
-    }
-};
-
-// Block GEMM, third generation: the DirectGemm data path with a ring of FOUR stages of 32 k
-// each (instead of two of 64), so that loads are issued three stages (1.5 K steps of 64)
-// before their data is multiplied.  Measured on this chip the L2 delivers about 30 bytes
-// per clock per CU, which for a 256 x 256 tile is the same time as the tile's MFMAs: with
-// both units near saturation the L2 queues are long (over 1500 clocks), and only a deep
-// ring keeps the matrix cores fed.
-//
-//   A stage [BM][32 k] : rows of 64 bytes; 16-byte slot c of row r sits at position
-//                        c ^ ((r >> 2) & 3) (rows r, r+4, r+8, r+12 share banks);
-//   B stage [32 k][BH] : as in DirectGemm.
 //
 // Step s multiplies stage s & 3 in two sub-steps of 16 k:
 //   sub-step 0: MFMAs on f[0]; reads the fragments of sub-step 1 into f[1]; issues the
@@ -245,6 +30,13 @@ struct DirectGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
 // After the barrier of step s every wave is done reading stage s & 3 and every wave's part
 // of stage (s + 1) & 3 is in LDS; the stage written after it, (s + 4) & 3 = s & 3, is
 // written by loads issued in step s + 1, i.e. after the barrier.
+#pragma once
+#include "ffuse_gemm0.h"
+
+namespace ffuse {
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
 template <typename T, bool GATED, int BM, int BH, int WM, int WN>
 struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     typedef FirstGemm<T, GATED, BM, BH, WM, WN> Base;

@@ -50,24 +50,26 @@ struct ExchangeArgs {
     uint64_t* stats;  // nullptr, or 4 words per workgroup: role, total ticks, waiting ticks, items
 };
 
-struct SmallMArgs {
+struct TwoPhaseArgs {
     const void* X;
     const void* W1;
     const void* W3;   // nullptr: not gated
     const void* W2;
     void* H;          // [M][N1] intermediate in the operand type (L2 / Infinity Cache resident)
-    float* part;      // fp32 partial sums [splits][M][N2], fully overwritten
+    void* Y;          // [M][N2] output, written by the kernel itself when splits == 1
+    float* part;      // splits > 1: fp32 partial sums [splits][M][N2], fully overwritten
     uint32_t* flags;  // [0] barrier arrivals, [1] exits, [2] error; [0..1] zero on entry and on exit
     int64_t M;
     int K, N1, N2;
     int act;
-    int splits;       // ranges of the hidden dimension summed per output element
+    int splits;       // ranges of the hidden dimension summed per output element (>= 1)
     int ksplit;       // hidden columns per range (multiple of 64)
+    int raster;       // row blocks per XCD patch (>= 1)
     uint64_t* stats;  // nullptr, or 4 words per workgroup: ticks of phase 1, barrier, phase 2
 };
 
 // 16-bit paths (dtype 0 = bf16, 1 = fp16)
-hipError_t launch_fused_small_m(int dtype, const SmallMArgs& a, int bm, int grid, hipStream_t st);
+hipError_t launch_fused_two_phase(int dtype, const TwoPhaseArgs& a, int bm, int grid, hipStream_t st);
 hipError_t launch_finalize_planes(int dtype, const float* part, void* Y, int64_t count, int planes, hipStream_t st);
 hipError_t launch_fused_exchange(int dtype, const ExchangeArgs& a, int wgs_per_group, hipStream_t st);
 hipError_t launch_fused_reduce(int dtype, const FusedArgs& a, int bm, int bh, hipStream_t st);

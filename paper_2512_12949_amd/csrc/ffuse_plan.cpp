@@ -48,8 +48,8 @@ bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t 
             return fused_reduce_tile_ok(gated, p.bm, p.bh) && p.raster >= 1;
         case FFUSE_FAMILY_TWOPHASE: {
             if (dtype == FFUSE_DT_F32) return false;
-            SmallMGeometry sg;
-            return small_m_geometry(p, M, N1, N2, &sg);
+            TwoPhaseGeometry sg;
+            return two_phase_geometry(p, M, N1, N2, &sg);
         }
         case FFUSE_FAMILY_EXCHANGE: {
             if (dtype == FFUSE_DT_F32) return false;
@@ -78,14 +78,23 @@ bool exchange_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, 
     return true;
 }
 
-bool small_m_geometry(const ffuse_plan_t& p, int64_t M, int64_t N1, int64_t N2, SmallMGeometry* g) {
-    if (M > 128) return false;
-    g->bm = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
-    int splits = p.splits > 0 ? p.splits : 8;
+int two_phase_max_splits(int64_t M) { return M <= 128 ? 32 : (M <= 512 ? 8 : (M <= 1024 ? 4 : (M <= 2048 ? 2 : 1))); }
+
+bool two_phase_geometry(const ffuse_plan_t& p, int64_t M, int64_t N1, int64_t N2, TwoPhaseGeometry* g) {
+    // rows per block: the plan's, or the smallest block that holds all rows, or 128 / 256
+    int bm = p.bm;
+    if (bm <= 0) bm = M <= 32 ? 32 : (M <= 64 ? 64 : (M <= 512 ? 128 : 256));
+    if (bm != 32 && bm != 64 && bm != 128 && bm != 256) return false;
+    if (bm < 128 && M > bm) return false;   // the small blocks are for a single row block
+    g->bm = bm;
+    const int64_t mb = (M + bm - 1) / bm;
+    g->raster = p.raster > 0 ? p.raster : 1;
+    if (g->raster > mb) g->raster = (int)mb;
+    int splits = p.splits > 0 ? p.splits : (M <= 128 ? 8 : 1);
     if (splits > 32) return false;
     g->ksplit = (int)(((N1 + splits - 1) / splits + 63) / 64 * 64);
     g->splits = (int)((N1 + g->ksplit - 1) / g->ksplit);
-    g->ysum_bytes = ((size_t)4 * M * N2 * g->splits + 255) & ~(size_t)255;
+    g->ysum_bytes = g->splits > 1 ? (((size_t)4 * M * N2 * g->splits + 255) & ~(size_t)255) : 0;
     g->h_bytes = ((size_t)2 * M * N1 + 255) & ~(size_t)255;
     g->ws_bytes = g->ysum_bytes + g->h_bytes + 256;
     return true;
@@ -134,8 +143,8 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         t->acc_regs = g * (bh / 32.0) * (bm / 128.0) * 16.0;
         t->feasible = t->lds_used <= d.lds_bytes && t->acc_regs <= d.acc_regs;
     } else if (p.family == FFUSE_FAMILY_TWOPHASE) {
-        SmallMGeometry sg;
-        t->feasible = small_m_geometry(p, M, N1, N2, &sg) ? 1 : 0;
+        TwoPhaseGeometry sg;
+        t->feasible = two_phase_geometry(p, M, N1, N2, &sg) ? 1 : 0;
         if (t->feasible) {
             const double bh1 = gated ? 128.0 : 256.0;
             const double bm = sg.bm, ns = cdiv(n1, bh1), items = cdiv(n2, 256) * sg.splits;
@@ -216,22 +225,33 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
     const double launches = 2.0;  // main kernel + finalise / second GEMM / zero fill
     t->t_pred = worst + launches * d.launch_s;
     if (p.family == FFUSE_FAMILY_TWOPHASE && t->feasible) {
-        // two streaming phases back to back.  A workgroup of this kernel keeps ~64 KB in flight
-        // and sustains ~25 GB/s on its own (measured), so a phase with few work items is
-        // bounded by items x 25 GB/s rather than by HBM; every item also pays ~3 us of
-        // pipeline fill and epilogue.  Fixed: launch, one device-wide barrier, finalize (~25 us).
-        SmallMGeometry sg;
-        small_m_geometry(p, M, N1, N2, &sg);
+        // two phases back to back, each the longer of its streaming time and its matrix time.
+        // Streaming: a workgroup of this kernel keeps ~64 KB in flight and sustains ~25 GB/s on
+        // its own (measured), so a phase with few work items is bounded by items x 25 GB/s
+        // rather than by HBM; every item also pays ~3 us of pipeline fill and epilogue.  A
+        // weight slice is fetched once per XCD patch of `raster` row blocks: the first fetch
+        // comes from HBM, repeats (and the rows, once per slice group) from the Infinity Cache.
+        // Fixed: launch, one device-wide barrier, finalize (~25 us).
+        TwoPhaseGeometry sg;
+        two_phase_geometry(p, M, N1, N2, &sg);
         const double per_wg = 25e9, bh1 = gated ? 128.0 : 256.0;
-        const double n_s = cdiv(n1, bh1), items = cdiv(n2, 256) * sg.splits;
+        const double mb = cdiv(m, sg.bm), patches = cdiv(mb, sg.raster);
+        const double n_s = cdiv(n1, bh1), ncb = cdiv(n2, 256);
+        const double items1 = mb * n_s, items = mb * ncb * sg.splits;
         const double b1 = e * g * k * n1, b2 = e * n1 * n2;
-        const double t1 = b1 / std::min(d.hbm_bw, std::min(n_s, (double)d.cus) * per_wg) + 3e-6 * cdiv(n_s, d.cus);
-        const double t2 = b2 / std::min(d.hbm_bw, std::min(items, (double)d.cus) * per_wg) + 3e-6 * cdiv(items, d.cus);
-        const double planes = 2.0 * 4.0 * m * n2 * sg.splits / d.fabric_bw;
-        // matrix-core time of each phase: items run one per CU, at the main loop's efficiency
-        const double f_cu = d.mfma_flops * d.mfma_eff / d.cus;
-        const double m1 = 2.0 * sg.bm * bh1 * g * k / f_cu * cdiv(n_s, d.cus);
+        const double cols_per_patch = std::max(1.0, 32.0 / std::min(mb, (double)sg.raster));
+        const double re1 = b1 * (patches - 1.0) + e * m * k * std::max(0.0, n_s / cols_per_patch / 8.0 - 1.0);
+        const double re2 = b2 * (patches - 1.0) + e * m * n1 * std::max(0.0, ncb / cols_per_patch / 8.0 - 1.0) + e * m * n1;
+        const double t1 = b1 / std::min(d.hbm_bw, std::min(items1, (double)d.cus) * per_wg) + re1 / d.fabric_bw + 3e-6 * cdiv(items1, d.cus);
+        const double t2 = b2 / std::min(d.hbm_bw, std::min(items, (double)d.cus) * per_wg) + re2 / d.fabric_bw + 3e-6 * cdiv(items, d.cus);
+        const double planes = sg.splits > 1 ? 2.0 * 4.0 * m * n2 * sg.splits / d.fabric_bw : 0.0;
+        // matrix-core time of each phase: items run one per CU, at the block GEMM's efficiency
+        // (the 256-row LDS-direct GEMM vs the register-staged one with four waves in a row)
+        const double f_cu = d.mfma_flops * (sg.bm == 256 ? 0.48 : 0.33) / d.cus;
+        const double m1 = 2.0 * sg.bm * bh1 * g * k / f_cu * cdiv(items1, d.cus);
         const double m2 = 2.0 * sg.bm * 256.0 * sg.ksplit / f_cu * cdiv(items, d.cus);
+        t->workgroups = d.cus;
+        t->fabric_bytes = b1 + b2 + re1 + re2;
         t->t_hbm = t1 + t2;
         t->t_mfma = m1 + m2;
         t->t_pred = std::max(t1, m1) + std::max(t2, m2) + planes + 25e-6;
@@ -270,18 +290,28 @@ void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1
             if (t.t_pred < best_t) { best_t = t.t_pred; best = p; }
         }
     }
-    if (M <= 128) {
-        static const int splits[] = {2, 4, 8, 16, 32};
-        for (int sp : splits) {
-            ffuse_plan_t p;
-            std::memset(&p, 0, sizeof(p));
-            p.family = FFUSE_FAMILY_TWOPHASE;
-            p.bm = M <= 32 ? 32 : (M <= 64 ? 64 : 128); p.bh = 128; p.bn2 = 128; p.bk = 64; p.h_level = 2; p.raster = 1;
-            p.splits = sp;
-            ffuse_traffic_t t;
-            traffic_model(p, dtype, gated, M, K, N1, N2, &t);
-            if (!t.feasible) continue;
-            if (t.t_pred < best_t) { best_t = t.t_pred; best = p; }
+    {
+        static const int splits[] = {1, 2, 4, 8, 16, 32};
+        static const int bms[] = {32, 64, 128, 256};
+        static const int rasters2[] = {4, 2, 8, 1};   // the model does not tell these apart: measured order of preference
+        for (int bm : bms) {
+            if (bm < 128 && M > bm) continue;                 // the small blocks hold all rows or are not used
+            if (bm > 32 && M <= bm / 2) continue;             // more than half a block of padding
+            for (int sp : splits) {
+                if (sp > two_phase_max_splits(M)) continue;
+                for (int r : rasters2) {
+                    if (r > 1 && r > (M + bm - 1) / bm) continue;   // a patch cannot have more row blocks than there are
+                    ffuse_plan_t p;
+                    std::memset(&p, 0, sizeof(p));
+                    p.family = FFUSE_FAMILY_TWOPHASE;
+                    p.bm = bm; p.bh = gated ? 128 : 256; p.bn2 = 256; p.bk = 64; p.h_level = 2; p.raster = r;
+                    p.splits = sp;
+                    ffuse_traffic_t t;
+                    traffic_model(p, dtype, gated, M, K, N1, N2, &t);
+                    if (!t.feasible) continue;
+                    if (t.t_pred < best_t) { best_t = t.t_pred; best = p; }
+                }
+            }
         }
     }
     static const int producers[] = {8, 12, 16, 20, 24};

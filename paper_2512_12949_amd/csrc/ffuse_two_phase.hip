@@ -1,0 +1,230 @@
+// Fused chain, "two-phase" family: ONE persistent kernel, two phases separated by ONE
+// device-wide barrier; the intermediate is exchanged through the shared cache levels (the
+// per-XCD L2s and the 256 MB Infinity Cache behind them) in the operand type.
+//
+//   phase 1: work items (row block of BM rows, hidden slice of BH1 columns); each computes,
+//            with K complete, H[rows, slice] = act(X W1[:, slice]) [.* X W3[:, slice]];
+//   barrier : every workgroup has published its tiles (agent-scope release / acquire, once);
+//   phase 2: work items (row block, 256 output columns, one of `splits` ranges of the hidden
+//            dimension); each multiplies its part of H with its W2 block.  With splits == 1
+//            the tile goes straight to Y; otherwise every range stores its partial tile into
+//            its own fp32 plane and `finalize_planes_kernel` sums the planes in a fixed order
+//            and converts to Y (deterministic, nothing has to be zeroed).
+//
+// In the paper's terms (Sec. 4.1) this is the "shuffle" strategy with the whole device as
+// the cluster, followed (for splits > 1) by a small "reduce" with cls_reduce = splits whose
+// volume, 4 M N2 splits bytes, is negligible next to the weights when M is small.  Splitting
+// the hidden dimension all the way (the reduce family) would cost 4 M N2 (N1/128) bytes of
+// atomics: more than the weights themselves at M = 64.
+//
+// Rows are blocked by BM = 32, 64, 128 (all four waves along the columns, register-staged
+// block GEMM with two stages in flight: the weight-streaming regime) or 256 (2 x 2 waves,
+// LDS-direct block GEMM: the compute-bound regime).
+//
+// Work items are dealt to workgroups XCD by XCD (blockIdx % 8 is the XCD): the items in
+// flight on one XCD form a patch of `raster` row blocks x consecutive slices, so that a
+// weight slice is fetched into that XCD's L2 once for all the row blocks of the patch.
+#include "ffuse_gemm1.h"
+#include "ffuse_launch.h"
+#include <cstdlib>
+
+namespace ffuse {
+
+static constexpr uint32_t kBarrierSpinLimit = 1u << 24;
+
+// item `idx` of XCD `xcd` -> (row block i, slice s); false past the XCD's share
+__device__ __forceinline__ bool map_item(int MB, int S, int raster, int xcd, int idx, int& i, int& s) {
+    const int total = MB * S;
+    const int per = (total + 7) / 8;
+    const int v = xcd * per + idx;
+    if (idx >= per || v >= total) return false;
+    const int panel = v / (raster * S);
+    const int rem = v - panel * raster * S;
+    const int rows = min(raster, MB - panel * raster);
+    i = panel * raster + rem % rows;
+    s = rem / rows;
+    return true;
+}
+
+template <typename T, bool GATED, int BM> struct TwoPhaseGemms {
+    // 32 KB of weights per K step in either phase: enough bytes in flight per CU to stream HBM
+    static constexpr int BH1 = GATED ? 128 : 256;
+    typedef FirstGemm<T, GATED, BM, BH1, 1, 4> G1;   // phase 1: X * W1 (, X * W3)
+    typedef FirstGemm<T, false, BM, 256, 1, 4> G2;   // phase 2: H * W2
+    static constexpr bool DEEP = false;
+};
+template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 256> {
+    static constexpr int BH1 = GATED ? 128 : 256;
+    typedef DeepGemm<T, GATED, 256, BH1, 2, 2> G1;
+    typedef DeepGemm<T, false, 256, 256, 2, 2> G2;
+    static constexpr bool DEEP = true;
+};
+
+template <typename T, bool GATED, int BM>
+__global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
+    typedef TwoPhaseGemms<T, GATED, BM> TG;
+    typedef typename TG::G1 G1;
+    typedef typename TG::G2 G2;
+    constexpr int BH1 = TG::BH1, BH2 = 256;
+    constexpr int LDS_BYTES = G1::LDS_BYTES > G2::LDS_BYTES ? G1::LDS_BYTES : G2::LDS_BYTES;
+    __shared__ __attribute__((aligned(16))) char smem[LDS_BYTES];
+    __shared__ uint32_t verdict;
+    const int tid = threadIdx.x;
+    const int G = gridDim.x, GX = G >> 3;             // workgroups, workgroups per XCD
+    const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
+    const int MB = (int)((a.M + BM - 1) / BM);
+    uint64_t t0 = 0, t1 = 0, t2 = 0;
+    if (a.stats) t0 = wall_clock64();
+
+    // ---------------------------------------------------------------- phase 1
+    {
+        f32x16 acc[G1::HT][G1::MT];
+        f32x16 acc3[GATED ? G1::HT : 1][GATED ? G1::MT : 1];
+        typename G1::Ctx c;
+        G1::init_lds(c, tid);
+        const int NS = (a.N1 + BH1 - 1) / BH1;
+        int rb, s;
+        for (int idx = loc; map_item(MB, NS, a.raster, xcd, idx, rb, s); idx += GX) {
+            G1::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)rb * BM, (uint32_t)a.K, a.K, tid);
+            G1::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1, (uint32_t)s * BH1, tid);
+            if constexpr (TG::DEEP) G1::run(smem, c, 0, a.K, acc, acc3, tid);
+            else G1::run_deep(smem, c, 0, a.K, acc, acc3, tid);
+            G1::store_tile_lds_rt(smem, a.act, acc, acc3, reinterpret_cast<char*>(a.H), a.N1, (int64_t)rb * BM, s * BH1, a.M, a.N1, tid);
+            __syncthreads();   // LDS is free again before the next item's loads
+        }
+    }
+
+    if (a.stats) t1 = wall_clock64();
+    // ---------------------------------------------------------------- device-wide barrier
+    // bounded: on expiry the error word is set and every workgroup leaves
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t ok = 1;
+        __hip_atomic_fetch_add(a.flags, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t spins = 0;
+        while (__hip_atomic_load(a.flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)G) {
+            __builtin_amdgcn_s_sleep(2);
+            if ((++spins & 1023u) == 0 &&
+                (spins > kBarrierSpinLimit || __hip_atomic_load(a.flags + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+                __hip_atomic_fetch_or(a.flags + 2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
+                break;
+            }
+        }
+        verdict = ok;
+    }
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    const bool ok = verdict != 0;
+    if (a.stats) t2 = wall_clock64();
+
+    // ---------------------------------------------------------------- phase 2
+    if (ok) {
+        f32x16 acc[G2::HT][G2::MT];
+        f32x16 acc3[1][1];
+        typename G2::Ctx c;
+        G2::init_lds(c, tid);
+        const int NCB = (a.N2 + BH2 - 1) / BH2;
+        const int wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
+        const int wm = wave % (BM == 256 ? 2 : 1), wn = wave / (BM == 256 ? 2 : 1);
+        int rb, u;
+        // slices of this phase: u = range * NCB + column block, so that neighbours share their part of H
+        for (int idx = loc; map_item(MB, NCB * a.splits, a.raster, xcd, idx, rb, u); idx += GX) {
+            const int cb = u % NCB, sp = u / NCB;
+            const int k0 = sp * a.ksplit, k1 = min(a.N1, k0 + a.ksplit);
+            G2::init_a(c, a.H, (uint32_t)((uint64_t)a.M * a.N1 * 2), 0u, (uint32_t)rb * BM, (uint32_t)a.N1, a.N1, tid);
+            G2::init_b(c, a.W2, nullptr, (uint32_t)((uint64_t)a.N1 * a.N2 * 2), (uint32_t)a.N2, (uint32_t)a.N2, (uint32_t)cb * BH2, tid);
+            if constexpr (TG::DEEP) G2::run(smem, c, k0, k1, acc, acc3, tid);
+            else G2::run_deep(smem, c, k0, k1, acc, acc3, tid);
+            if (a.splits == 1) {
+                G2::template store_tile_lds<ACT_IDENTITY>(smem, acc, acc3, reinterpret_cast<char*>(a.Y), a.N2, (int64_t)rb * BM,
+                                                          cb * BH2, a.M, a.N2, tid);
+                __syncthreads();
+                continue;
+            }
+            // acc[ht][mt][4q..4q+3]: row wm*WMR + 32*mt + x, columns wn*WHR + 32*ht + 8*q + 4*h + 0..3 of the tile
+            // -> one 16-byte store into this range's own partial-sum plane (no atomics: the
+            //    planes are summed in a fixed order by the finalize pass)
+            float* plane = a.part + (size_t)sp * (size_t)a.M * a.N2;
+#pragma unroll
+            for (int ht = 0; ht < G2::HT; ++ht)
+#pragma unroll
+                for (int mt = 0; mt < G2::MT; ++mt) {
+                    const int64_t row = (int64_t)rb * BM + wm * G2::WMR + 32 * mt + x;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int col = cb * BH2 + wn * G2::WHR + 32 * ht + 8 * q + 4 * h;
+                        if (row < a.M && col < a.N2) {
+                            f32x4 v = {acc[ht][mt][4 * q], acc[ht][mt][4 * q + 1], acc[ht][mt][4 * q + 2], acc[ht][mt][4 * q + 3]};
+                            *reinterpret_cast<f32x4*>(plane + row * a.N2 + col) = v;
+                        }
+                    }
+                }
+        }
+    }
+
+    if (a.stats && tid == 0) {
+        uint64_t* p = a.stats + 4 * blockIdx.x;
+        p[0] = t1 - t0; p[1] = t2 - t1; p[2] = wall_clock64() - t2; p[3] = 1;
+    }
+    // ---------------------------------------------------------------- leave the flags clean
+    // the last workgroup to get here resets the barrier counter for the next launch
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t prev = __hip_atomic_fetch_add(a.flags + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (prev == (uint32_t)G - 1u) {
+            __hip_atomic_store(a.flags, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(a.flags + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// Y = sum over planes (fixed order) of fp32 partial sums, rounded once to the operand type.
+template <typename T> __global__ __launch_bounds__(256) void finalize_planes_kernel(const float* __restrict__ part, void* __restrict__ Y,
+                                                                                 int64_t n8, int64_t plane_elems, int planes) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
+    for (int p = 0; p < planes; ++p) {
+        const f32x4* q = reinterpret_cast<const f32x4*>(part + (size_t)p * plane_elems) + 2 * i;
+        s0 += q[0];
+        s1 += q[1];
+    }
+    u32x4 o;
+    o[0] = pack2<T>(s0[0], s0[1]);
+    o[1] = pack2<T>(s0[2], s0[3]);
+    o[2] = pack2<T>(s1[0], s1[1]);
+    o[3] = pack2<T>(s1[2], s1[3]);
+    reinterpret_cast<u32x4*>(Y)[i] = o;
+}
+
+hipError_t launch_finalize_planes(int dtype, const float* part, void* Y, int64_t count, int planes, hipStream_t st) {
+    const int64_t n8 = count / 8;
+    const int blocks = (int)((n8 + 255) / 256);
+    if (dtype == 0)
+        hipLaunchKernelGGL(finalize_planes_kernel<__bf16>, dim3(blocks), dim3(256), 0, st, part, Y, n8, count, planes);
+    else
+        hipLaunchKernelGGL(finalize_planes_kernel<_Float16>, dim3(blocks), dim3(256), 0, st, part, Y, n8, count, planes);
+    return hipGetLastError();
+}
+
+template <typename T, bool GATED> static const void* two_phase_fn(int bm) {
+    if (bm == 32) return (const void*)fused_two_phase_kernel<T, GATED, 32>;
+    if (bm == 64) return (const void*)fused_two_phase_kernel<T, GATED, 64>;
+    if (bm == 128) return (const void*)fused_two_phase_kernel<T, GATED, 128>;
+    if (bm == 256) return (const void*)fused_two_phase_kernel<T, GATED, 256>;
+    return nullptr;
+}
+
+hipError_t launch_fused_two_phase(int dtype, const TwoPhaseArgs& a, int bm, int grid, hipStream_t st) {
+    const bool g = a.W3 != nullptr;
+    const void* fn = dtype == 0 ? (g ? two_phase_fn<__bf16, true>(bm) : two_phase_fn<__bf16, false>(bm))
+                                : (g ? two_phase_fn<_Float16, true>(bm) : two_phase_fn<_Float16, false>(bm));
+    if (!fn || grid < 8 || (grid & 7) || a.raster < 1 || a.splits < 1) return hipErrorInvalidValue;
+    TwoPhaseArgs copy = a;
+    void* params[] = {&copy};
+    return launch_resident(fn, grid, params, st);
+}
+
+}  // namespace ffuse

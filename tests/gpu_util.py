@@ -46,8 +46,12 @@ def run(w, dev, unfused=False, plan=None):
     """Runs one workload on device tensors ``dev``; returns Y as a device tensor."""
     M = dev["X"].shape[0]
     dt = ff.DTYPE_CODE[w.dtype]
-    Workspace.ensure(max(ff.ffuse_workspace_bytes(dt, w.gated, M, w.K, w.N1, w.N2, False),
-                         ff.ffuse_workspace_bytes(dt, w.gated, M, w.K, w.N1, w.N2, True)))
+    need = max(ff.ffuse_workspace_bytes(dt, w.gated, M, w.K, w.N1, w.N2, False),
+               ff.ffuse_workspace_bytes(dt, w.gated, M, w.K, w.N1, w.N2, True))
+    if plan is not None and plan.family == ff.FAMILY_TWOPHASE:
+        # a forced plan may ask for more partial planes than the chooser would ever use
+        need = max(need, 4 * M * w.N2 * max(1, plan.splits) + 2 * M * w.N1 + 1024)
+    Workspace.ensure(need)
     Y = torch.full((M, w.N2), float("nan"), dtype=torch_dtype(w.dtype), device="cuda")
     ff.ffuse_force_plan(plan)
     try:

@@ -93,6 +93,24 @@ def test_two_phase_small_m_family(dtype, gated):
             gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase splits={splits} again")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("gated", [False, True])
+def test_two_phase_family_with_row_blocks(dtype, gated):
+    """Two-phase kernel beyond one row block: 128- and 256-row blocks, ragged last block,
+    ragged K / N1 / N2, direct output (one range) and partial planes (several ranges), every
+    raster, more work items than workgroups."""
+    act = ACT_SILU if gated else ACT_GELU_TANH
+    for (M, K, N1, N2) in [(300, 200, 840, 264), (1000, 136, 1304, 520), (2600, 72, 520, 776)]:
+        w, host, dev = _case("blocks", M, K, N1, N2, dtype, act, gated)
+        rows = inputs.sample_rows(M, 128, 24, seed=5)
+        ref = gu.oracle_rows(w, host, rows)
+        for bm, splits, raster in ((128, 1, 1), (128, 3, 2), (256, 1, 4), (256, 2, 8)):
+            plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, splits=splits, raster=raster)
+            print(f"two-phase {dtype} gated={gated} shape {(M, K, N1, N2)} bm={bm} splits={splits} raster={raster}", flush=True)
+            gu.check(gu.run(w, dev, plan=plan), ref, dtype, rows=rows, what=f"two-phase bm={bm} splits={splits}")
+            gu.check(gu.run(w, dev, plan=plan), ref, dtype, rows=rows, what=f"two-phase bm={bm} splits={splits} again")
+
+
 @pytest.mark.parametrize("act", [ACT_RELU, ACT_GELU_TANH, ACT_SILU, ACT_IDENTITY])
 @pytest.mark.parametrize("gated", [False, True])
 def test_activations_medium(act, gated):
