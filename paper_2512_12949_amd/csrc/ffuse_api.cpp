@@ -268,7 +268,7 @@ size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t
         const size_t ex = ffuse::kExchangeFlagBytes + (size_t)8 * ffuse::kExchangeMaxRing * 256 * (gated ? 128 : 256) * 2;
         if (ex > b) b = ex;
         // two-phase family: partial-sum planes (at the most splits the chooser uses for this M) | H | flags
-        const int sp = ffuse::two_phase_max_splits(M);
+        const int sp = ffuse::two_phase_max_splits(M, N2);
         const size_t planes = sp > 1 ? (((size_t)4 * M * N2 * sp + 255) & ~(size_t)255) : 0;
         const size_t tp = planes + (((size_t)2 * M * N1 + 255) & ~(size_t)255) + 256;
         if (tp > b) b = tp;

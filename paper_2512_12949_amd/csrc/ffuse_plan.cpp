@@ -78,7 +78,12 @@ bool exchange_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, 
     return true;
 }
 
-int two_phase_max_splits(int64_t M) { return M <= 128 ? 32 : (M <= 512 ? 8 : (M <= 1024 ? 4 : (M <= 2048 ? 2 : 1))); }
+int two_phase_max_splits(int64_t M, int64_t N2) {
+    // as many partial-sum planes as fit in 64 MiB
+    int sp = 32;
+    while (sp > 1 && (double)sp * 4.0 * (double)M * (double)N2 > 64.0 * 1024 * 1024) sp >>= 1;
+    return sp;
+}
 
 bool two_phase_geometry(const ffuse_plan_t& p, int64_t M, int64_t N1, int64_t N2, TwoPhaseGeometry* g) {
     // rows per block: the plan's, or the smallest block that holds all rows, or 128 / 256
@@ -168,7 +173,9 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
             const double bhp = gated ? 128.0 : 256.0;
             const double NP = cdiv(m, 256), NG = cdiv(NP, x.PG), gx = cdiv(NG, 8);
             const double f_cu = d.mfma_flops / d.cus;
-            const double tp = 2.0 * 256 * bhp * g * k / f_cu, tc = 2.0 * 256 * 256 * bhp / f_cu;
+            // a producer tile also pays ~12 us of epilogue, publication and pipeline refill
+            // (measured; expressed here at the full matrix rate like the rest of `padded`)
+            const double tp = 2.0 * 256 * bhp * g * k / f_cu + 12e-6 * d.mfma_eff, tc = 2.0 * 256 * 256 * bhp / f_cu;
             // per group: producers share gx*NH*PG tiles; every consumer multiplies gx*NH items;
             // the consumers start one producer tile late
             const double Tp = cdiv(gx * x.NH * x.PG, x.P) * tp, Tc = gx * x.NH * tc;
@@ -212,7 +219,8 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
     // 256x256 main loop's efficiency (measured on the m = 128 shapes)
     const double eff = p.family == FFUSE_FAMILY_SCALAR ? 1.0 : (p.family == FFUSE_FAMILY_REDUCE ? 0.67 * d.mfma_eff : d.mfma_eff);
     t->t_mfma = padded * waves / (mfma_flops * eff);
-    t->t_hbm = t->hbm_bytes / d.hbm_bw;
+    // the reduce family's kernel streams weights at well under half the HBM rate (measured at M <= 16)
+    t->t_hbm = t->hbm_bytes / (p.family == FFUSE_FAMILY_REDUCE ? 0.45 * d.hbm_bw : d.hbm_bw);
     t->t_fabric = t->fabric_bytes / d.fabric_bw;
     t->t_l2 = t->l2_bytes / d.l2_bw;
     t->t_lds = t->lds_bytes / d.lds_bw;
@@ -234,7 +242,7 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         // Fixed: launch, one device-wide barrier, finalize (~25 us).
         TwoPhaseGeometry sg;
         two_phase_geometry(p, M, N1, N2, &sg);
-        const double per_wg = 25e9, bh1 = gated ? 128.0 : 256.0;
+        const double per_wg = 25e9, bh1 = (gated || sg.bm < 256) ? 128.0 : 256.0;
         const double mb = cdiv(m, sg.bm), patches = cdiv(mb, sg.raster);
         const double n_s = cdiv(n1, bh1), ncb = cdiv(n2, 256);
         const double items1 = mb * n_s, items = mb * ncb * sg.splits;
@@ -298,13 +306,13 @@ void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1
             if (bm < 128 && M > bm) continue;                 // the small blocks hold all rows or are not used
             if (bm > 32 && M <= bm / 2) continue;             // more than half a block of padding
             for (int sp : splits) {
-                if (sp > two_phase_max_splits(M)) continue;
+                if (sp > two_phase_max_splits(M, N2)) continue;
                 for (int r : rasters2) {
                     if (r > 1 && r > (M + bm - 1) / bm) continue;   // a patch cannot have more row blocks than there are
                     ffuse_plan_t p;
                     std::memset(&p, 0, sizeof(p));
                     p.family = FFUSE_FAMILY_TWOPHASE;
-                    p.bm = bm; p.bh = gated ? 128 : 256; p.bn2 = 256; p.bk = 64; p.h_level = 2; p.raster = r;
+                    p.bm = bm; p.bh = (gated || bm < 256) ? 128 : 256; p.bn2 = 256; p.bk = 64; p.h_level = 2; p.raster = r;
                     p.splits = sp;
                     ffuse_traffic_t t;
                     traffic_model(p, dtype, gated, M, K, N1, N2, &t);

@@ -40,8 +40,8 @@ struct TwoPhaseGeometry {
     int raster;         // row blocks per XCD patch
     size_t ysum_bytes, h_bytes, ws_bytes;   // workspace layout: partial-sum planes | H | 256 bytes of flags
 };
-// most hidden-dimension ranges the chooser considers for M rows (bounds the workspace)
-int two_phase_max_splits(int64_t M);
+// most hidden-dimension ranges the chooser considers for an M x N2 output (bounds the workspace)
+int two_phase_max_splits(int64_t M, int64_t N2);
 bool two_phase_geometry(const ffuse_plan_t& p, int64_t M, int64_t N1, int64_t N2, TwoPhaseGeometry* out);
 
 bool fused_reduce_tile_ok(int gated, int bm, int bh);

@@ -47,8 +47,9 @@ __device__ __forceinline__ bool map_item(int MB, int S, int raster, int xcd, int
 }
 
 template <typename T, bool GATED, int BM> struct TwoPhaseGemms {
-    // 32 KB of weights per K step in either phase: enough bytes in flight per CU to stream HBM
-    static constexpr int BH1 = GATED ? 128 : 256;
+    // hidden slices of 128 columns: with few rows the first phase is a weight stream, and
+    // narrow slices give it N1/128 work items to spread over the CUs
+    static constexpr int BH1 = 128;
     typedef FirstGemm<T, GATED, BM, BH1, 1, 4> G1;   // phase 1: X * W1 (, X * W3)
     typedef FirstGemm<T, false, BM, 256, 1, 4> G2;   // phase 2: H * W2
     static constexpr bool DEEP = false;
