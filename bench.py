@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--oracle-rows", type=int, default=0, help="rows of the CPU-baseline sample (0 = auto)")
     ap.add_argument("--plan", default="", help="force a plan: family,bm,bh[,raster[,splits[,producers[,ring]]]]")
+    ap.add_argument("--tune", type=int, default=6,
+                    help="before timing, profile the K analytically best plans on the device and use the fastest (0 = model's choice)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -71,6 +73,9 @@ def main():
         v += [0] * (7 - len(v))
         ff.ffuse_force_plan(ff.make_plan(v[0], v[1], v[2], bn2=256 if v[0] == 2 else 128, raster=v[3] or 4, splits=v[4],
                                          producers=v[5], ring=v[6]))
+    elif args.tune > 0 and w.dtype != "f32":
+        # offline step of the method (plans are fixed per M bin ahead of time): not part of the timed region
+        ff.ffuse_tune(dt, dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y, top_k=args.tune, reps=5)
     fused, unfused = ff.FUSED[w.dtype], ff.UNFUSED[w.dtype]
 
     def step(fn):
@@ -122,7 +127,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: M={w.M} K={w.K} N1={w.N1} N2={w.N2} {w.dtype} "
                                f"{ACT_NAMES[w.act]}{' gated' if w.gated else ''}",
-                   "plan": plan.as_dict()},
+                   "plan": plan.as_dict(), "plan_from": "forced" if args.plan else ("tuned top-%d" % args.tune if args.tune > 0 and w.dtype != "f32" else "model")},
         "pct_mfma_peak": 100.0 * value / MFMA_PEAK_TFLOPS,
         "roofline": roof,
         "unfused": {"ms_per_step": t_unf * 1e3, "tflops": flops / t_unf * 1e-12, "kernels_ms": k_unf * 1e3,

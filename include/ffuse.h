@@ -8,8 +8,9 @@
  *     standard:  Y = act(X * W1) * W2
  *     gated   :  Y = (act(X * W1) .* (X * W3)) * W2          (SwiGLU when act = SiLU)
  *
- * in ONE pass that keeps the M x N1 intermediate out of HBM, and, for comparison, as a
- * plain unfused two-GEMM path whose intermediate round-trips through a workspace.
+ * in ONE kernel that exchanges the M x N1 intermediate through the on-chip cache levels
+ * (or, in the reduce family, never lets it leave the register file), and, for comparison, as
+ * a plain unfused two-GEMM path of two launches.
  *
  * Conventions (all entry points)
  *   - Every tensor is row-major and contiguous:  X[M][K], W1[K][N1], W3[K][N1], W2[N1][N2],
@@ -79,10 +80,14 @@ typedef enum {
                                  (Sec. 4.1 "shuffle" strategy, exchange through L2)         */
     FFUSE_FAMILY_UNFUSED = 3, /* two GEMM launches, intermediate in the workspace          */
     FFUSE_FAMILY_SCALAR = 4,  /* fp32 debug kernels (plain FMA, no matrix cores)            */
-    FFUSE_FAMILY_TWOPHASE = 5 /* small M: every CU computes hidden slices of the intermediate
-                                 into an L2 / Infinity-Cache resident buffer, one device-wide
-                                 barrier, then every CU multiplies it with a block of W2;
-                                 `splits` partial products per output are summed by atomics */
+    FFUSE_FAMILY_TWOPHASE = 5 /* any M: one persistent kernel; every CU computes tiles of the
+                                 intermediate into an L2 / Infinity-Cache resident buffer, one
+                                 device-wide barrier, then every CU multiplies a row block of it
+                                 with a block of W2 (Sec. 4.1 "shuffle" with the device as the
+                                 cluster).  bm = 32 / 64 / 128 (M <= bm for the first two) or
+                                 256; `splits` ranges of the hidden dimension: 1 = the tile is
+                                 stored straight to Y, > 1 = per-range fp32 planes summed in a
+                                 fixed order by a finalize pass (Sec. 4.1 "reduce")          */
 } ffuse_family_t;
 
 typedef struct {
@@ -158,12 +163,31 @@ int ffuse_traffic_model(const ffuse_plan_t* plan, int dtype, int gated, int64_t 
 int ffuse_force_plan(const ffuse_plan_t* plan);
 /* Plan used by the most recent fused call of this process. */
 int ffuse_last_plan(ffuse_plan_t* out);
-/* Blocks until `stream` is idle, then reports whether the most recent exchange-family launch
- * ran to completion: FFUSE_OK, or FFUSE_ERR_TIMEOUT if a workgroup's bounded wait for a peer
- * expired, or FFUSE_ERR_PLACEMENT if the XCD-local protocol found a workgroup on the wrong
- * XCD (the output of that call is then undefined; force coherent = 1).  Other families
- * always report OK. */
+/* Blocks until `stream` is idle, then reports whether the most recent two-phase or
+ * exchange-family launch ran to completion: FFUSE_OK, or FFUSE_ERR_TIMEOUT if a workgroup's
+ * bounded wait for a peer expired, or FFUSE_ERR_PLACEMENT if the exchange family's XCD-local
+ * protocol found a workgroup on the wrong XCD (the output of that call is then undefined;
+ * force coherent = 1).  Other families always report OK. */
 int ffuse_sync_status(void* stream);
+
+/* ---- plan table and on-device tuning (Sec. 4.3: the dynamic dimension M is covered by plans
+ *      fixed ahead of time per range of M and looked up at run time; Algorithm 2: the
+ *      analytical ranking is followed by profiling the top-k candidates on the device).
+ *      ffuse_tune runs the `top_k` analytically best plans for this problem on `stream` with
+ *      the caller's operands (one checked run, then `reps` timed ones each; Y is overwritten
+ *      with a valid result every time), records the fastest for M's bin (M <= 16, then one bin
+ *      per power of two) and returns it.  Later fused calls with the same dtype, gate, K, N1,
+ *      N2 and an M of that bin use it when it is valid for their M and fits their workspace;
+ *      otherwise, and for bins never tuned, the model's choice for the exact M is used (and
+ *      remembered).  The registered workspace bounds which candidates can run.
+ *      ffuse_plan_lookup: the plan a fused call would use now; *tuned_ms (may be NULL) is
+ *      the measured milliseconds if that plan came from ffuse_tune, else 0. ---------------- */
+int ffuse_tune(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act,
+               int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, int top_k, int reps, void* stream,
+               ffuse_plan_t* best_plan /* may be NULL */, double* best_ms /* may be NULL */);
+int ffuse_plan_lookup(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
+                      ffuse_plan_t* out, double* tuned_ms);
+int ffuse_plan_table_clear(void);
 
 /* ---- measurement aid: when enabled, the library brackets the dominant kernel of every
  *      fused / unfused call with HIP events on the call's stream.  ffuse_profile_read

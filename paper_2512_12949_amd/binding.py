@@ -23,6 +23,7 @@ EXPORTS = [
     "ffuse_ffn_unfused", "ffuse_ffn_unfused_f16", "ffuse_ffn_unfused_f32",
     "ffuse_workspace_bytes", "ffuse_set_workspace", "ffuse_choose_plan", "ffuse_traffic_model",
     "ffuse_force_plan", "ffuse_last_plan", "ffuse_sync_status", "ffuse_profile_enable", "ffuse_profile_read",
+    "ffuse_tune", "ffuse_plan_lookup", "ffuse_plan_table_clear",
     "ffuse_status_string", "ffuse_version",
 ]
 
@@ -88,6 +89,12 @@ def lib():
         L.ffuse_profile_enable.argtypes = [ci]
         L.ffuse_profile_read.restype = ci
         L.ffuse_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+        L.ffuse_tune.restype = ci
+        L.ffuse_tune.argtypes = [ci, vp, vp, vp, vp, ci, i64, i64, i64, i64, vp, ci, ci, vp, ctypes.POINTER(Plan),
+                                 ctypes.POINTER(ctypes.c_double)]
+        L.ffuse_plan_lookup.restype = ci
+        L.ffuse_plan_lookup.argtypes = [ci, ci, ci, i64, i64, i64, i64, ctypes.POINTER(Plan), ctypes.POINTER(ctypes.c_double)]
+        L.ffuse_plan_table_clear.restype = ci
         L.ffuse_status_string.restype = ctypes.c_char_p
         L.ffuse_status_string.argtypes = [ci]
         L.ffuse_version.restype = ci
@@ -194,6 +201,28 @@ def ffuse_sync_status(stream=None, check=True):
     if check:
         _check(rc, "ffuse_sync_status")
     return rc
+
+
+def ffuse_tune(dtype, X, W1, W3, W2, act, Y, top_k=6, reps=5, stream=None):
+    """Returns (plan, milliseconds) of the fastest of the top_k modelled plans, now in the plan table."""
+    M, K = X.shape
+    N1, N2 = W2.shape
+    p, ms = Plan(), ctypes.c_double()
+    _check(lib().ffuse_tune(int(dtype), _ptr(X), _ptr(W1), _ptr(W3), _ptr(W2), int(act), M, K, N1, N2, _ptr(Y),
+                            int(top_k), int(reps), _stream(stream), ctypes.byref(p), ctypes.byref(ms)), "ffuse_tune")
+    return p, ms.value
+
+
+def ffuse_plan_lookup(dtype, act, gated, M, K, N1, N2):
+    """Returns (plan, tuned_ms): the plan a fused call would use now; tuned_ms is 0 for a modelled plan."""
+    p, ms = Plan(), ctypes.c_double()
+    _check(lib().ffuse_plan_lookup(int(dtype), int(act), int(bool(gated)), M, K, N1, N2, ctypes.byref(p), ctypes.byref(ms)),
+           "ffuse_plan_lookup")
+    return p, ms.value
+
+
+def ffuse_plan_table_clear():
+    _check(lib().ffuse_plan_table_clear(), "ffuse_plan_table_clear")
 
 
 def ffuse_profile_enable(on: bool):

@@ -5,7 +5,9 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
+#include <array>
 #include <cstring>
+#include <map>
 #include <mutex>
 #include <vector>
 
@@ -35,6 +37,14 @@ struct State {
     uint64_t* gemm_stats = nullptr;
     uint64_t* small_stats = nullptr;
     int exch_wgs = 0;
+    // plan table (Sec. 4.3: plans are fixed ahead of time per range of the dynamic dimension M
+    // and looked up at run time).  Key: dtype, gated, K, N1, N2 and either the M bin (plans
+    // measured by ffuse_tune) or, negated, the exact M (plans chosen by the model).
+    struct TableEntry {
+        ffuse_plan_t plan;
+        double ms;        // measured time of a tuned plan; 0 for a modelled one
+    };
+    std::map<std::array<int64_t, 6>, TableEntry> table;
 };
 State g;
 
@@ -105,6 +115,30 @@ struct Timer {  // brackets the dominant kernel with events when profiling is on
     }
 };
 
+std::array<int64_t, 6> table_key(int dtype, int gated, int64_t K, int64_t N1, int64_t N2, int64_t m_or_bin) {
+    return {dtype, gated, K, N1, N2, m_or_bin};
+}
+
+// a0: the plan for this call -- a tuned plan of M's bin if there is one that fits, else the
+// model's choice for exactly this M (computed once, then looked up)
+ffuse_plan_t lookup_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
+    auto it = g.table.find(table_key(dtype, gated, K, N1, N2, ffuse::m_bin(M)));
+    if (it != g.table.end() && ffuse::plan_valid(it->second.plan, dtype, gated, M, K, N1, N2) &&
+        ffuse::plan_workspace_bytes(it->second.plan, dtype, gated, M, K, N1, N2) <= g.ws_bytes)
+        return it->second.plan;
+    const auto key = table_key(dtype, gated, K, N1, N2, -M);
+    it = g.table.find(key);
+    if (it != g.table.end()) return it->second.plan;
+    ffuse_plan_t plan;
+    ffuse::choose_plan(dtype, act, gated, M, K, N1, N2, &plan);
+    if (g.table.size() > 4096) g.table.clear();
+    g.table[key] = {plan, 0.0};
+    return plan;
+}
+
+int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act,
+             int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
+
 int run_fused(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
               int64_t N1, int64_t N2, void* Y, void* stream) {
     const int elem = dtype == FFUSE_DT_F32 ? 4 : 2;
@@ -120,8 +154,15 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
         plan = g.forced_plan;
         if (!ffuse::plan_valid(plan, dtype, gated, M, K, N1, N2) || plan.family == FFUSE_FAMILY_UNFUSED) return FFUSE_ERR_PLAN;
     } else {
-        ffuse::choose_plan(dtype, act, gated, M, K, N1, N2, &plan);
+        plan = lookup_plan(dtype, act, gated, M, K, N1, N2);
     }
+    return run_plan(plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+}
+
+// launches one validated plan; the caller holds the lock
+int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act,
+             int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream) {
+    const int gated = W3 != nullptr;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     ffuse::FusedArgs a{X, W1, W3, W2, nullptr, M, (int)K, (int)N1, (int)N2, act, plan.raster > 0 ? plan.raster : 1};
     if (plan.family == FFUSE_FAMILY_SCALAR) {
@@ -374,6 +415,85 @@ int ffuse_sync_status(void* stream) {
     }
     if (word & 2u) return FFUSE_ERR_PLACEMENT;
     return word ? FFUSE_ERR_TIMEOUT : FFUSE_OK;
+}
+
+// Sec. 4.3, Algorithm 2, second half: time the analytically best `top_k` plans on the device
+// and keep the fastest in the plan table for M's bin.
+int ffuse_tune(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+               int64_t N1, int64_t N2, void* Y, int top_k, int reps, void* stream, ffuse_plan_t* best_plan, double* best_ms) {
+    if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F32) return FFUSE_ERR_ACT;
+    const int elem = dtype == FFUSE_DT_F32 ? 4 : 2;
+    int rc = validate(X, W1, W3, W2, act, M, K, N1, N2, Y, elem);
+    if (rc != FFUSE_OK) return rc;
+    if (top_k < 1 || reps < 1 || top_k > 64 || reps > 1000) return FFUSE_ERR_SHAPE;
+    std::lock_guard<std::mutex> lock(g.mu);
+    rc = check_arch();
+    if (rc != FFUSE_OK) return rc;
+    const int gated = W3 != nullptr;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    std::vector<ffuse::RankedPlan> ranked;
+    ffuse::rank_plans(dtype, act, gated, M, K, N1, N2, &ranked);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return FFUSE_ERR_LAUNCH;
+    const bool was_profiling = g.profiling;
+    g.profiling = false;
+    double best = 1e30;
+    ffuse_plan_t bestp{};
+    int tried = 0, last_rc = FFUSE_ERR_WORKSPACE;
+    for (const auto& cand : ranked) {
+        if (tried >= top_k) break;
+        const ffuse_plan_t& p = cand.plan;
+        if (!ffuse::plan_valid(p, dtype, gated, M, K, N1, N2)) continue;
+        if (ffuse::plan_workspace_bytes(p, dtype, gated, M, K, N1, N2) > g.ws_bytes) continue;
+        ++tried;
+        // one untimed run, checked, then `reps` timed ones
+        last_rc = run_plan(p, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+        if (last_rc != FFUSE_OK) continue;
+        if (hipStreamSynchronize(st) != hipSuccess) { last_rc = FFUSE_ERR_LAUNCH; break; }
+        if (g.exch_err) {
+            uint32_t word = 0;
+            if (hipMemcpy(&word, g.exch_err, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess) { last_rc = FFUSE_ERR_LAUNCH; break; }
+            if (word) { last_rc = (word & 2u) ? FFUSE_ERR_PLACEMENT : FFUSE_ERR_TIMEOUT; break; }   // device state is suspect: stop
+        }
+        (void)hipEventRecord(e0, st);
+        for (int r = 0; r < reps && last_rc == FFUSE_OK; ++r) last_rc = run_plan(p, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+        (void)hipEventRecord(e1, st);
+        if (hipEventSynchronize(e1) != hipSuccess) { last_rc = FFUSE_ERR_LAUNCH; break; }
+        if (last_rc != FFUSE_OK) continue;
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        const double per = (double)ms / reps;
+        if (g.log) std::fprintf(stderr, "[ffuse] tune: family %d bm %d bh %d splits %d raster %d producers %d: model %.1f us, measured %.1f us\n",
+                                p.family, p.bm, p.bh, p.splits, p.raster, p.producers, cand.t_pred * 1e6, per * 1e3);
+        if (per < best) { best = per; bestp = p; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    g.profiling = was_profiling;
+    if (best >= 1e30) return last_rc != FFUSE_OK ? last_rc : FFUSE_ERR_PLAN;
+    g.table[table_key(dtype, gated, K, N1, N2, ffuse::m_bin(M))] = {bestp, best};
+    if (best_plan) *best_plan = bestp;
+    if (best_ms) *best_ms = best;
+    return FFUSE_OK;
+}
+
+int ffuse_plan_table_clear(void) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.table.clear();
+    return FFUSE_OK;
+}
+
+int ffuse_plan_lookup(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* out, double* tuned_ms) {
+    if (!out) return FFUSE_ERR_NULL;
+    if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F32) return FFUSE_ERR_ACT;
+    if (M < 1 || K < 8 || N1 < 8 || N2 < 8) return FFUSE_ERR_SHAPE;
+    std::lock_guard<std::mutex> lock(g.mu);
+    *out = lookup_plan(dtype, act, gated ? 1 : 0, M, K, N1, N2);
+    if (tuned_ms) {
+        auto it = g.table.find(table_key(dtype, gated ? 1 : 0, K, N1, N2, ffuse::m_bin(M)));
+        *tuned_ms = (it != g.table.end() && std::memcmp(&it->second.plan, out, sizeof(*out)) == 0) ? it->second.ms : 0.0;
+    }
+    return FFUSE_OK;
 }
 
 int ffuse_profile_enable(int on) {

@@ -266,21 +266,21 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
     }
 }
 
-// Enumerates the plans the kernels implement, discards infeasible ones and returns the one
-// with the smallest predicted time (Sec. 4.3, Algorithm 2 without the on-device profiling
-// of the top-k list).
-void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* out) {
+// Enumerates the plans the kernels implement, discards infeasible ones and ranks the rest by
+// predicted time (Sec. 4.3, Algorithm 2 up to the top-k list; the on-device profiling of that
+// list is ffuse_tune in the API layer).
+void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, std::vector<RankedPlan>* out) {
     (void)act;
+    out->clear();
     ffuse_plan_t best;
     std::memset(&best, 0, sizeof(best));
     if (dtype == FFUSE_DT_F32) {
         best.family = FFUSE_FAMILY_SCALAR;
         best.bm = 16; best.bh = 64; best.bn2 = 256; best.bk = 32; best.h_level = 1; best.raster = 1;
         best.splits = (int)((N1 + 63) / 64);
-        *out = best;
+        out->push_back({0.0, best});
         return;
     }
-    double best_t = 1e30;
     static const int tiles[][2] = {{256, 256}, {128, 256}, {256, 128}, {128, 128}, {128, 64}};
     static const int rasters[] = {1, 2, 4, 8, 16};
     for (auto& tl : tiles) {
@@ -295,7 +295,7 @@ void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1
             ffuse_traffic_t t;
             traffic_model(p, dtype, gated, M, K, N1, N2, &t);
             if (!t.feasible) continue;
-            if (t.t_pred < best_t) { best_t = t.t_pred; best = p; }
+            out->push_back({t.t_pred, p});
         }
     }
     {
@@ -317,7 +317,7 @@ void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1
                     ffuse_traffic_t t;
                     traffic_model(p, dtype, gated, M, K, N1, N2, &t);
                     if (!t.feasible) continue;
-                    if (t.t_pred < best_t) { best_t = t.t_pred; best = p; }
+                    out->push_back({t.t_pred, p});
                 }
             }
         }
@@ -332,9 +332,43 @@ void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1
         ffuse_traffic_t t;
         traffic_model(p, dtype, gated, M, K, N1, N2, &t);
         if (!t.feasible) continue;
-        if (t.t_pred < best_t) { best_t = t.t_pred; best = p; }
+        out->push_back({t.t_pred, p});
     }
-    *out = best;
+    // stable: among equal predictions the enumeration order (the measured preference) decides
+    std::stable_sort(out->begin(), out->end(), [](const RankedPlan& x, const RankedPlan& y) { return x.t_pred < y.t_pred; });
+}
+
+void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* out) {
+    std::vector<RankedPlan> r;
+    rank_plans(dtype, act, gated, M, K, N1, N2, &r);
+    if (r.empty()) {
+        std::memset(out, 0, sizeof(*out));
+        return;
+    }
+    *out = r.front().plan;
+}
+
+size_t plan_workspace_bytes(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
+    (void)K;
+    switch (p.family) {
+        case FFUSE_FAMILY_REDUCE: return sizeof(float) * (size_t)M * (size_t)N2;
+        case FFUSE_FAMILY_EXCHANGE: {
+            ExchangeGeometry e;
+            return exchange_geometry(p, gated, M, N1, N2, kDevice.cus, &e) ? e.ws_bytes : 0;
+        }
+        case FFUSE_FAMILY_TWOPHASE: {
+            TwoPhaseGeometry t;
+            return two_phase_geometry(p, M, N1, N2, &t) ? t.ws_bytes : 0;
+        }
+        case FFUSE_FAMILY_UNFUSED: return (dtype == FFUSE_DT_F32 ? 4 : 2) * (size_t)M * (size_t)N1;
+        default: return 0;
+    }
+}
+
+int m_bin(int64_t M) {
+    int b = 0;
+    for (int64_t edge = 16; edge < M; edge <<= 1) ++b;
+    return b;
 }
 
 }  // namespace ffuse

@@ -1,5 +1,6 @@
 // Host-side plan chooser / traffic model interface (no device code, no torch types).
 #pragma once
+#include <vector>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -48,6 +49,19 @@ bool fused_reduce_tile_ok(int gated, int bm, int bh);
 bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2);
 void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
                    ffuse_traffic_t* out);
+// All plans the kernels implement for this problem that pass the capacity constraints,
+// in order of increasing predicted time (Sec. 4.3, Algorithm 2: the analytical ranking that
+// precedes the on-device profiling of the top-k list).
+struct RankedPlan {
+    double t_pred;
+    ffuse_plan_t plan;
+};
+void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, std::vector<RankedPlan>* out);
 void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* out);
+// Bytes of workspace a plan needs for this problem.
+size_t plan_workspace_bytes(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2);
+// Bin of the row count for the plan table (Sec. 4.3: plans are chosen offline per range of
+// the dynamic dimension M and looked up at run time): 0 for M <= 16, then one per power of two.
+int m_bin(int64_t M);
 
 }  // namespace ffuse

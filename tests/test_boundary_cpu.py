@@ -61,3 +61,24 @@ def test_workspace_size_formula():
     assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 4096, 4096, 16384, 4096, True) == 2 * 4096 * 16384
     assert ff.ffuse_workspace_bytes(ff.DT_F32, False, 128, 256, 1024, 256, True) == 4 * 128 * 1024
     assert ff.ffuse_workspace_bytes(ff.DT_F32, False, 128, 256, 1024, 256, False) == 0
+
+
+def test_plan_lookup_without_tuning_is_the_models_choice():
+    ff.ffuse_plan_table_clear()
+    for M in (1, 16, 17, 128, 300, 4096):
+        want = ff.ffuse_choose_plan(ff.DT_BF16, 2, False, M, 4096, 16384, 4096).as_dict()
+        got, tuned_ms = ff.ffuse_plan_lookup(ff.DT_BF16, 2, False, M, 4096, 16384, 4096)
+        assert got.as_dict() == want and tuned_ms == 0.0
+        again, _ = ff.ffuse_plan_lookup(ff.DT_BF16, 2, False, M, 4096, 16384, 4096)   # now from the table
+        assert again.as_dict() == want
+    ff.ffuse_plan_table_clear()
+
+
+def test_tune_validates_before_touching_the_device():
+    import ctypes
+    L = ff.lib()
+    p, ms = ff.Plan(), ctypes.c_double()
+    rc = L.ffuse_tune(ff.DT_BF16, None, None, None, None, 2, 128, 64, 64, 64, None, 4, 3, None, ctypes.byref(p), ctypes.byref(ms))
+    assert rc == -1
+    rc = L.ffuse_tune(7, None, None, None, None, 2, 128, 64, 64, 64, None, 4, 3, None, ctypes.byref(p), ctypes.byref(ms))
+    assert rc == -4

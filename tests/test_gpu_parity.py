@@ -160,3 +160,27 @@ def test_workspace_errors_on_device():
     ff.ffuse_set_workspace(small)
     assert ff.ffuse_ffn(dev["X"], dev["W1"], None, dev["W2"], ACT_RELU, Y, check=False) == -5
     ff.ffuse_set_workspace(None)
+
+
+def test_tune_fills_the_plan_table_for_the_bin():
+    """On-device tuning: the winner is one of the modelled candidates, later calls of the same M
+    bin use it, other bins fall back to the model, and results stay within the parity bar."""
+    ff.ffuse_plan_table_clear()
+    w, host, dev = _case("tune", 200, 264, 1304, 520, "bf16", ACT_GELU_TANH, False)
+    ref = gu.oracle_rows(w, host)
+    gu.run(w, dev)                               # sizes and registers the workspace
+    Y = torch.empty((200, 520), dtype=torch.bfloat16, device="cuda")
+    plan, ms = ff.ffuse_tune(ff.DT_BF16, dev["X"], dev["W1"], None, dev["W2"], w.act, Y, top_k=5, reps=3)
+    assert ms > 0 and plan.family in (ff.FAMILY_REDUCE, ff.FAMILY_EXCHANGE, ff.FAMILY_TWOPHASE)
+    gu.check(Y, ref, "bf16", what="output left by tuning")
+    looked, tuned_ms = ff.ffuse_plan_lookup(ff.DT_BF16, w.act, False, 200, 264, 1304, 520)
+    assert looked.as_dict() == plan.as_dict() and tuned_ms == ms
+    gu.check(gu.run(w, dev), ref, "bf16", what="fused call after tuning")
+    assert ff.ffuse_last_plan().as_dict() == plan.as_dict()
+    # same bin (129..256 rows), other M: the tuned plan when it is valid there
+    looked2, _ = ff.ffuse_plan_lookup(ff.DT_BF16, w.act, False, 256, 264, 1304, 520)
+    assert looked2.as_dict() == plan.as_dict()
+    # another bin: the model's choice
+    other, other_ms = ff.ffuse_plan_lookup(ff.DT_BF16, w.act, False, 64, 264, 1304, 520)
+    assert other_ms == 0.0 and other.as_dict() == ff.ffuse_choose_plan(ff.DT_BF16, w.act, False, 64, 264, 1304, 520).as_dict()
+    ff.ffuse_plan_table_clear()
