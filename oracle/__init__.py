@@ -1,4 +1,4 @@
-"""fp64 CPU oracle for the fused FFN chain -- TEST INFRASTRUCTURE ONLY.
+"""fp64 CPU oracle for the fused FFN chain and the convolution chain -- TEST INFRASTRUCTURE ONLY.
 
 Only tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may
 import this package.  It is independent of the HIP library: no shared code, no import of
@@ -14,6 +14,7 @@ from .ffn_oracle import (  # noqa: F401
     ACT_SILU,
     act,
     build,
+    conv_chain,
     ffn,
     ffn_rows,
     num_threads,

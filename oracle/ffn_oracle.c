@@ -154,6 +154,82 @@ int orc_ffn_rows(const void* X, const void* W1, const void* W3, const void* W2, 
     return failed ? -1 : 0;
 }
 
+/* ---- convolution chains -------------------------------------------------------------
+ *
+ * The paper's second workload class (Evaluation, table "The configuration of conv chain":
+ * IC, H, W, OC1, OC2, k1, k2): two convolutions back to back with an activation between
+ * them.  As a formula, for batch b, pixel (h, w):
+ *
+ *   A[b][h][w][o] = act( sum_{kh<k1} sum_{kw<k1} sum_{ic<IC}
+ *                        X[b][h+kh-p1][w+kw-p1][ic] * W1[kh][kw][ic][o] ),      p1 = k1/2
+ *   Y[b][h][w][q] =      sum_{kh<k2} sum_{kw<k2} sum_{o<OC1}
+ *                        A[b][h+kh-p2][w+kw-p2][o] * W2[kh][kw][o][q],          p2 = k2/2
+ *
+ * with X and A read as zero outside the image.  Readings (the paper gives only the table):
+ * stride 1 and zero padding k/2, so that H x W is preserved; "convolution" is the
+ * cross-correlation of deep-learning frameworks (no kernel flip); no bias; activations
+ * channels-last (N H W C), weights [kh][kw][in][out].  With k1 = k2 = 1 this is exactly the
+ * standard chain on the M = B*H*W pixel rows.  The activation sees complete sums over
+ * (kh, kw, ic) only, as in the GEMM chain.  k1 and k2 must be odd.
+ *
+ * A_out (optional) receives the activated intermediate, B*H*W*OC1 doubles.
+ * Returns 0, or -1 on a bad argument.
+ */
+static int conv_pass(const void* in_raw, const double* in_f64, int dtype, const void* Wt, int apply_act, int act,
+                     int64_t B, int64_t H, int64_t W, int64_t CI, int64_t CO, int64_t k, double* out) {
+    const int64_t p = k / 2;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double* acc = (double*)malloc(sizeof(double) * (size_t)(CO > 0 ? CO : 1));
+        if (!acc) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(dynamic, 4)
+            for (int64_t pix = 0; pix < B * H * W; ++pix) {
+                const int64_t b = pix / (H * W), h = (pix / W) % H, w = pix % W;
+                for (int64_t o = 0; o < CO; ++o) acc[o] = 0.0;
+                for (int64_t kh = 0; kh < k; ++kh) {
+                    const int64_t hh = h + kh - p;
+                    if (hh < 0 || hh >= H) continue; /* zero padding */
+                    for (int64_t kw = 0; kw < k; ++kw) {
+                        const int64_t ww = w + kw - p;
+                        if (ww < 0 || ww >= W) continue;
+                        const int64_t src = ((b * H + hh) * W + ww) * CI;
+                        for (int64_t ci = 0; ci < CI; ++ci) {
+                            const double x = in_f64 ? in_f64[src + ci] : load_elem(in_raw, dtype, src + ci);
+                            const int64_t wrow = ((kh * k + kw) * CI + ci) * CO;
+                            for (int64_t o = 0; o < CO; ++o) acc[o] += x * load_elem(Wt, dtype, wrow + o);
+                        }
+                    }
+                }
+                for (int64_t o = 0; o < CO; ++o) out[pix * CO + o] = apply_act ? orc_act(act, acc[o]) : acc[o];
+            }
+        }
+        free(acc);
+    }
+    return failed ? -1 : 0;
+}
+
+int orc_conv_chain(const void* X, const void* W1, const void* W2, int dtype, int act, int64_t B, int64_t H,
+                   int64_t W, int64_t IC, int64_t OC1, int64_t OC2, int64_t k1, int64_t k2, double* Y,
+                   double* A_out) {
+    if (!X || !W1 || !W2 || !Y) return -1;
+    if (B < 0 || H < 0 || W < 0 || IC < 0 || OC1 < 0 || OC2 < 0) return -1;
+    if (k1 < 1 || k2 < 1 || !(k1 & 1) || !(k2 & 1)) return -1;
+    if (dtype < ORC_BF16 || dtype > ORC_F32 || act < ORC_IDENTITY || act > ORC_SILU) return -1;
+    const int64_t npix = B * H * W;
+    double* A = A_out ? A_out : (double*)malloc(sizeof(double) * (size_t)(npix * OC1 > 0 ? npix * OC1 : 1));
+    if (!A) return -1;
+    int rc = conv_pass(X, NULL, dtype, W1, 1, act, B, H, W, IC, OC1, k1, A);
+    if (rc == 0) rc = conv_pass(NULL, A, dtype, W2, 0, act, B, H, W, OC1, OC2, k2, Y);
+    if (!A_out) free(A);
+    return rc;
+}
+
 int orc_num_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();

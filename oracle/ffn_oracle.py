@@ -39,6 +39,9 @@ def _load():
         lib.orc_ffn_rows.restype = ctypes.c_int
         lib.orc_ffn_rows.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int, ctypes.c_int] + \
             [ctypes.c_int64] * 4 + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        lib.orc_conv_chain.restype = ctypes.c_int
+        lib.orc_conv_chain.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int, ctypes.c_int] + [ctypes.c_int64] * 8 + \
+            [ctypes.c_void_p, ctypes.c_void_p]
         lib.orc_act.restype = ctypes.c_double
         lib.orc_act.argtypes = [ctypes.c_int, ctypes.c_double]
         lib.orc_widen.restype = None
@@ -117,3 +120,27 @@ def ffn_rows(X, W1, W3, W2, act_kind: int, rows=None, bf16: bool = False, want_h
 
 def ffn(X, W1, W3, W2, act_kind: int, bf16: bool = False):
     return ffn_rows(X, W1, W3, W2, act_kind, None, bf16)
+
+
+def conv_chain(X, W1, W2, act_kind: int, bf16: bool = False, want_a: bool = False):
+    """``Y = conv_k2(act(conv_k1(X, W1)), W2)`` in double: stride 1, zero padding k/2,
+    cross-correlation, no bias.  X is [B][H][W][IC], W1 [k1][k1][IC][OC1], W2 [k2][k2][OC1][OC2];
+    returns Y [B][H][W][OC2] float64, or ``(Y, A)`` with the activated intermediate."""
+    X = np.ascontiguousarray(X)
+    W1 = np.ascontiguousarray(W1)
+    W2 = np.ascontiguousarray(W2)
+    B, H, W, IC = X.shape
+    k1, k1b, ICb, OC1 = W1.shape
+    k2, k2b, OC1b, OC2 = W2.shape
+    if k1 != k1b or k2 != k2b or ICb != IC or OC1b != OC1:
+        raise ValueError("shape mismatch")
+    dt = _dtype_code(X, bf16)
+    if _dtype_code(W1, bf16) != dt or _dtype_code(W2, bf16) != dt:
+        raise TypeError("operands must share one dtype")
+    Y = np.empty((B, H, W, OC2), dtype=np.float64)
+    A = np.empty((B, H, W, OC1), dtype=np.float64) if want_a else None
+    rc = _load().orc_conv_chain(_ptr(X), _ptr(W1), _ptr(W2), dt, int(act_kind), B, H, W, IC, OC1, OC2, k1, k2,
+                                _ptr(Y), _ptr(A) if want_a else None)
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return (Y, A) if want_a else Y

@@ -68,3 +68,25 @@ def test_sample_rows():
     for b in range(4):
         lo, hi = b * 256, min(1000, (b + 1) * 256)
         assert lo in r and hi - 1 in r
+
+
+def _golden_tables():
+    import os
+    rows = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "shape_tables.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                parts = line.split()
+                rows[parts[0]] = [int(v) for v in parts[1:]]
+    return rows
+
+
+def test_chain_workloads_match_the_papers_printed_tables():
+    """G1-G10 / S1-S8 (Evaluation, tables of gemm-chain and gated-FFN configurations): the
+    paper prints (m, n, k, l); the workloads use (M, K, N1, N2) = (m, k, n, l)."""
+    rows = _golden_tables()
+    for name, (m, n, k, l) in ((k_, v) for k_, v in rows.items() if k_[0] in "GS"):
+        w = inputs.WORKLOADS[name]
+        assert (w.M, w.K, w.N1, w.N2) == (m, k, n, l), name
+        assert w.gated == (name[0] == "S")
+    assert sum(1 for k_ in rows if k_[0] == "G") == 10 and sum(1 for k_ in rows if k_[0] == "S") == 8
