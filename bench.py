@@ -49,8 +49,10 @@ def main():
     from paper_2512_12949_amd import binding as ff
     from paper_2512_12949_amd import inputs
 
-    w = inputs.WORKLOADS[args.workload]
     torch.cuda.set_device(0)
+    if args.workload in inputs.CONV_WORKLOADS:
+        return conv_main(args, ff, inputs, np, torch)
+    w = inputs.WORKLOADS[args.workload]
     host = inputs.make(w)
 
     def up(a):
@@ -158,6 +160,81 @@ def main():
         torch.cuda.synchronize()
         torch.mul(src, 1.0, out=dst)
         torch.cuda.synchronize()
+    ff.ffuse_set_workspace(None)
+    print(json.dumps(out))
+
+
+def conv_main(args, ff, inputs, np, torch):
+    """Convolution-chain workloads C1..C8: same JSON line; the comparison is torch's
+    channels-last conv2d -> activation -> conv2d (the vendor library's unfused chain)."""
+    w = inputs.CONV_WORKLOADS[args.workload]
+    host = inputs.make_conv(w)
+    dev = {k: torch.from_numpy(v.view(np.int16)).view(torch.bfloat16).cuda() for k, v in host.items()}
+    M, K, N1, N2 = w.gemm_shape()
+    ws = torch.empty(max(256, ff.ffuse_workspace_bytes(ff.DT_BF16, False, M, K, N1, N2, False)), dtype=torch.uint8, device="cuda")
+    ff.ffuse_set_workspace(ws)
+    Y = torch.empty((w.B, w.H, w.W, w.OC2), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        ff.ffuse_conv_chain(dev["X"], dev["W1"], dev["W2"], w.act, Y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ff.ffuse_profile_read()
+    ff.ffuse_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_fused = (time.perf_counter() - t0) / args.steps
+    ff.ffuse_profile_enable(False)
+    kms, kn = ff.ffuse_profile_read()
+    k_fused = kms / kn * 1e-3
+    plan = ff.ffuse_last_plan()
+    # vendor-library chain on the same data (NCHW tensors in channels-last memory format)
+    x = dev["X"].permute(0, 3, 1, 2)
+    w1 = dev["W1"].permute(3, 2, 0, 1).contiguous(memory_format=torch.channels_last)
+    w2 = dev["W2"].permute(3, 2, 0, 1).contiguous(memory_format=torch.channels_last)
+
+    def torch_step():
+        return torch.nn.functional.conv2d(torch.relu(torch.nn.functional.conv2d(x, w1, padding=w.k1 // 2)), w2)
+
+    for _ in range(3):
+        yt = torch_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        yt = torch_step()
+    torch.cuda.synchronize()
+    t_torch = (time.perf_counter() - t0) / args.steps
+    diff = float((yt.permute(0, 2, 3, 1).float() - Y.float()).abs().max() / Y.float().abs().max())
+    flops = float(w.flops())
+    roof = {"bound": "hbm", "achieved": w.q_min() / k_fused * 1e-9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel_ms"] = k_fused * 1e3
+    out = {
+        "metric": "fused FFN TFLOP/s (% MFMA peak) + HBM bytes vs unfused, 1 MI355X",
+        "value": flops / t_fused * 1e-12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_fused * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: conv chain IC={w.IC} {w.H}x{w.W} OC1={w.OC1} OC2={w.OC2} k1={w.k1} k2={w.k2} "
+                               f"batch {w.B} bf16 relu", "plan": plan.as_dict(), "plan_from": "model"},
+        "roofline": roof,
+        "unfused": {"ms_per_step": t_torch * 1e3, "kind": "torch conv2d + relu + conv2d (channels-last)",
+                    "max_rel_diff_vs_fused": diff},
+        "bytes": {"q_min": w.q_min()},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        ref = oracle.conv_chain(host["X"], host["W1"], host["W2"], w.act, bf16=True)
+        t_cpu = time.perf_counter() - t0
+        got = Y.float().cpu().numpy().astype(np.float64)
+        out["cpu_baseline"] = {"value": flops / t_cpu * 1e-12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": f"the whole workload, {t_cpu:.2f} s"}
+        out["max_rel_err_vs_oracle"] = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
     ff.ffuse_set_workspace(None)
     print(json.dumps(out))
 

@@ -146,6 +146,20 @@ int ffuse_ffn_unfused_f16(const void* X, const void* W1, const void* W3, const v
 int ffuse_ffn_unfused_f32(const void* X, const void* W1, const void* W3, const void* W2, int act,
                           int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
 
+/* ---- convolution chains (Evaluation, table "The configuration of conv chain": IC, H, W,
+ *      OC1, OC2, k1, k2): Y = conv_k2(act(conv_k1(X, W1)), W2), both convolutions stride 1
+ *      with zero padding k/2 (H x W is preserved), cross-correlation, no bias.  Layouts:
+ *      X[B][H][W][IC] and Y[B][H][W][OC2] channels-last, W1[k1][k1][IC][OC1],
+ *      W2[k2][k2][OC1][OC2]; bf16 (or fp16 for the _f16 twin), device pointers as above.
+ *      Built: k2 = 1 with k1 = 1 (the standard chain on the B*H*W pixel rows, any plan) or
+ *      k1 = 3 (two-phase kernel whose first product gathers the 3x3 neighbourhood while
+ *      loading; needs IC % 64 == 0).  Other kernel sizes return FFUSE_ERR_SHAPE.  IC, OC1, OC2
+ *      multiples of 8.  Workspace: ffuse_workspace_bytes(dtype, 0, B*H*W, k1*k1*IC, OC1, OC2, 0). */
+int ffuse_conv_chain(const void* X, const void* W1, const void* W2, int act, int64_t B, int64_t H,
+                     int64_t W, int64_t IC, int64_t OC1, int64_t OC2, int k1, int k2, void* Y, void* stream);
+int ffuse_conv_chain_f16(const void* X, const void* W1, const void* W2, int act, int64_t B, int64_t H,
+                         int64_t W, int64_t IC, int64_t OC1, int64_t OC2, int k1, int k2, void* Y, void* stream);
+
 /* ---- workspace.  ffuse_workspace_bytes: bytes the given problem needs (fused path when
  *      unfused == 0).  ffuse_set_workspace: registers a caller-owned device buffer with the
  *      library (it is zero-filled once on `stream`); passing NULL unregisters it. --------- */

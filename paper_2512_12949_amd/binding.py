@@ -23,7 +23,7 @@ EXPORTS = [
     "ffuse_ffn_unfused", "ffuse_ffn_unfused_f16", "ffuse_ffn_unfused_f32",
     "ffuse_workspace_bytes", "ffuse_set_workspace", "ffuse_choose_plan", "ffuse_traffic_model",
     "ffuse_force_plan", "ffuse_last_plan", "ffuse_sync_status", "ffuse_profile_enable", "ffuse_profile_read",
-    "ffuse_tune", "ffuse_plan_lookup", "ffuse_plan_table_clear",
+    "ffuse_tune", "ffuse_plan_lookup", "ffuse_plan_table_clear", "ffuse_conv_chain", "ffuse_conv_chain_f16",
     "ffuse_status_string", "ffuse_version",
 ]
 
@@ -95,6 +95,10 @@ def lib():
         L.ffuse_plan_lookup.restype = ci
         L.ffuse_plan_lookup.argtypes = [ci, ci, ci, i64, i64, i64, i64, ctypes.POINTER(Plan), ctypes.POINTER(ctypes.c_double)]
         L.ffuse_plan_table_clear.restype = ci
+        for name in ("ffuse_conv_chain", "ffuse_conv_chain_f16"):
+            f = getattr(L, name)
+            f.restype = ci
+            f.argtypes = [vp, vp, vp, ci, i64, i64, i64, i64, i64, i64, ci, ci, vp, vp]
         L.ffuse_status_string.restype = ctypes.c_char_p
         L.ffuse_status_string.argtypes = [ci]
         L.ffuse_version.restype = ci
@@ -223,6 +227,25 @@ def ffuse_plan_lookup(dtype, act, gated, M, K, N1, N2):
 
 def ffuse_plan_table_clear():
     _check(lib().ffuse_plan_table_clear(), "ffuse_plan_table_clear")
+
+
+def _conv(name, X, W1, W2, act, Y, stream, check):
+    B, H, W, IC = X.shape
+    k1, _, _, OC1 = W1.shape
+    k2, _, _, OC2 = W2.shape
+    rc = getattr(lib(), name)(_ptr(X), _ptr(W1), _ptr(W2), int(act), B, H, W, IC, OC1, OC2, k1, k2, _ptr(Y), _stream(stream))
+    if check:
+        _check(rc, name)
+    return rc
+
+
+def ffuse_conv_chain(X, W1, W2, act, Y, stream=None, check=True):
+    """X [B][H][W][IC], W1 [k1][k1][IC][OC1], W2 [k2][k2][OC1][OC2], Y [B][H][W][OC2] (bf16)."""
+    return _conv("ffuse_conv_chain", X, W1, W2, act, Y, stream, check)
+
+
+def ffuse_conv_chain_f16(X, W1, W2, act, Y, stream=None, check=True):
+    return _conv("ffuse_conv_chain_f16", X, W1, W2, act, Y, stream, check)
 
 
 def ffuse_profile_enable(on: bool):

@@ -45,6 +45,7 @@ struct State {
         double ms;        // measured time of a tuned plan; 0 for a modelled one
     };
     std::map<std::array<int64_t, 6>, TableEntry> table;
+    int conv_ic = 0, conv_h = 0, conv_w = 0;   // set around a 3x3 convolution-chain call only
 };
 State g;
 
@@ -207,7 +208,8 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
         }
         g.ws_zero = 0;      // planes and H overwrite the region the reduce family keeps at zero
         ffuse::TwoPhaseArgs s{X, W1, W3, W2, base + sg.ysum_bytes, Y, reinterpret_cast<float*>(base), flags,
-                              M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, sg.raster, nullptr};
+                              M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, sg.raster, nullptr,
+                              g.conv_ic, g.conv_h, g.conv_w};
         if (g.log && g.ws_bytes >= sg.ws_bytes + 32768) {
             s.stats = reinterpret_cast<uint64_t*>(base + sg.ws_bytes);
             g.small_stats = s.stats;
@@ -417,6 +419,47 @@ int ffuse_sync_status(void* stream) {
     return word ? FFUSE_ERR_TIMEOUT : FFUSE_OK;
 }
 
+// Convolution chain (Evaluation, table of conv-chain configurations): conv k1 x k1 ->
+// activation -> conv 1 x 1 over a channels-last image.  A 1x1 first convolution is the GEMM
+// chain on the pixel rows; a 3x3 one runs the two-phase kernel with implicit-im2col loads.
+int run_conv_chain(int dtype, const void* X, const void* W1, const void* W2, int act, int64_t B, int64_t H, int64_t W,
+                   int64_t IC, int64_t OC1, int64_t OC2, int k1, int k2, void* Y, void* stream) {
+    if (B < 1 || H < 1 || W < 1 || IC < 8 || H > 32768 || W > 32768) return FFUSE_ERR_SHAPE;
+    if (k2 != 1 || (k1 != 1 && k1 != 3)) return FFUSE_ERR_SHAPE;
+    const int64_t M = B * H * W, K = (int64_t)k1 * k1 * IC;
+    if (k1 == 1) return run_fused(dtype, X, W1, nullptr, W2, act, M, K, OC1, OC2, Y, stream);
+    if (IC % 64) return FFUSE_ERR_SHAPE;   // one tap per K step of 64
+    int rc = validate(X, W1, nullptr, W2, act, M, K, OC1, OC2, Y, 2);
+    if (rc != FFUSE_OK) return rc;
+    std::lock_guard<std::mutex> lock(g.mu);
+    rc = check_arch();
+    if (rc != FFUSE_OK) return rc;
+    read_env_plan();
+    ffuse_plan_t plan{};
+    bool found = false;
+    if (g.forced && g.forced_plan.family == FFUSE_FAMILY_TWOPHASE) {
+        plan = g.forced_plan;
+        if (plan.bm == 0) plan.bm = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
+        found = plan.bm <= 128 && ffuse::plan_valid(plan, dtype, 0, M, K, OC1, OC2);
+        if (!found) return FFUSE_ERR_PLAN;
+    } else {
+        std::vector<ffuse::RankedPlan> ranked;
+        ffuse::rank_plans(dtype, act, 0, M, K, OC1, OC2, &ranked);
+        for (const auto& r : ranked)
+            if (r.plan.family == FFUSE_FAMILY_TWOPHASE && r.plan.bm <= 128 &&
+                ffuse::plan_workspace_bytes(r.plan, dtype, 0, M, K, OC1, OC2) <= g.ws_bytes) {
+                plan = r.plan;
+                found = true;
+                break;
+            }
+    }
+    if (!found) return g.ws ? FFUSE_ERR_WORKSPACE : FFUSE_ERR_WORKSPACE;
+    g.conv_ic = (int)IC; g.conv_h = (int)H; g.conv_w = (int)W;
+    rc = run_plan(plan, dtype, X, W1, nullptr, W2, act, M, K, OC1, OC2, Y, stream);
+    g.conv_ic = g.conv_h = g.conv_w = 0;
+    return rc;
+}
+
 // Sec. 4.3, Algorithm 2, second half: time the analytically best `top_k` plans on the device
 // and keep the fastest in the plan table for M's bin.
 int ffuse_tune(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
@@ -483,6 +526,17 @@ int ffuse_tune(int dtype, const void* X, const void* W1, const void* W3, const v
     if (best_plan) *best_plan = bestp;
     if (best_ms) *best_ms = best;
     return FFUSE_OK;
+}
+
+int ffuse_conv_chain(const void* X, const void* W1, const void* W2, int act, int64_t B, int64_t H, int64_t W, int64_t IC,
+                     int64_t OC1, int64_t OC2, int k1, int k2, void* Y, void* stream) {
+    if (!X || !W1 || !W2 || !Y) return FFUSE_ERR_NULL;
+    return run_conv_chain(FFUSE_DT_BF16, X, W1, W2, act, B, H, W, IC, OC1, OC2, k1, k2, Y, stream);
+}
+int ffuse_conv_chain_f16(const void* X, const void* W1, const void* W2, int act, int64_t B, int64_t H, int64_t W, int64_t IC,
+                         int64_t OC1, int64_t OC2, int k1, int k2, void* Y, void* stream) {
+    if (!X || !W1 || !W2 || !Y) return FFUSE_ERR_NULL;
+    return run_conv_chain(FFUSE_DT_F16, X, W1, W2, act, B, H, W, IC, OC1, OC2, k1, k2, Y, stream);
 }
 
 int ffuse_plan_table_clear(void) {

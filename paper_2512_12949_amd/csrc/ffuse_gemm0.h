@@ -22,7 +22,11 @@
 
 namespace ffuse {
 
-template <typename T, bool GATED, int BM, int BH, int WM, int WN>
+// CONV: the row operand is the implicit im2col matrix of a 3x3, stride-1, zero-padded
+// convolution over a channels-last image (row m = pixel m, column k = tap * IC + channel):
+// the loader adds the tap's pixel shift to the row's address and masks the taps that fall
+// outside the image.  IC must be a multiple of 64, so that a K step of 64 stays in one tap.
+template <typename T, bool GATED, int BM, int BH, int WM, int WN, bool CONV = false>
 struct FirstGemm {
     static_assert(WM * WN == 4, "four waves");
     typedef typename Mma<T>::vec8 vec8;
@@ -56,6 +60,9 @@ struct FirstGemm {
         int KX;               // extent of the A operand along k (chunks at or past it read as 0)
         // LDS read offsets of this lane's fragments at sub-step 0, stage 0
         uint32_t rdx[MT], rdw[HT];
+        // CONV only: channels and width of the image; per row, bit t set = tap t is inside the image
+        int conv_ic, conv_w;
+        uint32_t vmask[CONV ? XCH : 1];
     };
 
     // A operand: `rows x lda` elements at `A` (+ base_bytes), first row row0; rows past the
@@ -72,6 +79,56 @@ struct FirstGemm {
             c.xoff[p] = (row * lda + 8u * c.xc) * 2u;
         }
     }
+    // CONV: A = im2col of the image X[npix][IC] (npix = B*H*W pixels, channels last) for a 3x3
+    // kernel; rows are pixels, K = 9 * IC.
+    static __device__ __forceinline__ void init_a_conv(Ctx& c, const void* X, uint32_t x_bytes, uint32_t row0, int64_t npix,
+                                                       int H, int W, int IC, int tid) {
+        c.rx = make_rsrc(X, x_bytes);
+        c.KX = 9 * IC;
+        c.abase = 0u;
+        c.xc = tid & 7;
+        c.conv_ic = IC;
+        c.conv_w = W;
+#pragma unroll
+        for (int p = 0; p < XCH; ++p) {
+            const uint32_t row = row0 + (tid >> 3) + 32u * p;
+            c.xoff[p] = (row * (uint32_t)IC + 8u * c.xc) * 2u;
+            const int h = (int)((row / (uint32_t)W) % (uint32_t)H), w = (int)(row % (uint32_t)W);
+            uint32_t m = 0;
+            if ((int64_t)row < npix)
+                for (int t = 0; t < 9; ++t) {
+                    const int hh = h + t / 3 - 1, ww = w + t % 3 - 1;
+                    if (hh >= 0 && hh < H && ww >= 0 && ww < W) m |= 1u << t;
+                }
+            c.vmask[CONV ? p : 0] = m;
+        }
+    }
+    // per K step: the uniform part of the A addresses
+    struct AStep {
+        bool ok;
+        uint32_t add;
+        int tap;
+    };
+    static __device__ __forceinline__ AStep a_step(const Ctx& c, int kx) {
+        AStep s;
+        if (CONV) {
+            const int tap = kx / c.conv_ic, ic0 = kx - tap * c.conv_ic;
+            const int dh = tap / 3 - 1, dw = tap - 3 * (tap / 3) - 1;
+            s.add = (uint32_t)(((dh * c.conv_w + dw) * c.conv_ic + ic0) * 2);   // may be "negative": offsets add modulo 2^32
+            s.tap = tap;
+            s.ok = kx < c.KX;
+        } else {
+            s.add = (uint32_t)kx * 2u;
+            s.tap = 0;
+            s.ok = (kx + 8 * (int)c.xc) < c.KX && c.abase != kOob;
+        }
+        return s;
+    }
+    static __device__ __forceinline__ uint32_t a_offset(const Ctx& c, const AStep& s, int p) {
+        const bool ok = s.ok && (!CONV || ((c.vmask[CONV ? p : 0] >> s.tap) & 1u));
+        return ok ? c.xoff[p] + c.abase + s.add : kOob;
+    }
+
     // B operands: [K][ldb] matrices, first column n0 (columns at or past ncols read as zero).
     static __device__ __forceinline__ void init_b(Ctx& c, const void* B, const void* B3, uint32_t b_bytes,
                                                   uint32_t ldb, uint32_t ncols, uint32_t n0, int tid) {
@@ -102,9 +159,9 @@ struct FirstGemm {
 
     // global -> registers for the K step whose A columns start at kx / B rows at kw
     static __device__ __forceinline__ void gload_a(const Ctx& c, Stage& s, int kx) {
-        const bool xok = (kx + 8 * (int)c.xc) < c.KX && c.abase != kOob;
+        const AStep as = a_step(c, kx);
 #pragma unroll
-        for (int p = 0; p < XCH; ++p) s.x[p] = buf_load16(c.rx, xok ? c.xoff[p] + c.abase + (uint32_t)kx * 2u : kOob);
+        for (int p = 0; p < XCH; ++p) s.x[p] = buf_load16(c.rx, a_offset(c, as, p));
     }
     static __device__ __forceinline__ void gload_b(const Ctx& c, Stage& s, int kw) {
 #pragma unroll
@@ -213,7 +270,7 @@ struct FirstGemm {
 #pragma unroll
         for (int i = 0; i < NR; ++i) read_one(cur, c, 0, i, f[0]);
         __builtin_amdgcn_sched_barrier(0);
-        const bool xok = (kx + 8 * (int)c.xc) < c.KX && c.abase != kOob;
+        const AStep as = a_step(c, kx);
         const uint32_t kb = (uint32_t)kw * c.wrow;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
@@ -228,7 +285,7 @@ struct FirstGemm {
 #pragma unroll
                     for (int e = (i * XCH) / NM; e < ((i + 1) * XCH) / NM; ++e) {
                         lds_write16(nxt, lds_row_off((tid >> 3) + 32u * e, tid & 7), st.x[e]);
-                        st.x[e] = buf_load16(c.rx, xok ? c.xoff[e] + c.abase + (uint32_t)kx * 2u : kOob);
+                        st.x[e] = buf_load16(c.rx, a_offset(c, as, e));
                     }
                 }
                 if (ks == 3) {

@@ -66,6 +66,9 @@ struct TwoPhaseArgs {
     int ksplit;       // hidden columns per range (multiple of 64)
     int raster;       // row blocks per XCD patch (>= 1)
     uint64_t* stats;  // nullptr, or 4 words per workgroup: ticks of phase 1, barrier, phase 2
+    // 3x3 first product (conv_ic > 0): X is a channels-last image of M pixels (conv_h x conv_w
+    // per image) with conv_ic channels, W1 is [3][3][conv_ic][N1], K = 9 * conv_ic
+    int conv_ic, conv_h, conv_w;
 };
 
 // 16-bit paths (dtype 0 = bf16, 1 = fp16)

@@ -46,24 +46,26 @@ __device__ __forceinline__ bool map_item(int MB, int S, int raster, int xcd, int
     return true;
 }
 
-template <typename T, bool GATED, int BM> struct TwoPhaseGemms {
+template <typename T, bool GATED, int BM, bool CONV> struct TwoPhaseGemms {
     // hidden slices of 128 columns: with few rows the first phase is a weight stream, and
     // narrow slices give it N1/128 work items to spread over the CUs
     static constexpr int BH1 = 128;
-    typedef FirstGemm<T, GATED, BM, BH1, 1, 4> G1;   // phase 1: X * W1 (, X * W3)
+    typedef FirstGemm<T, GATED, BM, BH1, 1, 4, CONV> G1;   // phase 1: X * W1 (, X * W3); CONV: im2col(X) * W1
     typedef FirstGemm<T, false, BM, 256, 1, 4> G2;   // phase 2: H * W2
     static constexpr bool DEEP = false;
 };
-template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 256> {
+template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 256, false> {
     static constexpr int BH1 = GATED ? 128 : 256;
     typedef DeepGemm<T, GATED, 256, BH1, 2, 2> G1;
     typedef DeepGemm<T, false, 256, 256, 2, 2> G2;
     static constexpr bool DEEP = true;
 };
 
-template <typename T, bool GATED, int BM>
+// CONV: the first product is a 3x3 convolution (rows = pixels of a channels-last image,
+// a.K = 9 * a.conv_ic); everything after the first product's loads is unchanged.
+template <typename T, bool GATED, int BM, bool CONV = false>
 __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
-    typedef TwoPhaseGemms<T, GATED, BM> TG;
+    typedef TwoPhaseGemms<T, GATED, BM, CONV> TG;
     typedef typename TG::G1 G1;
     typedef typename TG::G2 G2;
     constexpr int BH1 = TG::BH1, BH2 = 256;
@@ -86,7 +88,10 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
         const int NS = (a.N1 + BH1 - 1) / BH1;
         int rb, s;
         for (int idx = loc; map_item(MB, NS, a.raster, xcd, idx, rb, s); idx += GX) {
-            G1::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)rb * BM, (uint32_t)a.K, a.K, tid);
+            if constexpr (CONV)
+                G1::init_a_conv(c, a.X, (uint32_t)((uint64_t)a.M * a.conv_ic * 2), (uint32_t)rb * BM, a.M, a.conv_h, a.conv_w, a.conv_ic, tid);
+            else
+                G1::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)rb * BM, (uint32_t)a.K, a.K, tid);
             G1::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1, (uint32_t)s * BH1, tid);
             if constexpr (TG::DEEP) G1::run(smem, c, 0, a.K, acc, acc3, tid);
             else G1::run_deep(smem, c, 0, a.K, acc, acc3, tid);
@@ -218,10 +223,24 @@ template <typename T, bool GATED> static const void* two_phase_fn(int bm) {
     return nullptr;
 }
 
+template <typename T> static const void* two_phase_conv_fn(int bm) {
+    if (bm == 32) return (const void*)fused_two_phase_kernel<T, false, 32, true>;
+    if (bm == 64) return (const void*)fused_two_phase_kernel<T, false, 64, true>;
+    if (bm == 128) return (const void*)fused_two_phase_kernel<T, false, 128, true>;
+    return nullptr;
+}
+
 hipError_t launch_fused_two_phase(int dtype, const TwoPhaseArgs& a, int bm, int grid, hipStream_t st) {
     const bool g = a.W3 != nullptr;
-    const void* fn = dtype == 0 ? (g ? two_phase_fn<__bf16, true>(bm) : two_phase_fn<__bf16, false>(bm))
-                                : (g ? two_phase_fn<_Float16, true>(bm) : two_phase_fn<_Float16, false>(bm));
+    const void* fn;
+    if (a.conv_ic > 0) {
+        // 3x3 first product: one tap per K step of 64, and the shifted addresses must fit 32 bits
+        if (g || a.conv_ic % 64 || a.K != 9 * a.conv_ic || a.conv_h < 1 || a.conv_w < 1) return hipErrorInvalidValue;
+        fn = dtype == 0 ? two_phase_conv_fn<__bf16>(bm) : two_phase_conv_fn<_Float16>(bm);
+    } else {
+        fn = dtype == 0 ? (g ? two_phase_fn<__bf16, true>(bm) : two_phase_fn<__bf16, false>(bm))
+                        : (g ? two_phase_fn<_Float16, true>(bm) : two_phase_fn<_Float16, false>(bm));
+    }
     if (!fn || grid < 8 || (grid & 7) || a.raster < 1 || a.splits < 1) return hipErrorInvalidValue;
     TwoPhaseArgs copy = a;
     void* params[] = {&copy};

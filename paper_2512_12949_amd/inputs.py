@@ -176,6 +176,58 @@ for _i, (_n, _k, _l) in enumerate(_S):
                                   "normal", 200 + _i)
 
 
+@dataclass(frozen=True)
+class ConvWorkload:
+    """Two convolutions with an activation between them (paper: Evaluation, table "The
+    configuration of conv chain"): channels-last image, stride 1, zero padding k/2."""
+    name: str
+    B: int
+    H: int
+    W: int
+    IC: int
+    OC1: int
+    OC2: int
+    k1: int
+    k2: int
+    dtype: str
+    act: int
+    cfg_id: int
+
+    def gemm_shape(self):
+        """(M, K, N1, N2) of the equivalent GEMM chain over pixel rows (k2 = 1)."""
+        return (self.B * self.H * self.W, self.k1 * self.k1 * self.IC, self.OC1, self.OC2 * self.k2 * self.k2)
+
+    def flops(self) -> int:
+        npix = self.B * self.H * self.W
+        return 2 * npix * self.OC1 * (self.k1 * self.k1 * self.IC + self.k2 * self.k2 * self.OC2)
+
+    def q_min(self) -> int:
+        npix = self.B * self.H * self.W
+        return 2 * (npix * self.IC + self.k1 * self.k1 * self.IC * self.OC1 + self.k2 * self.k2 * self.OC1 * self.OC2 +
+                    npix * self.OC2)
+
+
+# The paper's conv-chain table (IC, H, W, OC1, OC2, k1, k2).  The table gives no batch size,
+# activation or type: batch 1, ReLU between the convolutions and bf16 are this build's reading.
+_C = [(64, 56, 56, 256, 64, 1, 1), (128, 28, 28, 512, 128, 1, 1), (256, 14, 14, 1024, 256, 1, 1),
+      (512, 7, 7, 2048, 512, 1, 1), (64, 56, 56, 64, 256, 3, 1), (128, 28, 28, 128, 512, 3, 1),
+      (256, 14, 14, 256, 1024, 3, 1), (512, 7, 7, 512, 2048, 3, 1)]
+CONV_WORKLOADS = {
+    f"C{_i + 1}": ConvWorkload(f"C{_i + 1}", 1, _h, _w, _ic, _o1, _o2, _k1, _k2, "bf16", ACT_RELU, 300 + _i)
+    for _i, (_ic, _h, _w, _o1, _o2, _k1, _k2) in enumerate(_C)
+}
+
+
+def make_conv(w: ConvWorkload):
+    """Operand buffers of a conv chain: X [B][H][W][IC] ~ N(0,1), W1 [k1][k1][IC][OC1] and
+    W2 [k2][k2][OC1][OC2] ~ N(0, 1/fan_in) with fan_in = k*k*channels_in (storage arrays)."""
+    s = 1000 * w.cfg_id
+    X = tensor(s + 0, (w.B, w.H, w.W, w.IC), "normal", 1.0, w.dtype)
+    W1 = tensor(s + 1, (w.k1, w.k1, w.IC, w.OC1), "normal", (w.k1 * w.k1 * w.IC) ** -0.5, w.dtype)
+    W2 = tensor(s + 3, (w.k2, w.k2, w.OC1, w.OC2), "normal", (w.k2 * w.k2 * w.OC1) ** -0.5, w.dtype)
+    return {"X": X, "W1": W1, "W2": W2}
+
+
 def make(w: Workload, m_rows=None):
     """Operand buffers of a workload: dict with X, W1, W3 (or None), W2 (storage arrays).
 

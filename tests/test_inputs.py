@@ -90,3 +90,17 @@ def test_chain_workloads_match_the_papers_printed_tables():
         assert (w.M, w.K, w.N1, w.N2) == (m, k, n, l), name
         assert w.gated == (name[0] == "S")
     assert sum(1 for k_ in rows if k_[0] == "G") == 10 and sum(1 for k_ in rows if k_[0] == "S") == 8
+
+
+def test_conv_workloads_match_the_papers_printed_table():
+    """C1-C8 (Evaluation, table of conv-chain configurations): IC, H, W, OC1, OC2, k1, k2."""
+    rows = _golden_tables()
+    names = [k_ for k_ in rows if k_[0] == "C"]
+    assert len(names) == 8
+    for name in names:
+        w = inputs.CONV_WORKLOADS[name]
+        assert [w.IC, w.H, w.W, w.OC1, w.OC2, w.k1, w.k2] == rows[name], name
+        M, K, N1, N2 = w.gemm_shape()
+        assert (M, K, N1, N2) == (w.H * w.W, w.k1 ** 2 * w.IC, w.OC1, w.OC2)
+    ops = inputs.make_conv(inputs.CONV_WORKLOADS["C8"])
+    assert ops["X"].shape == (1, 7, 7, 512) and ops["W1"].shape == (3, 3, 512, 512) and ops["W2"].shape == (1, 1, 512, 2048)
