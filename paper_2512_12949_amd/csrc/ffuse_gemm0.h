@@ -33,7 +33,8 @@ struct FirstGemm {
     static constexpr int G = GATED ? 2 : 1;
     static constexpr int WMR = BM / WM, WHR = BH / WN;  // rows / columns per wave
     static constexpr int MT = WMR / 32, HT = WHR / 32;  // 32x32 tiles per wave
-    static_assert(MT >= 1 && HT >= 1 && BM % 32 == 0 && BH % 64 == 0, "tile shape");
+    // (a gated tile needs BH >= 64: which of the two weight matrices a lane loads must be uniform per wave)
+    static_assert(MT >= 1 && HT >= 1 && BM % 32 == 0 && BH % 32 == 0 && (BH % 64 == 0 || !GATED), "tile shape");
     static constexpr int XB = BM * 128;       // bytes of one A stage
     static constexpr int WB = BH * 128;       // bytes of one B stage
     static constexpr int STAGE = XB + G * WB;

@@ -49,7 +49,7 @@ bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t 
         case FFUSE_FAMILY_TWOPHASE: {
             if (dtype == FFUSE_DT_F32) return false;
             TwoPhaseGeometry sg;
-            return two_phase_geometry(p, M, N1, N2, &sg);
+            return two_phase_geometry(p, gated, M, N1, N2, &sg);
         }
         case FFUSE_FAMILY_EXCHANGE: {
             if (dtype == FFUSE_DT_F32) return false;
@@ -85,13 +85,24 @@ int two_phase_max_splits(int64_t M, int64_t N2) {
     return sp;
 }
 
-bool two_phase_geometry(const ffuse_plan_t& p, int64_t M, int64_t N1, int64_t N2, TwoPhaseGeometry* g) {
+bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, int64_t N2, TwoPhaseGeometry* g) {
     // rows per block: the plan's, or the smallest block that holds all rows, or 128 / 256
     int bm = p.bm;
     if (bm <= 0) bm = M <= 32 ? 32 : (M <= 64 ? 64 : (M <= 512 ? 128 : 256));
     if (bm != 32 && bm != 64 && bm != 128 && bm != 256) return false;
     if (bm < 128 && M > bm) return false;   // the small blocks are for a single row block
     g->bm = bm;
+    // hidden slice of a phase-1 item: the plan's bh where the kernels implement it
+    if (bm == 256) {
+        g->bh1 = gated ? 128 : 256;
+    } else {
+        g->bh1 = p.bh > 0 ? p.bh : 128;
+        const bool ok = g->bh1 == 128 || (g->bh1 == 64 && bm >= 64) || (g->bh1 == 32 && bm == 128 && !gated);
+        if (!ok) {
+            if (p.bh == 256) g->bh1 = 128;   // plans written before narrow slices existed
+            else return false;
+        }
+    }
     const int64_t mb = (M + bm - 1) / bm;
     g->raster = p.raster > 0 ? p.raster : 1;
     if (g->raster > mb) g->raster = (int)mb;
@@ -149,7 +160,7 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         t->feasible = t->lds_used <= d.lds_bytes && t->acc_regs <= d.acc_regs;
     } else if (p.family == FFUSE_FAMILY_TWOPHASE) {
         TwoPhaseGeometry sg;
-        t->feasible = two_phase_geometry(p, M, N1, N2, &sg) ? 1 : 0;
+        t->feasible = two_phase_geometry(p, gated, M, N1, N2, &sg) ? 1 : 0;
         if (t->feasible) {
             const double bh1 = gated ? 128.0 : 256.0;
             const double bm = sg.bm, ns = cdiv(n1, bh1), items = cdiv(n2, 256) * sg.splits;
@@ -241,8 +252,12 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         // comes from HBM, repeats (and the rows, once per slice group) from the Infinity Cache.
         // Fixed: launch, one device-wide barrier, finalize (~25 us).
         TwoPhaseGeometry sg;
-        two_phase_geometry(p, M, N1, N2, &sg);
-        const double per_wg = 25e9, bh1 = (gated || sg.bm < 256) ? 128.0 : 256.0;
+        two_phase_geometry(p, gated, M, N1, N2, &sg);
+        const double bh1 = sg.bh1;
+        // a workgroup keeps a fixed number of bytes in flight, split between its row tile and its
+        // weight tile in proportion to their widths: ~50 GB/s in all, of which the weights' share
+        // (and never more than ~30 GB/s: three K steps of loads against a loaded memory latency)
+        const double per_wg1 = std::min(30e9, 50e9 * (g * bh1) / (sg.bm + g * bh1)), per_wg2 = std::min(30e9, 50e9 * 256.0 / (sg.bm + 256.0));
         const double mb = cdiv(m, sg.bm), patches = cdiv(mb, sg.raster);
         const double n_s = cdiv(n1, bh1), ncb = cdiv(n2, 256);
         const double items1 = mb * n_s, items = mb * ncb * sg.splits;
@@ -250,9 +265,10 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         const double cols_per_patch = std::max(1.0, 32.0 / std::min(mb, (double)sg.raster));
         const double re1 = b1 * (patches - 1.0) + e * m * k * std::max(0.0, n_s / cols_per_patch / 8.0 - 1.0);
         const double re2 = b2 * (patches - 1.0) + e * m * n1 * std::max(0.0, ncb / cols_per_patch / 8.0 - 1.0) + e * m * n1;
-        const double t1 = b1 / std::min(d.hbm_bw, std::min(items1, (double)d.cus) * per_wg) + re1 / d.fabric_bw + 3e-6 * cdiv(items1, d.cus);
-        const double t2 = b2 / std::min(d.hbm_bw, std::min(items, (double)d.cus) * per_wg) + re2 / d.fabric_bw + 3e-6 * cdiv(items, d.cus);
-        const double planes = sg.splits > 1 ? 2.0 * 4.0 * m * n2 * sg.splits / d.fabric_bw : 0.0;
+        const double t1 = b1 / std::min(d.hbm_bw, std::min(items1, (double)d.cus) * per_wg1) + re1 / d.fabric_bw + 3e-6 * cdiv(items1, d.cus);
+        const double t2 = b2 / std::min(d.hbm_bw, std::min(items, (double)d.cus) * per_wg2) + re2 / d.fabric_bw + 3e-6 * cdiv(items, d.cus);
+        // planes are written and read once; small transfers reach about half the cache rate
+        const double planes = sg.splits > 1 ? 2.0 * 4.0 * m * n2 * sg.splits / (0.5 * d.fabric_bw) : 0.0;
         // matrix-core time of each phase: items run one per CU, at the block GEMM's efficiency
         // (the 256-row LDS-direct GEMM vs the register-staged one with four waves in a row)
         const double f_cu = d.mfma_flops * (sg.bm == 256 ? 0.48 : 0.33) / d.cus;
@@ -305,19 +321,24 @@ void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1,
         for (int bm : bms) {
             if (bm < 128 && M > bm) continue;                 // the small blocks hold all rows or are not used
             if (bm > 32 && M <= bm / 2) continue;             // more than half a block of padding
-            for (int sp : splits) {
-                if (sp > two_phase_max_splits(M, N2)) continue;
-                for (int r : rasters2) {
-                    if (r > 1 && r > (M + bm - 1) / bm) continue;   // a patch cannot have more row blocks than there are
-                    ffuse_plan_t p;
-                    std::memset(&p, 0, sizeof(p));
-                    p.family = FFUSE_FAMILY_TWOPHASE;
-                    p.bm = bm; p.bh = (gated || bm < 256) ? 128 : 256; p.bn2 = 256; p.bk = 64; p.h_level = 2; p.raster = r;
-                    p.splits = sp;
-                    ffuse_traffic_t t;
-                    traffic_model(p, dtype, gated, M, K, N1, N2, &t);
-                    if (!t.feasible) continue;
-                    out->push_back({t.t_pred, p});
+            static const int slices[] = {128, 64, 32};
+            for (int bh1 : slices) {
+                if (bm == 256 && bh1 != 128) continue;                        // the 256-row kernel has one slice width
+                if ((bh1 == 64 && bm < 64) || (bh1 == 32 && (bm != 128 || gated))) continue;
+                for (int sp : splits) {
+                    if (sp > two_phase_max_splits(M, N2)) continue;
+                    for (int r : rasters2) {
+                        if (r > 1 && r > (M + bm - 1) / bm) continue;   // a patch cannot have more row blocks than there are
+                        ffuse_plan_t p;
+                        std::memset(&p, 0, sizeof(p));
+                        p.family = FFUSE_FAMILY_TWOPHASE;
+                        p.bm = bm; p.bh = bm == 256 ? (gated ? 128 : 256) : bh1; p.bn2 = 256; p.bk = 64; p.h_level = 2; p.raster = r;
+                        p.splits = sp;
+                        ffuse_traffic_t t;
+                        traffic_model(p, dtype, gated, M, K, N1, N2, &t);
+                        if (!t.feasible) continue;
+                        out->push_back({t.t_pred, p});
+                    }
                 }
             }
         }
@@ -358,7 +379,7 @@ size_t plan_workspace_bytes(const ffuse_plan_t& p, int dtype, int gated, int64_t
         }
         case FFUSE_FAMILY_TWOPHASE: {
             TwoPhaseGeometry t;
-            return two_phase_geometry(p, M, N1, N2, &t) ? t.ws_bytes : 0;
+            return two_phase_geometry(p, gated, M, N1, N2, &t) ? t.ws_bytes : 0;
         }
         case FFUSE_FAMILY_UNFUSED: return (dtype == FFUSE_DT_F32 ? 4 : 2) * (size_t)M * (size_t)N1;
         default: return 0;

@@ -37,13 +37,14 @@ bool exchange_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, 
 // Two-phase family: derived geometry.
 struct TwoPhaseGeometry {
     int bm;             // rows per block: 32, 64, 128 or 256
+    int bh1;            // hidden slice of a phase-1 item: 128 / 64 / 32 (bm <= 128), 256 or 128 gated (bm = 256)
     int splits, ksplit; // phase-2 ranges of the hidden dimension (splits == 1: no partial planes)
     int raster;         // row blocks per XCD patch
     size_t ysum_bytes, h_bytes, ws_bytes;   // workspace layout: partial-sum planes | H | 256 bytes of flags
 };
 // most hidden-dimension ranges the chooser considers for an M x N2 output (bounds the workspace)
 int two_phase_max_splits(int64_t M, int64_t N2);
-bool two_phase_geometry(const ffuse_plan_t& p, int64_t M, int64_t N1, int64_t N2, TwoPhaseGeometry* out);
+bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, int64_t N2, TwoPhaseGeometry* out);
 
 bool fused_reduce_tile_ok(int gated, int bm, int bh);
 bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2);

@@ -111,6 +111,27 @@ def test_two_phase_family_with_row_blocks(dtype, gated):
             gu.check(gu.run(w, dev, plan=plan), ref, dtype, rows=rows, what=f"two-phase bm={bm} splits={splits} again")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("gated", [False, True])
+def test_two_phase_narrow_hidden_slices(dtype, gated):
+    """Phase-1 items of 64 and 32 hidden columns (2 x 2 waves, four waves along the rows):
+    one row block and several, ragged everything."""
+    act = ACT_SILU if gated else ACT_GELU_TANH
+    for (M, K, N1, N2) in [(50, 136, 392, 520), (128, 200, 840, 264), (300, 72, 1304, 136)]:
+        w, host, dev = _case("narrow", M, K, N1, N2, dtype, act, gated)
+        ref = gu.oracle_rows(w, host)
+        for bm, bh, splits in ((64, 64, 2), (128, 64, 1), (128, 64, 3), (128, 32, 1), (128, 32, 4)):
+            if (bm < 128 and M > bm) or (bh == 32 and gated):
+                continue
+            plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=bh, splits=splits, raster=2)
+            print(f"two-phase {dtype} gated={gated} shape {(M, K, N1, N2)} bm={bm} bh={bh} splits={splits}", flush=True)
+            gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase bm={bm} bh={bh} splits={splits}")
+    if gated:   # a 32-column slice cannot serve two weight matrices
+        w, host, dev = _case("narrow", 128, 64, 256, 64, dtype, act, gated)
+        with pytest.raises(ff.FfuseError):
+            gu.run(w, dev, plan=ff.make_plan(ff.FAMILY_TWOPHASE, bm=128, bh=32, splits=1))
+
+
 @pytest.mark.parametrize("act", [ACT_RELU, ACT_GELU_TANH, ACT_SILU, ACT_IDENTITY])
 @pytest.mark.parametrize("gated", [False, True])
 def test_activations_medium(act, gated):
