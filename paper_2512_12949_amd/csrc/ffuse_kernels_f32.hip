@@ -4,6 +4,8 @@
 // activation (paper Sec. 4.3, Rule 3), partial second products added atomically into Y.
 #include "ffuse_dev.h"
 #include "ffuse_launch.h"
+#include <mutex>
+#include <unordered_map>
 
 #include <cstdlib>
 
@@ -127,12 +129,27 @@ hipError_t launch_zero(void* p, size_t bytes, hipStream_t st) {
 hipError_t launch_resident(const void* fn, int grid, void** params, hipStream_t st) {
     static const bool cooperative = getenv("FFUSE_COOPERATIVE_LAUNCH") != nullptr;
     if (cooperative) return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, st);
-    int per_cu = 0, dev = 0, cus = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, 0);
-    if (e != hipSuccess) return e;
-    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-    if (grid > per_cu * cus) return hipErrorCooperativeLaunchTooLarge;
+    // how many workgroups of this kernel the device holds at once: asked once per kernel
+    static std::mutex mu;
+    static std::unordered_map<const void*, int> capacity;
+    int cap = 0;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        auto it = capacity.find(fn);
+        if (it != capacity.end()) cap = it->second;
+    }
+    if (cap == 0) {
+        int per_cu = 0, dev = 0, cus = 0;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, 0);
+        if (e != hipSuccess) return e;
+        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+        cap = per_cu * cus;
+        if (cap <= 0) return hipErrorCooperativeLaunchTooLarge;
+        std::lock_guard<std::mutex> lock(mu);
+        capacity[fn] = cap;
+    }
+    if (grid > cap) return hipErrorCooperativeLaunchTooLarge;
     return hipLaunchKernel(fn, dim3(grid), dim3(256), params, 0, st);
 }
 
