@@ -217,7 +217,7 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
         g.exch_err = flags + 2;
         {
             Timer t(st);
-            if (ffuse::launch_fused_two_phase(dtype, s, sg.bm, sg.bh1, g.cus, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+            if (ffuse::launch_fused_two_phase(dtype, s, sg.bm, sg.bh1, sg.bk, g.cus, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
             t.stop();
         }
         if (sg.splits > 1 && ffuse::launch_finalize_planes(dtype, s.part, Y, M * N2, sg.splits, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
@@ -440,14 +440,14 @@ int run_conv_chain(int dtype, const void* X, const void* W1, const void* W2, int
     if (g.forced && g.forced_plan.family == FFUSE_FAMILY_TWOPHASE) {
         plan = g.forced_plan;
         if (plan.bm == 0) plan.bm = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
-        if (plan.bh != 128) plan.bh = 128;   // the 3x3 loader exists for 128-column slices only
+        plan.bh = 128; plan.bk = 64;   // the 3x3 loader exists for the register-staged loop with 128-column slices only
         found = plan.bm <= 128 && ffuse::plan_valid(plan, dtype, 0, M, K, OC1, OC2);
         if (!found) return FFUSE_ERR_PLAN;
     } else {
         std::vector<ffuse::RankedPlan> ranked;
         ffuse::rank_plans(dtype, act, 0, M, K, OC1, OC2, &ranked);
         for (const auto& r : ranked)
-            if (r.plan.family == FFUSE_FAMILY_TWOPHASE && r.plan.bm <= 128 && r.plan.bh == 128 &&
+            if (r.plan.family == FFUSE_FAMILY_TWOPHASE && r.plan.bm <= 128 && r.plan.bh == 128 && r.plan.bk != 32 &&
                 ffuse::plan_workspace_bytes(r.plan, dtype, 0, M, K, OC1, OC2) <= g.ws_bytes) {
                 plan = r.plan;
                 found = true;

@@ -37,14 +37,17 @@ namespace ffuse {
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-template <typename T, bool GATED, int BM, int BH, int WM, int WN>
+// NS_: stages in the ring (a power of two, 4 or 8): loads run NS_ - 1 stages ahead.  Four keeps a
+// 256 x 256 tile fed; eight is for small tiles in the weight-streaming regime, where the
+// bytes a workgroup keeps in flight set the rate at which it can pull weights.
+template <typename T, bool GATED, int BM, int BH, int WM, int WN, int NS_ = 4>
 struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     typedef FirstGemm<T, GATED, BM, BH, WM, WN> Base;
     typedef typename Base::vec8 vec8;
     using Base::G; using Base::HT; using Base::MT; using Base::WHR; using Base::WMR;
     static_assert(BH == 128 || BH == 256, "unit swizzle needs 8 or 16 units of 32 bytes per row");
     static_assert(BM % 64 == 0, "every wave issues the same number of loads");
-    static constexpr int NS = 4;                       // stages in the ring
+    static constexpr int NS = NS_;                     // stages in the ring
     static constexpr int XB = BM * 64;                 // bytes of one A stage
     static constexpr int WB = BH * 64;                 // bytes of one B stage (one matrix)
     static constexpr int STAGE = XB + G * WB;
@@ -56,6 +59,7 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     static constexpr int NLOAD = XI + G * BI;          // load instructions per wave per stage
     static constexpr int NM = HT * MT * G;             // MFMAs per wave per sub-step
     static constexpr int NR = MT + HT * G;             // fragment reads per wave per sub-step
+    static_assert((NS == 4 || NS == 8) && (NS - 2) * NLOAD <= 63, "ring depth: the vmcnt field holds 6 bits");
 
     struct Ctx {
         __amdgpu_buffer_rsrc_t rx, rw[G];
@@ -202,7 +206,7 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
             for (int e = (i * NLOAD) / NM; e < ((i + 1) * NLOAD) / NM; ++e) issue_one(ld, c, kx, kw, xlim, valid, e);
             __builtin_amdgcn_sched_barrier(0);
         }
-        loads_in_flight_at_most<2 * NLOAD>();   // the two youngest steps may still be on their way
+        loads_in_flight_at_most<(NS - 2) * NLOAD>();   // all but the oldest of the stages in flight may still be on their way
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
@@ -213,13 +217,12 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         }
     }
 
-    // Fills the ring for a stream of steps that starts at (kx, kw): stages 0..2 <- steps 0..2,
-    // and leaves the fragments of step 0 in f[0].  `valid3` says which of the three exist.
+    // Fills the ring for a stream of steps that starts at (kx, kw): stages 0..NS-2 <- steps
+    // 0..NS-2, and leaves the fragments of step 0 in f[0].  `nvalid` says how many of them exist.
     static __device__ __forceinline__ void prime(char* smem, const Ctx& c, int kx, int kw, int xlim, int nvalid, Frags (&f)[2]) {
-        issue(smem, c, kx, kw, xlim, nvalid > 0);
-        issue(smem + STAGE, c, kx + 32, kw + 32, xlim, nvalid > 1);
-        issue(smem + 2 * STAGE, c, kx + 64, kw + 64, xlim, nvalid > 2);
-        loads_in_flight_at_most<2 * NLOAD>();
+#pragma unroll
+        for (int j = 0; j < NS - 1; ++j) issue(smem + j * STAGE, c, kx + 32 * j, kw + 32 * j, xlim, nvalid > j);
+        loads_in_flight_at_most<(NS - 2) * NLOAD>();
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < NR; ++i) read_one(smem, c, 0, i, f[0]);
@@ -242,11 +245,11 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         prime(smem, c, kbegin, kbegin, xlim, KT, f);
         if (t_loop) *t_loop = wall_clock64();
         for (int s = 0; s < KT; ++s) {
-            const char* cur = smem + (s & 3) * STAGE;
-            const char* nxt = smem + ((s + 1) & 3) * STAGE;
-            char* ld = smem + ((s + 3) & 3) * STAGE;
-            const int k3 = kbegin + (s + 3) * 32;
-            step(cur, nxt, ld, c, k3, k3, xlim, s + 3 < KT, f, acc, acc3);
+            const char* cur = smem + (s & (NS - 1)) * STAGE;
+            const char* nxt = smem + ((s + 1) & (NS - 1)) * STAGE;
+            char* ld = smem + ((s + NS - 1) & (NS - 1)) * STAGE;
+            const int kl = kbegin + (s + NS - 1) * 32;
+            step(cur, nxt, ld, c, kl, kl, xlim, s + NS - 1 < KT, f, acc, acc3);
         }
         drain();
     }

@@ -319,7 +319,7 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
     constexpr int LDS_BYTES = GP::LDS_BYTES > GC::LDS_BYTES ? GP::LDS_BYTES : GC::LDS_BYTES;
     constexpr uint32_t SLOT_BYTES = 256u * BHP * 2u;
     constexpr int SPI = BHP / 32;                     // steps of 32 k per item on the consumer side
-    static_assert(SPI % GC::NS == 0 && SPI > 3, "an item is a whole number of turns of the stage ring");
+    static_assert(GC::NS == 4 && SPI % GC::NS == 0 && SPI > 3, "an item is a whole number of turns of the four-stage ring");
     __shared__ __attribute__((aligned(16))) char smem[LDS_BYTES];
     const int tid = threadIdx.x;
     const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
@@ -420,7 +420,7 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
         if (!wait_at_least(ready + o0 % R, (uint32_t)o0 + 1u, err, coherent)) return;
         es.end_wait(a.stats);
         GC::init_a(c, ring, (uint32_t)R * SLOT_BYTES, (uint32_t)(o0 % R) * SLOT_BYTES, 0u, BHP, BHP, tid);
-        GC::prime(smem, c, 0, 0, BHP, 3, f);
+        GC::prime(smem, c, 0, 0, BHP, GC::NS - 1, f);
         for (int hh = 0; hh < NH; ++hh) {
             const int o = o0 + hh * PG, on = o + PG;
             const bool more = hh + 1 < NH;

@@ -103,6 +103,8 @@ bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1,
             else return false;
         }
     }
+    g->bk = bm == 256 ? 32 : (p.bk == 32 ? 32 : 64);
+    if (g->bk == 32 && bm != 256 && (bm < 64 || g->bh1 != 128)) return false;
     const int64_t mb = (M + bm - 1) / bm;
     g->raster = p.raster > 0 ? p.raster : 1;
     if (g->raster > mb) g->raster = (int)mb;
@@ -257,7 +259,10 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         // a workgroup keeps a fixed number of bytes in flight, split between its row tile and its
         // weight tile in proportion to their widths: ~50 GB/s in all, of which the weights' share
         // (and never more than ~30 GB/s: three K steps of loads against a loaded memory latency)
-        const double per_wg1 = std::min(30e9, 50e9 * (g * bh1) / (sg.bm + g * bh1)), per_wg2 = std::min(30e9, 50e9 * 256.0 / (sg.bm + 256.0));
+        // the LDS-direct loop's eight-stage ring holds about a third more
+        const bool deep = sg.bk == 32 && sg.bm < 256;
+        const double wg_all = deep ? 65e9 : 50e9, wg_cap = deep ? 40e9 : 30e9;
+        const double per_wg1 = std::min(wg_cap, wg_all * (g * bh1) / (sg.bm + g * bh1)), per_wg2 = std::min(wg_cap, wg_all * 256.0 / (sg.bm + 256.0));
         const double mb = cdiv(m, sg.bm), patches = cdiv(mb, sg.raster);
         const double n_s = cdiv(n1, bh1), ncb = cdiv(n2, 256);
         const double items1 = mb * n_s, items = mb * ncb * sg.splits;
@@ -265,13 +270,15 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         const double cols_per_patch = std::max(1.0, 32.0 / std::min(mb, (double)sg.raster));
         const double re1 = b1 * (patches - 1.0) + e * m * k * std::max(0.0, n_s / cols_per_patch / 8.0 - 1.0);
         const double re2 = b2 * (patches - 1.0) + e * m * n1 * std::max(0.0, ncb / cols_per_patch / 8.0 - 1.0) + e * m * n1;
-        const double t1 = b1 / std::min(d.hbm_bw, std::min(items1, (double)d.cus) * per_wg1) + re1 / d.fabric_bw + 3e-6 * cdiv(items1, d.cus);
-        const double t2 = b2 / std::min(d.hbm_bw, std::min(items, (double)d.cus) * per_wg2) + re2 / d.fabric_bw + 3e-6 * cdiv(items, d.cus);
+        // pipeline fill and epilogue per item: the LDS-direct loop primes its ring faster (measured on the m = 128 tables)
+        const double per_item = (sg.bk == 32 && sg.bm < 256) ? 1.5e-6 : 3e-6;
+        const double t1 = b1 / std::min(d.hbm_bw, std::min(items1, (double)d.cus) * per_wg1) + re1 / d.fabric_bw + per_item * cdiv(items1, d.cus);
+        const double t2 = b2 / std::min(d.hbm_bw, std::min(items, (double)d.cus) * per_wg2) + re2 / d.fabric_bw + per_item * cdiv(items, d.cus);
         // planes are written and read once; small transfers reach about half the cache rate
         const double planes = sg.splits > 1 ? 2.0 * 4.0 * m * n2 * sg.splits / (0.5 * d.fabric_bw) : 0.0;
         // matrix-core time of each phase: items run one per CU, at the block GEMM's efficiency
-        // (the 256-row LDS-direct GEMM vs the register-staged one with four waves in a row)
-        const double f_cu = d.mfma_flops * (sg.bm == 256 ? 0.48 : 0.33) / d.cus;
+        // (the LDS-direct GEMM at 256 rows, at 64 / 128 rows, and the register-staged one)
+        const double f_cu = d.mfma_flops * (sg.bm == 256 ? 0.48 : (sg.bk == 32 ? 0.45 : 0.33)) / d.cus;
         const double m1 = 2.0 * sg.bm * bh1 * g * k / f_cu * cdiv(items1, d.cus);
         const double m2 = 2.0 * sg.bm * 256.0 * sg.ksplit / f_cu * cdiv(items, d.cus);
         t->workgroups = d.cus;
@@ -321,9 +328,12 @@ void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1,
         for (int bm : bms) {
             if (bm < 128 && M > bm) continue;                 // the small blocks hold all rows or are not used
             if (bm > 32 && M <= bm / 2) continue;             // more than half a block of padding
-            static const int slices[] = {128, 64, 32};
-            for (int bh1 : slices) {
-                if (bm == 256 && bh1 != 128) continue;                        // the 256-row kernel has one slice width
+            // 128 / 64 / 32: register-staged loop with that slice width; -128: LDS-direct loop, 128 wide
+            static const int slices[] = {128, 64, 32, -128};
+            for (int sl : slices) {
+                const int bh1 = sl < 0 ? -sl : sl;
+                if (bm == 256 && sl != 128) continue;                         // the 256-row kernel has one variant
+                if (sl < 0 && bm < 64) continue;
                 if ((bh1 == 64 && bm < 64) || (bh1 == 32 && (bm != 128 || gated))) continue;
                 for (int sp : splits) {
                     if (sp > two_phase_max_splits(M, N2)) continue;
@@ -332,7 +342,7 @@ void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1,
                         ffuse_plan_t p;
                         std::memset(&p, 0, sizeof(p));
                         p.family = FFUSE_FAMILY_TWOPHASE;
-                        p.bm = bm; p.bh = bm == 256 ? (gated ? 128 : 256) : bh1; p.bn2 = 256; p.bk = 64; p.h_level = 2; p.raster = r;
+                        p.bm = bm; p.bh = bm == 256 ? (gated ? 128 : 256) : bh1; p.bn2 = 256; p.bk = (bm == 256 || sl < 0) ? 32 : 64; p.h_level = 2; p.raster = r;
                         p.splits = sp;
                         ffuse_traffic_t t;
                         traffic_model(p, dtype, gated, M, K, N1, N2, &t);

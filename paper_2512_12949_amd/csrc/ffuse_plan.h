@@ -37,6 +37,7 @@ bool exchange_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, 
 // Two-phase family: derived geometry.
 struct TwoPhaseGeometry {
     int bm;             // rows per block: 32, 64, 128 or 256
+    int bk;             // 32: LDS-direct block GEMM (always for bm = 256; optional for bm = 64 / 128 with bh1 = 128); 64: register-staged
     int bh1;            // hidden slice of a phase-1 item: 128 / 64 / 32 (bm <= 128), 256 or 128 gated (bm = 256)
     int splits, ksplit; // phase-2 ranges of the hidden dimension (splits == 1: no partial planes)
     int raster;         // row blocks per XCD patch

@@ -50,25 +50,39 @@ __device__ __forceinline__ bool map_item(int MB, int S, int raster, int xcd, int
 // that a single workgroup can only pull at ~20 GB/s, so it wants at least as many items as
 // there are CUs: 128-column slices (four waves along the columns), 64 (2 x 2 waves) or 32
 // (four waves along the rows) give N1/128, N1/64 or N1/32 of them.
-template <typename T, bool GATED, int BM, bool CONV, int BH1_> struct TwoPhaseGemms {
+template <typename T, bool GATED, int BM, bool CONV, int BH1_, bool DEEP_> struct TwoPhaseGemms {
     static constexpr int BH1 = BH1_;
     static constexpr int WM1 = BH1 == 128 ? 1 : (BH1 == 64 ? 2 : 4);
     typedef FirstGemm<T, GATED, BM, BH1, WM1, 4 / WM1, CONV> G1;   // phase 1: X * W1 (, X * W3); CONV: im2col(X) * W1
     typedef FirstGemm<T, false, BM, 256, 1, 4> G2;   // phase 2: H * W2
     static constexpr bool DEEP = false;
 };
-template <typename T, bool GATED, int BH1_> struct TwoPhaseGemms<T, GATED, 256, false, BH1_> {
+template <typename T, bool GATED, int BH1_, bool DEEP_> struct TwoPhaseGemms<T, GATED, 256, false, BH1_, DEEP_> {
     static constexpr int BH1 = GATED ? 128 : 256;
     typedef DeepGemm<T, GATED, 256, BH1, 2, 2> G1;
     typedef DeepGemm<T, false, 256, 256, 2, 2> G2;
     static constexpr bool DEEP = true;
 };
+// 64 / 128 rows with the LDS-direct block GEMM (2 x 2 waves) and a deeper ring in the first
+// phase: more bytes in flight per workgroup than the register-staged loop can hold
+template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 128, true> {
+    static constexpr int BH1 = 128;
+    typedef DeepGemm<T, GATED, 128, 128, 2, 2, GATED ? 4 : 8> G1;
+    typedef DeepGemm<T, false, 128, 256, 2, 2, 4> G2;
+    static constexpr bool DEEP = true;
+};
+template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 128, true> {
+    static constexpr int BH1 = 128;
+    typedef DeepGemm<T, GATED, 64, 128, 2, 2, GATED ? 4 : 8> G1;
+    typedef DeepGemm<T, false, 64, 256, 2, 2, 4> G2;
+    static constexpr bool DEEP = true;
+};
 
 // CONV: the first product is a 3x3 convolution (rows = pixels of a channels-last image,
 // a.K = 9 * a.conv_ic); everything after the first product's loads is unchanged.
-template <typename T, bool GATED, int BM, bool CONV = false, int BH1_ = 128>
+template <typename T, bool GATED, int BM, bool CONV = false, int BH1_ = 128, bool DEEP_ = false>
 __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
-    typedef TwoPhaseGemms<T, GATED, BM, CONV, BH1_> TG;
+    typedef TwoPhaseGemms<T, GATED, BM, CONV, BH1_, DEEP_> TG;
     typedef typename TG::G1 G1;
     typedef typename TG::G2 G2;
     constexpr int BH1 = TG::BH1, BH2 = 256;
@@ -136,7 +150,7 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
         G2::init_lds(c, tid);
         const int NCB = (a.N2 + BH2 - 1) / BH2;
         const int wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
-        const int wm = wave % (BM == 256 ? 2 : 1), wn = wave / (BM == 256 ? 2 : 1);
+        const int wm = wave % (TG::DEEP ? 2 : 1), wn = wave / (TG::DEEP ? 2 : 1);
         int rb, u;
         // slices of this phase: u = range * NCB + column block, so that neighbours share their part of H
         for (int idx = loc; map_item(MB, NCB * a.splits, a.raster, xcd, idx, rb, u); idx += GX) {
@@ -218,7 +232,12 @@ hipError_t launch_finalize_planes(int dtype, const float* part, void* Y, int64_t
     return hipGetLastError();
 }
 
-template <typename T, bool GATED> static const void* two_phase_fn(int bm, int bh1) {
+template <typename T, bool GATED> static const void* two_phase_fn(int bm, int bh1, int bk) {
+    if (bk == 32 && bh1 == 128) {   // the LDS-direct block GEMM for small row blocks
+        if (bm == 64) return (const void*)fused_two_phase_kernel<T, GATED, 64, false, 128, true>;
+        if (bm == 128) return (const void*)fused_two_phase_kernel<T, GATED, 128, false, 128, true>;
+    }
+    if (bk == 32 && bm != 256) return nullptr;
     if (bm == 32 && bh1 == 128) return (const void*)fused_two_phase_kernel<T, GATED, 32>;
     if (bm == 64 && bh1 == 128) return (const void*)fused_two_phase_kernel<T, GATED, 64>;
     if (bm == 64 && bh1 == 64) return (const void*)fused_two_phase_kernel<T, GATED, 64, false, 64>;
@@ -237,16 +256,16 @@ template <typename T> static const void* two_phase_conv_fn(int bm) {
     return nullptr;
 }
 
-hipError_t launch_fused_two_phase(int dtype, const TwoPhaseArgs& a, int bm, int bh1, int grid, hipStream_t st) {
+hipError_t launch_fused_two_phase(int dtype, const TwoPhaseArgs& a, int bm, int bh1, int bk, int grid, hipStream_t st) {
     const bool g = a.W3 != nullptr;
     const void* fn;
     if (a.conv_ic > 0) {
         // 3x3 first product: one tap per K step of 64, and the shifted addresses must fit 32 bits
-        if (g || bh1 != 128 || a.conv_ic % 64 || a.K != 9 * a.conv_ic || a.conv_h < 1 || a.conv_w < 1) return hipErrorInvalidValue;
+        if (g || bh1 != 128 || bk == 32 || a.conv_ic % 64 || a.K != 9 * a.conv_ic || a.conv_h < 1 || a.conv_w < 1) return hipErrorInvalidValue;
         fn = dtype == 0 ? two_phase_conv_fn<__bf16>(bm) : two_phase_conv_fn<_Float16>(bm);
     } else {
-        fn = dtype == 0 ? (g ? two_phase_fn<__bf16, true>(bm, bh1) : two_phase_fn<__bf16, false>(bm, bh1))
-                        : (g ? two_phase_fn<_Float16, true>(bm, bh1) : two_phase_fn<_Float16, false>(bm, bh1));
+        fn = dtype == 0 ? (g ? two_phase_fn<__bf16, true>(bm, bh1, bk) : two_phase_fn<__bf16, false>(bm, bh1, bk))
+                        : (g ? two_phase_fn<_Float16, true>(bm, bh1, bk) : two_phase_fn<_Float16, false>(bm, bh1, bk));
     }
     if (!fn || grid < 8 || (grid & 7) || a.raster < 1 || a.splits < 1) return hipErrorInvalidValue;
     TwoPhaseArgs copy = a;

@@ -126,6 +126,12 @@ def test_two_phase_narrow_hidden_slices(dtype, gated):
             plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=bh, splits=splits, raster=2)
             print(f"two-phase {dtype} gated={gated} shape {(M, K, N1, N2)} bm={bm} bh={bh} splits={splits}", flush=True)
             gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase bm={bm} bh={bh} splits={splits}")
+        for bm, splits in ((64, 2), (128, 1), (128, 3)):   # LDS-direct block GEMM on small row blocks (bk = 32)
+            if bm < 128 and M > bm:
+                continue
+            plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=128, bk=32, splits=splits, raster=2)
+            print(f"two-phase {dtype} gated={gated} shape {(M, K, N1, N2)} bm={bm} bk=32 splits={splits}", flush=True)
+            gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase bm={bm} bk=32 splits={splits}")
     if gated:   # a 32-column slice cannot serve two weight matrices
         w, host, dev = _case("narrow", 128, 64, 256, 64, dtype, act, gated)
         with pytest.raises(ff.FfuseError):
