@@ -46,13 +46,16 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     typedef typename Base::vec8 vec8;
     using Base::G; using Base::HT; using Base::MT; using Base::WHR; using Base::WMR;
     static_assert(BH == 128 || BH == 256, "unit swizzle needs 8 or 16 units of 32 bytes per row");
-    static_assert(BM % 64 == 0, "every wave issues the same number of loads");
+    static_assert(BM == 32 || BM % 64 == 0, "every wave issues the same number of loads");
+    // BM = 32: the A stage is 2 KB, half a load instruction per wave -- every wave issues one
+    // with its upper 32 lanes switched off (8 rows each)
+    static constexpr bool HALF_A = BM == 32;
     static constexpr int NS = NS_;                     // stages in the ring
     static constexpr int XB = BM * 64;                 // bytes of one A stage
     static constexpr int WB = BH * 64;                 // bytes of one B stage (one matrix)
     static constexpr int STAGE = XB + G * WB;
     static constexpr int LDS_BYTES = NS * STAGE;
-    static constexpr int XI = BM / 64;                 // A load instructions per wave per stage
+    static constexpr int XI = HALF_A ? 1 : BM / 64;    // A load instructions per wave per stage
     static constexpr int ROWB = BH * 2;                // bytes of one B row in LDS
     static constexpr int RPI = 1024 / ROWB;            // B rows per load instruction
     static constexpr int BI = 32 / RPI / 4;            // B load instructions per wave per matrix
@@ -72,6 +75,7 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         uint32_t lds_a, lds_b;  // uniform LDS byte offsets of this wave's first A / B instruction
         uint32_t rdx[MT];       // LDS read offsets: A fragments (sub-step 0)
         uint32_t rdw[HT];       //                   B fragments (sub-step 0, first half)
+        bool a_lane;            // this lane takes part in A loads (all lanes unless HALF_A)
     };
 
     static __device__ __forceinline__ void init_a(Ctx& c, const void* A, uint32_t a_bytes, uint32_t base_bytes,
@@ -80,12 +84,16 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         c.rx = make_rsrc(A, a_bytes);
         c.KX = kx;
         c.abase = base_bytes;
-        // lane i of an instruction fills slot i & 3 of row 16 q + (i >> 2): the chunk that lives there
-        const uint32_t chunk = (lane & 3) ^ ((lane >> 4) & 3u);
+        // lane i of an instruction fills slot i & 3 of the row (i >> 2) rows below the
+        // instruction's first: the chunk that lives there is slot ^ ((row >> 2) & 3), which is
+        // the same for every instruction of a wave (their first rows are 16 apart)
+        const uint32_t first = HALF_A ? (uint32_t)wave * 8u : (uint32_t)(wave * XI) * 16u;
+        const uint32_t chunk = (lane & 3) ^ (((first + (lane >> 2)) >> 2) & 3u);
         c.xk = 8u * chunk;
+        c.a_lane = !HALF_A || lane < 32;
 #pragma unroll
         for (int j = 0; j < XI; ++j) {
-            const uint32_t row = (uint32_t)(wave * XI + j) * 16u + (lane >> 2);
+            const uint32_t row = first + (uint32_t)j * 16u + (lane >> 2);
             c.xoff[j] = ((row0 + row) * lda + 8u * chunk) * 2u;
         }
     }
@@ -108,7 +116,7 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // uniform: feeds M0
         const int wm = wave % WM, wn = wave / WM;
         const uint32_t x = lane & 31, h = lane >> 5;
-        c.lds_a = (uint32_t)(wave * XI) * 1024u;
+        c.lds_a = HALF_A ? (uint32_t)wave * 512u : (uint32_t)(wave * XI) * 1024u;
         c.lds_b = XB + (uint32_t)(wave * BI) * 1024u;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -138,8 +146,9 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     static __device__ __forceinline__ void issue_one(char* stage, const Ctx& c, int kx, int kw, int xlim, bool valid, int i) {
         if (i < XI) {
             const bool ok = valid && (kx + (int)c.xk) < xlim && c.abase != kOob;
-            lds_dma16(c.rx, ok ? c.xoff[i] + c.abase + (uint32_t)kx * 2u : kOob,
-                      (uint32_t)(uintptr_t)stage + c.lds_a + (uint32_t)i * 1024u);
+            if (!HALF_A || c.a_lane)
+                lds_dma16(c.rx, ok ? c.xoff[i] + c.abase + (uint32_t)kx * 2u : kOob,
+                          (uint32_t)(uintptr_t)stage + c.lds_a + (uint32_t)i * 1024u);
         } else {
             const int which = (i - XI) / BI, j = (i - XI) % BI;
             const uint32_t off = c.boff[j];

@@ -104,7 +104,7 @@ bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1,
         }
     }
     g->bk = bm == 256 ? 32 : (p.bk == 32 ? 32 : 64);
-    if (g->bk == 32 && bm != 256 && (bm < 64 || g->bh1 != 128)) return false;
+    if (g->bk == 32 && bm != 256 && g->bh1 != 128) return false;
     const int64_t mb = (M + bm - 1) / bm;
     g->raster = p.raster > 0 ? p.raster : 1;
     if (g->raster > mb) g->raster = (int)mb;
@@ -333,7 +333,6 @@ void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1,
             for (int sl : slices) {
                 const int bh1 = sl < 0 ? -sl : sl;
                 if (bm == 256 && sl != 128) continue;                         // the 256-row kernel has one variant
-                if (sl < 0 && bm < 64) continue;
                 if ((bh1 == 64 && bm < 64) || (bh1 == 32 && (bm != 128 || gated))) continue;
                 for (int sp : splits) {
                     if (sp > two_phase_max_splits(M, N2)) continue;

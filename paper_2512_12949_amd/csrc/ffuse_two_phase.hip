@@ -71,6 +71,12 @@ template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 128
     typedef DeepGemm<T, false, 128, 256, 2, 2, 4> G2;
     static constexpr bool DEEP = true;
 };
+template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 32, false, 128, true> {
+    static constexpr int BH1 = 128;
+    typedef DeepGemm<T, GATED, 32, 128, 1, 4, 8> G1;
+    typedef DeepGemm<T, false, 32, 256, 1, 4, 8> G2;
+    static constexpr bool DEEP = true;
+};
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 128, true> {
     static constexpr int BH1 = 128;
     typedef DeepGemm<T, GATED, 64, 128, 2, 2, GATED ? 4 : 8> G1;
@@ -150,7 +156,8 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
         G2::init_lds(c, tid);
         const int NCB = (a.N2 + BH2 - 1) / BH2;
         const int wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
-        const int wm = wave % (TG::DEEP ? 2 : 1), wn = wave / (TG::DEEP ? 2 : 1);
+        constexpr int WM2 = G2::WMR == BM ? 1 : 2;   // waves along the rows of a phase-2 tile
+        const int wm = wave % WM2, wn = wave / WM2;
         int rb, u;
         // slices of this phase: u = range * NCB + column block, so that neighbours share their part of H
         for (int idx = loc; map_item(MB, NCB * a.splits, a.raster, xcd, idx, rb, u); idx += GX) {
@@ -234,6 +241,7 @@ hipError_t launch_finalize_planes(int dtype, const float* part, void* Y, int64_t
 
 template <typename T, bool GATED> static const void* two_phase_fn(int bm, int bh1, int bk) {
     if (bk == 32 && bh1 == 128) {   // the LDS-direct block GEMM for small row blocks
+        if (bm == 32) return (const void*)fused_two_phase_kernel<T, GATED, 32, false, 128, true>;
         if (bm == 64) return (const void*)fused_two_phase_kernel<T, GATED, 64, false, 128, true>;
         if (bm == 128) return (const void*)fused_two_phase_kernel<T, GATED, 128, false, 128, true>;
     }

@@ -91,6 +91,8 @@ def test_two_phase_small_m_family(dtype, gated):
             print(f"two-phase {dtype} gated={gated} shape {(M, K, N1, N2)} splits={splits}", flush=True)
             gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase splits={splits}")
             gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase splits={splits} again")
+            deep = ff.make_plan(ff.FAMILY_TWOPHASE, bh=128, bk=32, splits=splits)   # LDS-direct loop, row block picked from M
+            gu.check(gu.run(w, dev, plan=deep), ref, dtype, what=f"two-phase bk=32 splits={splits}")
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
