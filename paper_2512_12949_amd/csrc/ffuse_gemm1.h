@@ -37,7 +37,7 @@ namespace ffuse {
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-// NS_: stages in the ring (a power of two, 4 or 8): loads run NS_ - 1 stages ahead.  Four keeps a
+// NS_: stages in the ring (a power of two, 4 to 16): loads run NS_ - 1 stages ahead.  Four keeps a
 // 256 x 256 tile fed; eight is for small tiles in the weight-streaming regime, where the
 // bytes a workgroup keeps in flight set the rate at which it can pull weights.
 template <typename T, bool GATED, int BM, int BH, int WM, int WN, int NS_ = 4>
@@ -62,7 +62,7 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     static constexpr int NLOAD = XI + G * BI;          // load instructions per wave per stage
     static constexpr int NM = HT * MT * G;             // MFMAs per wave per sub-step
     static constexpr int NR = MT + HT * G;             // fragment reads per wave per sub-step
-    static_assert((NS == 4 || NS == 8) && (NS - 2) * NLOAD <= 63, "ring depth: the vmcnt field holds 6 bits");
+    static_assert((NS == 4 || NS == 8 || NS == 16) && (NS - 2) * NLOAD <= 63, "ring depth: the vmcnt field holds 6 bits");
 
     struct Ctx {
         __amdgpu_buffer_rsrc_t rx, rw[G];

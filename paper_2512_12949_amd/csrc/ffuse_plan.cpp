@@ -90,7 +90,7 @@ bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1,
     int bm = p.bm;
     if (bm <= 0) bm = M <= 32 ? 32 : (M <= 64 ? 64 : (M <= 512 ? 128 : 256));
     if (bm != 32 && bm != 64 && bm != 128 && bm != 256) return false;
-    if (bm < 128 && M > bm) return false;   // the small blocks are for a single row block
+    if (bm < 128 && M > 4 * bm) return false;   // the small blocks are for a few row blocks at most
     g->bm = bm;
     // hidden slice of a phase-1 item: the plan's bh where the kernels implement it
     if (bm == 256) {
@@ -326,7 +326,7 @@ void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1,
         static const int bms[] = {32, 64, 128, 256};
         static const int rasters2[] = {4, 2, 8, 1};   // the model does not tell these apart: measured order of preference
         for (int bm : bms) {
-            if (bm < 128 && M > bm) continue;                 // the small blocks hold all rows or are not used
+            if (bm < 128 && M > bm) continue;                 // measured: several small row blocks lose to one larger one
             if (bm > 32 && M <= bm / 2) continue;             // more than half a block of padding
             // 128 / 64 / 32: register-staged loop with that slice width; -128: LDS-direct loop, 128 wide
             static const int slices[] = {128, 64, 32, -128};

@@ -73,7 +73,7 @@ template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 128
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 32, false, 128, true> {
     static constexpr int BH1 = 128;
-    typedef DeepGemm<T, GATED, 32, 128, 1, 4, 8> G1;
+    typedef DeepGemm<T, GATED, 32, 128, 1, 4, 8> G1;   // (a sixteen-stage ring measured no faster)
     typedef DeepGemm<T, false, 32, 256, 1, 4, 8> G2;
     static constexpr bool DEEP = true;
 };
@@ -94,7 +94,9 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
     constexpr int BH1 = TG::BH1, BH2 = 256;
     constexpr int LDS_BYTES = G1::LDS_BYTES > G2::LDS_BYTES ? G1::LDS_BYTES : G2::LDS_BYTES;
     __shared__ __attribute__((aligned(16))) char smem[LDS_BYTES];
-    __shared__ uint32_t verdict;
+    // the barrier's verdict word lives in the stage memory, which is idle between the phases
+    // (the deepest ring takes all 160 KB)
+    volatile uint32_t& verdict = *reinterpret_cast<volatile uint32_t*>(smem);
     const int tid = threadIdx.x;
     const int G = gridDim.x, GX = G >> 3;             // workgroups, workgroups per XCD
     const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
@@ -146,6 +148,7 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
     __syncthreads();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     const bool ok = verdict != 0;
+    __syncthreads();   // everybody has read the word before phase 2's loads reuse its place
     if (a.stats) t2 = wall_clock64();
 
     // ---------------------------------------------------------------- phase 2

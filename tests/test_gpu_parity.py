@@ -134,6 +134,12 @@ def test_two_phase_narrow_hidden_slices(dtype, gated):
             plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=128, bk=32, splits=splits, raster=2)
             print(f"two-phase {dtype} gated={gated} shape {(M, K, N1, N2)} bm={bm} bk=32 splits={splits}", flush=True)
             gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase bm={bm} bk=32 splits={splits}")
+        for bm, bk in ((32, 64), (32, 32), (64, 64), (64, 32)):   # a few small row blocks instead of one large one
+            if M > 4 * bm:
+                continue
+            plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=128, bk=bk, splits=2, raster=2)
+            print(f"two-phase {dtype} gated={gated} shape {(M, K, N1, N2)} bm={bm} bk={bk} in {-(-M // bm)} row blocks", flush=True)
+            gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase bm={bm} bk={bk} row blocks")
     if gated:   # a 32-column slice cannot serve two weight matrices
         w, host, dev = _case("narrow", 128, 64, 256, 64, dtype, act, gated)
         with pytest.raises(ff.FfuseError):
