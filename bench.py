@@ -105,6 +105,30 @@ def main():
     t_unf, k_unf = timed(unfused, max(3, args.steps // 2), 2)
     diff = float((Y_fused.float() - Y.float()).abs().max() / Y.float().abs().max())
 
+    # context: the vendor library's unfused chain on the same tensors (hipBLASLt GEMMs through
+    # torch.matmul plus torch's elementwise kernels); not part of the hot path
+    t_vendor = None
+    if w.dtype != "f32":
+        def vendor_step():
+            h = torch.matmul(dev["X"], dev["W1"])
+            if w.act == 1:
+                h = torch.relu(h)
+            elif w.act == 2:
+                h = torch.nn.functional.gelu(h, approximate="tanh")
+            elif w.act == 3:
+                h = torch.nn.functional.silu(h)
+            if w.gated:
+                h = h * torch.matmul(dev["X"], dev["W3"])
+            return torch.matmul(h, dev["W2"])
+        for _ in range(3):
+            vendor_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(max(3, args.steps // 2)):
+            vendor_step()
+        torch.cuda.synchronize()
+        t_vendor = (time.perf_counter() - t0) / max(3, args.steps // 2)
+
     flops = float(w.flops())
     value = flops / t_fused * 1e-12
     decode = w.M <= 128 and flops / w.q_min() < 300.0
@@ -137,6 +161,7 @@ def main():
         "bytes": {"q_min": w.q_min(), "q_unfused": w.q_unfused(), "model_hbm": model["hbm_bytes"],
                   "model_reduce": model["reduce_bytes"], "model_fabric": model["fabric_bytes"]},
         "model_t_pred_ms": model["t_pred"] * 1e3,
+        "vendor_unfused_ms": None if t_vendor is None else t_vendor * 1e3,
     }
 
     if not args.no_cpu_baseline:
