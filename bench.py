@@ -41,7 +41,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards by rows or by hidden slices, see DESIGN.md).", file=sys.stderr)
+              "(the path would shard by rows or by hidden slices; that is not built).", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -3,10 +3,11 @@
 //     activated slice never leaves registers; partial second products are summed across
 //     hidden slices with fp32 atomics (paper Sec. 4.1 "reduce" strategy, with the hidden
 //     split taking the place of the cluster's n dimension).
-//   * fused_exchange_kernel -- persistent cooperative kernel; on every XCD some workgroups
-//     produce activated tiles into a ring buffer that stays in that XCD's L2, the others
-//     consume them into register-resident output tiles (Sec. 4.1 "shuffle" strategy with
-//     the XCD as the cluster and its L2 as the shared on-chip pool).
+//   * fused_exchange_kernel -- persistent kernel, one workgroup per CU; on every XCD some
+//     workgroups produce activated tiles into a ring buffer read through that XCD's L2, the
+//     others consume them into register-resident output tiles (Sec. 4.1 "shuffle" strategy
+//     with the XCD as the cluster and its L2 as the shared on-chip pool).
+//   (the two-phase family, the default, lives in ffuse_two_phase.hip)
 //   * finalize_kernel       -- fp32 sums -> Y in the operand type, workspace back to zero.
 //   * gemm_act_kernel       -- plain GEMM with the activation/gate epilogue: the two launches
 //     of the unfused comparison path.
@@ -353,7 +354,7 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
 
     {
         // ------------------------------------------------------------------ producer
-        // Round 0: the first E = min(workgroups, ring slots) items are produced by ALL
+        // Pass 0: the first E = min(workgroups, ring slots) items are produced by ALL
         // workgroups of the group (consumers have nothing to multiply yet, and no slot is
         // being reused, so nobody waits).  After that producer q makes items E + q, E + q + P, ...
         f32x16 acc[GP::HT][GP::MT];
