@@ -62,7 +62,8 @@ typedef enum {
     FFUSE_ERR_ARCH = -7,      /* the current device is not gfx950                          */
     FFUSE_ERR_PLAN = -8,      /* a forced plan is not valid for this problem               */
     FFUSE_ERR_TIMEOUT = -9,   /* a cooperative kernel gave up waiting for a peer workgroup  */
-    FFUSE_ERR_PLACEMENT = -10 /* workgroups of an exchange group did not share one XCD      */
+    FFUSE_ERR_PLACEMENT = -10 /* an XCD received more workgroups of an exchange launch than
+                                 its share (dispatch was not round robin over the XCDs)     */
 } ffuse_status_t;
 
 /*
@@ -102,7 +103,8 @@ typedef struct {
     int32_t producers;/* exchange family: producer workgroups per XCD group (0 = default)  */
     int32_t ring;     /* exchange family: ring slots per XCD group (0 = default)           */
     int32_t coherent; /* exchange family: 0 = ring kept coherent through the XCD's shared L2
-                         (needs group x on XCD x, checked on the device); 1 = agent-scope
+                         (groups form by the XCD a workgroup runs on; needs an even spread of the
+                         launch over the XCDs, checked on the device); 1 = agent-scope
                          release/acquire, valid for any placement, much slower            */
     int32_t reserved[1];
 } ffuse_plan_t;

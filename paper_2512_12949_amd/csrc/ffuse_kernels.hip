@@ -246,10 +246,10 @@ __global__ __launch_bounds__(256) void gemm_act_kernel(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Fused chain, "exchange" family.  One persistent workgroup per CU, launched cooperatively
-// so that all of them are resident.  The workgroups with blockIdx % 8 == x form group x
-// (one XCD under round-robin dispatch); within a group the first P are producers, the next
-// PG*NCT are consumers:
+// Fused chain, "exchange" family.  One persistent workgroup per CU, all resident.  The
+// workgroups that run on XCD x form group x (numbered by order of arrival; under round-robin
+// dispatch every XCD gets the same number); within a group the first P are producers, the
+// next PG*NCT are consumers:
 //   producer q  : H tile (256 rows x BHP hidden) = act(X W1)[.* X W3] for item o = q, q+P, ...
 //                 written to ring slot o % R in the operand type, then ready[slot] = o + 1
 //   consumer c  : owns output tile (panel pi = c / NCT, 256 columns ct = c % NCT) of the group
@@ -258,8 +258,8 @@ __global__ __launch_bounds__(256) void gemm_act_kernel(GemmArgs a) {
 //                 register accumulators, then done[slot] += 1; after the last h it stores Y.
 // Items are ordered (group of panels g, hidden tile h, panel in group pi); a producer may
 // overwrite slot s only when the NCT consumers of the item that used it R items earlier are
-// done.  Flags are agent-scope release/acquire, so results do not depend on where
-// workgroups land; placement on one XCD only makes the ring traffic L2 hits.
+// done.  How ring and flags are kept coherent is described below (XCD-local by default,
+// agent-scope release/acquire on request).
 // All waits are bounded: on expiry the error word is set and every workgroup leaves.
 // ---------------------------------------------------------------------------------------
 static constexpr uint32_t kSpinLimit = 1u << 23;
@@ -323,17 +323,39 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
     static_assert(GC::NS == 4 && SPI % GC::NS == 0 && SPI > 3, "an item is a whole number of turns of the four-stage ring");
     __shared__ __attribute__((aligned(16))) char smem[LDS_BYTES];
     const int tid = threadIdx.x;
-    const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
-    const int P = a.P, NCT = a.NCT, PG = a.PG, R = a.R, NH = a.NH;
+    const int coherent = a.coherent;
+    const int R = a.R;
+    uint32_t* err = a.flags + 16 * R;
+    // Which group, and which member of it, is this workgroup?  XCD-local protocol: the group
+    // is the XCD the workgroup really runs on (read from the hardware) and the member number
+    // is the order of arrival on that XCD, counted in rank[xcd] -- dispatch is round robin
+    // over the XCDs, but where it starts is not ours to assume.  An XCD that receives more
+    // than its share reports FFUSE_ERR_PLACEMENT; one that receives fewer runs into the
+    // bounded waits.  Coherent protocol: any placement works, groups follow blockIdx.
+    int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
+    if (!coherent) {
+        uint32_t xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(xcc));
+        uint32_t* rank = err + 1;
+        uint32_t* slot0 = reinterpret_cast<uint32_t*>(smem);
+        if (tid == 0) *slot0 = __hip_atomic_fetch_add(rank + (xcc & 7u), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        xcd = (int)(xcc & 7u);
+        loc = (int)*slot0;
+        __syncthreads();
+        if (loc >= (int)(gridDim.x >> 3)) {
+            if (tid == 0) __hip_atomic_fetch_or(err, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+    }
+    const int P = a.P, NCT = a.NCT, PG = a.PG, NH = a.NH;
     const int NP = (int)((a.M + 255) / 256);
     const int NG = (NP + PG - 1) / PG;                       // groups of panels
     const int ngx = (NG > xcd) ? (NG - xcd + 7) / 8 : 0;      // groups handled by this XCD
     const int items = ngx * NH * PG;
     uint32_t* ready = a.flags + xcd * 2 * R;
     uint32_t* done = ready + R;
-    uint32_t* err = a.flags + 16 * R;
     char* ring = a.ring + (size_t)xcd * R * SLOT_BYTES;
-    const int coherent = a.coherent;
     ExchStats es;
     if (a.stats) es.t0 = wall_clock64();
     auto finish = [&](int role, int n) {
@@ -342,15 +364,6 @@ __global__ __launch_bounds__(256) void fused_exchange_kernel(ExchangeArgs a) {
             p[0] = (uint64_t)role | (es.gemm << 8); p[1] = wall_clock64() - es.t0; p[2] = es.wait; p[3] = (uint64_t)n | (es.epi << 32);
         }
     };
-    if (!coherent) {
-        // the fast protocol needs every workgroup of group x on XCD x
-        uint32_t xcc;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(xcc));
-        if ((int)xcc != xcd) {
-            if (tid == 0) __hip_atomic_fetch_or(err, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            return;
-        }
-    }
 
     {
         // ------------------------------------------------------------------ producer
