@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--plan", default="", help="force a plan: family,bm,bh[,raster[,splits[,producers[,ring]]]]")
     ap.add_argument("--tune", type=int, default=6,
                     help="before timing, profile the K analytically best plans on the device and use the fastest (0 = model's choice)")
+    ap.add_argument("--model-check", type=int, default=0,
+                    help="instead of the benchmark line: time the model's N best-ranked plans and print predicted vs measured")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -79,6 +81,8 @@ def main():
         # offline step of the method (plans are fixed per M bin ahead of time): not part of the timed region
         ff.ffuse_tune(dt, dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y, top_k=args.tune, reps=5)
     fused, unfused = ff.FUSED[w.dtype], ff.UNFUSED[w.dtype]
+    if args.model_check > 0:
+        return model_check(args, ff, w, dev, Y, dt, nws, torch)
 
     def step(fn):
         fn(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y)
@@ -185,6 +189,54 @@ def main():
         torch.cuda.synchronize()
         torch.mul(src, 1.0, out=dst)
         torch.cuda.synchronize()
+    ff.ffuse_set_workspace(None)
+    print(json.dumps(out))
+
+
+def model_check(args, ff, w, dev, Y, dt, nws, torch):
+    """Validation of the traffic model (the paper validates its cost model the same way): every
+    one of the N best-ranked plans is timed; reports rank correlation and the regret of
+    trusting the model's first choice."""
+    fn = ff.FUSED[w.dtype]
+    rows = []
+    for plan, t_pred in ff.ffuse_rank_plans(dt, w.act, w.gated, w.M, w.K, w.N1, w.N2):
+        if len(rows) >= args.model_check:
+            break
+        ff.ffuse_force_plan(plan)
+        if fn(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y, check=False) != 0:   # does not fit this workspace
+            continue
+        if ff.ffuse_sync_status(check=False) != 0:
+            continue
+        for _ in range(3):
+            fn(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y)
+        e1.record()
+        torch.cuda.synchronize()
+        d = plan.as_dict()
+        rows.append({"plan": {k: d[k] for k in ("family", "bm", "bh", "bk", "splits", "raster", "producers")},
+                     "model_us": t_pred * 1e6, "measured_us": e0.elapsed_time(e1) / args.steps * 1e3})
+    ff.ffuse_force_plan(None)
+
+    def ranks(v):
+        order = sorted(range(len(v)), key=lambda i: v[i])
+        r = [0.0] * len(v)
+        for pos, i in enumerate(order):
+            r[i] = float(pos)
+        return r
+    a, b = ranks([r["model_us"] for r in rows]), ranks([r["measured_us"] for r in rows])
+    n = len(rows)
+    ma, mb = sum(a) / n, sum(b) / n
+    cov = sum((x - ma) * (y - mb) for x, y in zip(a, b))
+    var = (sum((x - ma) ** 2 for x in a) * sum((y - mb) ** 2 for y in b)) ** 0.5
+    best = min(r["measured_us"] for r in rows)
+    out = {"workload": w.name, "plans_timed": n, "spearman_rank_correlation": cov / var if var else 1.0,
+           "model_first_choice_us": rows[0]["measured_us"], "best_measured_us": best,
+           "regret_of_first_choice": rows[0]["measured_us"] / best - 1.0,
+           "best_measured_is_model_rank": 1 + min(range(n), key=lambda i: rows[i]["measured_us"]), "plans": rows}
     ff.ffuse_set_workspace(None)
     print(json.dumps(out))
 

@@ -204,6 +204,11 @@ int ffuse_tune(int dtype, const void* X, const void* W1, const void* W3, const v
 int ffuse_plan_lookup(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
                       ffuse_plan_t* out, double* tuned_ms);
 int ffuse_plan_table_clear(void);
+/* The model's ranking itself (host only): writes up to `capacity` plans in order of increasing
+ * predicted time (seconds in t_pred_s, which may be NULL) and returns how many, or a negative
+ * status. */
+int ffuse_rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
+                     ffuse_plan_t* plans, double* t_pred_s, int capacity);
 
 /* ---- measurement aid: when enabled, the library brackets the dominant kernel of every
  *      fused / unfused call with HIP events on the call's stream.  ffuse_profile_read

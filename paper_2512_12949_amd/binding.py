@@ -23,7 +23,7 @@ EXPORTS = [
     "ffuse_ffn_unfused", "ffuse_ffn_unfused_f16", "ffuse_ffn_unfused_f32",
     "ffuse_workspace_bytes", "ffuse_set_workspace", "ffuse_choose_plan", "ffuse_traffic_model",
     "ffuse_force_plan", "ffuse_last_plan", "ffuse_sync_status", "ffuse_profile_enable", "ffuse_profile_read",
-    "ffuse_tune", "ffuse_plan_lookup", "ffuse_plan_table_clear", "ffuse_conv_chain", "ffuse_conv_chain_f16",
+    "ffuse_tune", "ffuse_plan_lookup", "ffuse_plan_table_clear", "ffuse_conv_chain", "ffuse_conv_chain_f16", "ffuse_rank_plans",
     "ffuse_status_string", "ffuse_version",
 ]
 
@@ -95,6 +95,8 @@ def lib():
         L.ffuse_plan_lookup.restype = ci
         L.ffuse_plan_lookup.argtypes = [ci, ci, ci, i64, i64, i64, i64, ctypes.POINTER(Plan), ctypes.POINTER(ctypes.c_double)]
         L.ffuse_plan_table_clear.restype = ci
+        L.ffuse_rank_plans.restype = ci
+        L.ffuse_rank_plans.argtypes = [ci, ci, ci, i64, i64, i64, i64, ctypes.POINTER(Plan), ctypes.POINTER(ctypes.c_double), ci]
         for name in ("ffuse_conv_chain", "ffuse_conv_chain_f16"):
             f = getattr(L, name)
             f.restype = ci
@@ -223,6 +225,21 @@ def ffuse_plan_lookup(dtype, act, gated, M, K, N1, N2):
     _check(lib().ffuse_plan_lookup(int(dtype), int(act), int(bool(gated)), M, K, N1, N2, ctypes.byref(p), ctypes.byref(ms)),
            "ffuse_plan_lookup")
     return p, ms.value
+
+
+def ffuse_rank_plans(dtype, act, gated, M, K, N1, N2, capacity=256):
+    """The model's ranking: list of (plan, predicted seconds), best first."""
+    plans = (Plan * capacity)()
+    t = (ctypes.c_double * capacity)()
+    n = lib().ffuse_rank_plans(int(dtype), int(act), int(bool(gated)), M, K, N1, N2, plans, t, capacity)
+    if n < 0:
+        raise FfuseError(n, "ffuse_rank_plans")
+    out = []
+    for i in range(n):
+        p = Plan()
+        ctypes.memmove(ctypes.byref(p), ctypes.byref(plans[i]), ctypes.sizeof(Plan))
+        out.append((p, t[i]))
+    return out
 
 
 def ffuse_plan_table_clear():

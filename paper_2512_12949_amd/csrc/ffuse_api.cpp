@@ -540,6 +540,23 @@ int ffuse_conv_chain_f16(const void* X, const void* W1, const void* W2, int act,
     return run_conv_chain(FFUSE_DT_F16, X, W1, W2, act, B, H, W, IC, OC1, OC2, k1, k2, Y, stream);
 }
 
+int ffuse_rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* plans,
+                     double* t_pred_s, int capacity) {
+    if (!plans || capacity < 1) return FFUSE_ERR_NULL;
+    if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F32) return FFUSE_ERR_ACT;
+    if (M < 1 || K < 8 || N1 < 8 || N2 < 8) return FFUSE_ERR_SHAPE;
+    std::vector<ffuse::RankedPlan> ranked;
+    ffuse::rank_plans(dtype, act, gated ? 1 : 0, M, K, N1, N2, &ranked);
+    int n = 0;
+    for (const auto& r : ranked) {
+        if (n >= capacity) break;
+        plans[n] = r.plan;
+        if (t_pred_s) t_pred_s[n] = r.t_pred;
+        ++n;
+    }
+    return n;
+}
+
 int ffuse_plan_table_clear(void) {
     std::lock_guard<std::mutex> lock(g.mu);
     g.table.clear();
