@@ -15,7 +15,7 @@
 //                        is realised by WHICH global chunk each lane fetches, because an
 //                        LDS-direct load writes lane i's 16 bytes at base + 16*i.
 //   B stage [32 k][BH] : kept in its global orientation, rows of BH*2 bytes; 32-byte units
-//                        within a row are XOR-swizzled with (k & 3) << 1 so that the four
+//                        within a row are XOR-swizzled with a key of k so that the four
 //                        k-rows one transposing read touches fall into different banks.
 //   ds_read_b64_tr_b16 : in every group of 16 lanes, lanes 4j..4j+3 supply the address of 16
 //                        consecutive n of row k0 + j; lane L receives (k0..k0+3, n0 + L).
@@ -45,7 +45,12 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     typedef FirstGemm<T, GATED, BM, BH, WM, WN> Base;
     typedef typename Base::vec8 vec8;
     using Base::G; using Base::HT; using Base::MT; using Base::WHR; using Base::WMR;
-    static_assert(BH == 128 || BH == 256, "unit swizzle needs 8 or 16 units of 32 bytes per row");
+    static_assert(BH == 64 || BH == 128 || BH == 256, "unit swizzle is defined for rows of 4, 8 or 16 units of 32 bytes");
+    // XOR key of the 32-byte units of B row k: the four k-rows one transposing read touches
+    // must land in four different 32-byte bank groups.  Rows of 256 or 512 bytes all start in
+    // the same bank, so each of the four gets its own key; rows of 128 bytes alternate
+    // between two banks already, so rows k and k + 2 need different keys.
+    static __device__ __forceinline__ uint32_t bkey(uint32_t k) { return BH == 64 ? (k & 2u) : ((k & 3u) << 1); }
     static_assert(BM == 32 || BM % 64 == 0, "every wave issues the same number of loads");
     // BM = 32: the A stage is 2 KB, half a load instruction per wave -- every wave issues one
     // with its upper 32 lanes switched off (8 rows each)
@@ -107,7 +112,7 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         for (int j = 0; j < BI; ++j) {
             const uint32_t byte = (uint32_t)(wave * BI + j) * 1024u + 16u * lane;   // within the B stage
             const uint32_t k = byte / ROWB, pp = (byte % ROWB) / 16u;             // row, 16-byte position
-            const uint32_t p = ((((pp >> 1) ^ ((k & 3u) << 1)) << 1) | (pp & 1u));   // global chunk stored there
+            const uint32_t p = ((((pp >> 1) ^ bkey(k)) << 1) | (pp & 1u));   // global chunk stored there
             const uint32_t col = n0 + 8u * p;
             c.boff[j] = col < ncols ? (k * ldb + col) * 2u : kOob;
         }
@@ -127,7 +132,7 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht) {
             const uint32_t u = (uint32_t)(wn * WHR + 32 * ht) / 16u + (gidx & 1u);
-            c.rdw[ht] = XB + (8u * (gidx >> 1) + jj) * ROWB + ((u ^ (jj << 1)) * 32u) + 8u * q;
+            c.rdw[ht] = XB + (8u * (gidx >> 1) + jj) * ROWB + ((u ^ bkey(jj)) * 32u) + 8u * q;   // bkey(k) = bkey(jj): k = jj mod 4
         }
     }
 

@@ -104,7 +104,7 @@ bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1,
         }
     }
     g->bk = bm == 256 ? 32 : (p.bk == 32 ? 32 : 64);
-    if (g->bk == 32 && bm != 256 && g->bh1 != 128) return false;
+    if (g->bk == 32 && bm != 256 && !(g->bh1 == 128 || (g->bh1 == 64 && bm >= 64))) return false;
     const int64_t mb = (M + bm - 1) / bm;
     g->raster = p.raster > 0 ? p.raster : 1;
     if (g->raster > mb) g->raster = (int)mb;
@@ -261,8 +261,11 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         // (and never more than ~30 GB/s: three K steps of loads against a loaded memory latency)
         // the LDS-direct loop's eight-stage ring holds about a third more
         const bool deep = sg.bk == 32 && sg.bm < 256;
+        // (the second phase's ring has eight stages only for 32-row blocks)
+        const bool deep2 = deep && sg.bm == 32;
         const double wg_all = deep ? 65e9 : 50e9, wg_cap = deep ? 40e9 : 30e9;
-        const double per_wg1 = std::min(wg_cap, wg_all * (g * bh1) / (sg.bm + g * bh1)), per_wg2 = std::min(wg_cap, wg_all * 256.0 / (sg.bm + 256.0));
+        const double wg_all2 = deep2 ? 65e9 : 50e9, wg_cap2 = deep2 ? 40e9 : 30e9;
+        const double per_wg1 = std::min(wg_cap, wg_all * (g * bh1) / (sg.bm + g * bh1)), per_wg2 = std::min(wg_cap2, wg_all2 * 256.0 / (sg.bm + 256.0));
         const double mb = cdiv(m, sg.bm), patches = cdiv(mb, sg.raster);
         const double n_s = cdiv(n1, bh1), ncb = cdiv(n2, 256);
         const double items1 = mb * n_s, items = mb * ncb * sg.splits;
@@ -328,8 +331,8 @@ void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1,
         for (int bm : bms) {
             if (bm < 128 && M > bm) continue;                 // measured: several small row blocks lose to one larger one
             if (bm > 32 && M <= bm / 2) continue;             // more than half a block of padding
-            // 128 / 64 / 32: register-staged loop with that slice width; -128: LDS-direct loop, 128 wide
-            static const int slices[] = {128, 64, 32, -128};
+            // 128 / 64 / 32: register-staged loop with that slice width; -128 / -64: LDS-direct loop
+            static const int slices[] = {128, 64, 32, -128, -64};
             for (int sl : slices) {
                 const int bh1 = sl < 0 ? -sl : sl;
                 if (bm == 256 && sl != 128) continue;                         // the 256-row kernel has one variant

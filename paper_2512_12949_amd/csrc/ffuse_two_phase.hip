@@ -71,6 +71,18 @@ template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 128
     typedef DeepGemm<T, false, 128, 256, 2, 2, 4> G2;
     static constexpr bool DEEP = true;
 };
+template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 64, true> {
+    static constexpr int BH1 = 64;
+    typedef DeepGemm<T, GATED, 128, 64, 2, 2, 8> G1;
+    typedef DeepGemm<T, false, 128, 256, 2, 2, 4> G2;
+    static constexpr bool DEEP = true;
+};
+template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 64, true> {
+    static constexpr int BH1 = 64;
+    typedef DeepGemm<T, GATED, 64, 64, 2, 2, 8> G1;
+    typedef DeepGemm<T, false, 64, 256, 2, 2, 4> G2;
+    static constexpr bool DEEP = true;
+};
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 32, false, 128, true> {
     static constexpr int BH1 = 128;
     typedef DeepGemm<T, GATED, 32, 128, 1, 4, 8> G1;   // (a sixteen-stage ring measured no faster)
@@ -247,6 +259,10 @@ template <typename T, bool GATED> static const void* two_phase_fn(int bm, int bh
         if (bm == 32) return (const void*)fused_two_phase_kernel<T, GATED, 32, false, 128, true>;
         if (bm == 64) return (const void*)fused_two_phase_kernel<T, GATED, 64, false, 128, true>;
         if (bm == 128) return (const void*)fused_two_phase_kernel<T, GATED, 128, false, 128, true>;
+    }
+    if (bk == 32 && bh1 == 64) {
+        if (bm == 64) return (const void*)fused_two_phase_kernel<T, GATED, 64, false, 64, true>;
+        if (bm == 128) return (const void*)fused_two_phase_kernel<T, GATED, 128, false, 64, true>;
     }
     if (bk == 32 && bm != 256) return nullptr;
     if (bm == 32 && bh1 == 128) return (const void*)fused_two_phase_kernel<T, GATED, 32>;

@@ -128,12 +128,12 @@ def test_two_phase_narrow_hidden_slices(dtype, gated):
             plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=bh, splits=splits, raster=2)
             print(f"two-phase {dtype} gated={gated} shape {(M, K, N1, N2)} bm={bm} bh={bh} splits={splits}", flush=True)
             gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase bm={bm} bh={bh} splits={splits}")
-        for bm, splits in ((64, 2), (128, 1), (128, 3)):   # LDS-direct block GEMM on small row blocks (bk = 32)
-            if bm < 128 and M > bm:
+        for bm, bh, splits in ((64, 128, 2), (128, 128, 1), (128, 128, 3), (64, 64, 2), (128, 64, 1), (128, 64, 3)):
+            if bm < 128 and M > bm:    # LDS-direct block GEMM on small row blocks (bk = 32), 128- and 64-column slices
                 continue
-            plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=128, bk=32, splits=splits, raster=2)
-            print(f"two-phase {dtype} gated={gated} shape {(M, K, N1, N2)} bm={bm} bk=32 splits={splits}", flush=True)
-            gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase bm={bm} bk=32 splits={splits}")
+            plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=bh, bk=32, splits=splits, raster=2)
+            print(f"two-phase {dtype} gated={gated} shape {(M, K, N1, N2)} bm={bm} bh={bh} bk=32 splits={splits}", flush=True)
+            gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=f"two-phase bm={bm} bh={bh} bk=32 splits={splits}")
         for bm, bk in ((32, 64), (32, 32), (64, 64), (64, 32)):   # a few small row blocks instead of one large one
             if M > 4 * bm:
                 continue
