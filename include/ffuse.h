@@ -204,6 +204,14 @@ int ffuse_tune(int dtype, const void* X, const void* W1, const void* W3, const v
 int ffuse_plan_lookup(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
                       ffuse_plan_t* out, double* tuned_ms);
 int ffuse_plan_table_clear(void);
+/* The offline side of the table: enter a plan for M's bin by hand (ms: its measured time, any
+ * positive number), write the measured entries to a text file, read them back (entries are
+ * checked against the concrete M when they are used).  save / load return the number of
+ * entries written / read, or a negative status (FFUSE_ERR_LAUNCH: the file cannot be opened). */
+int ffuse_plan_table_set(int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
+                         const ffuse_plan_t* plan, double ms);
+int ffuse_plan_table_save(const char* path);
+int ffuse_plan_table_load(const char* path);
 /* The model's ranking itself (host only): writes up to `capacity` plans in order of increasing
  * predicted time (seconds in t_pred_s, which may be NULL) and returns how many, or a negative
  * status. */

@@ -24,6 +24,7 @@ EXPORTS = [
     "ffuse_workspace_bytes", "ffuse_set_workspace", "ffuse_choose_plan", "ffuse_traffic_model",
     "ffuse_force_plan", "ffuse_last_plan", "ffuse_sync_status", "ffuse_profile_enable", "ffuse_profile_read",
     "ffuse_tune", "ffuse_plan_lookup", "ffuse_plan_table_clear", "ffuse_conv_chain", "ffuse_conv_chain_f16", "ffuse_rank_plans",
+    "ffuse_plan_table_set", "ffuse_plan_table_save", "ffuse_plan_table_load",
     "ffuse_status_string", "ffuse_version",
 ]
 
@@ -96,6 +97,12 @@ def lib():
         L.ffuse_plan_lookup.argtypes = [ci, ci, ci, i64, i64, i64, i64, ctypes.POINTER(Plan), ctypes.POINTER(ctypes.c_double)]
         L.ffuse_plan_table_clear.restype = ci
         L.ffuse_rank_plans.restype = ci
+        L.ffuse_plan_table_set.restype = ci
+        L.ffuse_plan_table_set.argtypes = [ci, ci, i64, i64, i64, i64, ctypes.POINTER(Plan), ctypes.c_double]
+        L.ffuse_plan_table_save.restype = ci
+        L.ffuse_plan_table_save.argtypes = [ctypes.c_char_p]
+        L.ffuse_plan_table_load.restype = ci
+        L.ffuse_plan_table_load.argtypes = [ctypes.c_char_p]
         L.ffuse_rank_plans.argtypes = [ci, ci, ci, i64, i64, i64, i64, ctypes.POINTER(Plan), ctypes.POINTER(ctypes.c_double), ci]
         for name in ("ffuse_conv_chain", "ffuse_conv_chain_f16"):
             f = getattr(L, name)
@@ -240,6 +247,25 @@ def ffuse_rank_plans(dtype, act, gated, M, K, N1, N2, capacity=256):
         ctypes.memmove(ctypes.byref(p), ctypes.byref(plans[i]), ctypes.sizeof(Plan))
         out.append((p, t[i]))
     return out
+
+
+def ffuse_plan_table_set(dtype, gated, M, K, N1, N2, plan: Plan, ms=1.0):
+    _check(lib().ffuse_plan_table_set(int(dtype), int(bool(gated)), M, K, N1, N2, ctypes.byref(plan), float(ms)),
+           "ffuse_plan_table_set")
+
+
+def ffuse_plan_table_save(path) -> int:
+    n = lib().ffuse_plan_table_save(os.fsencode(path))
+    if n < 0:
+        raise FfuseError(n, "ffuse_plan_table_save")
+    return n
+
+
+def ffuse_plan_table_load(path) -> int:
+    n = lib().ffuse_plan_table_load(os.fsencode(path))
+    if n < 0:
+        raise FfuseError(n, "ffuse_plan_table_load")
+    return n
 
 
 def ffuse_plan_table_clear():

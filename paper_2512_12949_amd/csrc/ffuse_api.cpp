@@ -125,7 +125,7 @@ std::array<int64_t, 6> table_key(int dtype, int gated, int64_t K, int64_t N1, in
 ffuse_plan_t lookup_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
     auto it = g.table.find(table_key(dtype, gated, K, N1, N2, ffuse::m_bin(M)));
     if (it != g.table.end() && ffuse::plan_valid(it->second.plan, dtype, gated, M, K, N1, N2) &&
-        ffuse::plan_workspace_bytes(it->second.plan, dtype, gated, M, K, N1, N2) <= g.ws_bytes)
+        (!g.ws || ffuse::plan_workspace_bytes(it->second.plan, dtype, gated, M, K, N1, N2) <= g.ws_bytes))   // (no workspace yet: nothing to fit)
         return it->second.plan;
     const auto key = table_key(dtype, gated, K, N1, N2, -M);
     it = g.table.find(key);
@@ -554,6 +554,64 @@ int ffuse_rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_
         if (t_pred_s) t_pred_s[n] = r.t_pred;
         ++n;
     }
+    return n;
+}
+
+int ffuse_plan_table_set(int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, const ffuse_plan_t* plan, double ms) {
+    if (!plan) return FFUSE_ERR_NULL;
+    if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F32) return FFUSE_ERR_ACT;
+    if (M < 1 || K < 8 || N1 < 8 || N2 < 8) return FFUSE_ERR_SHAPE;
+    if (!ffuse::plan_valid(*plan, dtype, gated ? 1 : 0, M, K, N1, N2)) return FFUSE_ERR_PLAN;
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.table[table_key(dtype, gated ? 1 : 0, K, N1, N2, ffuse::m_bin(M))] = {*plan, ms > 0.0 ? ms : 1e-9};
+    return FFUSE_OK;
+}
+
+// Text format, one tuned entry per line:
+//   ffuse-plan 1 <dtype> <gated> <K> <N1> <N2> <bin> <ms> <family> <bm> <bh> <bn2> <bk> <splits> <h_level> <raster> <producers> <ring> <coherent>
+int ffuse_plan_table_save(const char* path) {
+    if (!path) return FFUSE_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g.mu);
+    std::FILE* f = std::fopen(path, "w");
+    if (!f) return FFUSE_ERR_LAUNCH;
+    int n = 0;
+    for (const auto& kv : g.table) {
+        if (kv.first[5] < 0) continue;   // modelled entries are recomputed, not stored
+        const ffuse_plan_t& p = kv.second.plan;
+        std::fprintf(f, "ffuse-plan 1 %lld %lld %lld %lld %lld %lld %.9g %d %d %d %d %d %d %d %d %d %d %d\n", (long long)kv.first[0],
+                     (long long)kv.first[1], (long long)kv.first[2], (long long)kv.first[3], (long long)kv.first[4],
+                     (long long)kv.first[5], kv.second.ms, p.family, p.bm, p.bh, p.bn2, p.bk, p.splits, p.h_level, p.raster,
+                     p.producers, p.ring, p.coherent);
+        ++n;
+    }
+    std::fclose(f);
+    return n;
+}
+
+int ffuse_plan_table_load(const char* path) {
+    if (!path) return FFUSE_ERR_NULL;
+    std::FILE* f = std::fopen(path, "r");
+    if (!f) return FFUSE_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g.mu);
+    int n = 0;
+    char line[512];
+    while (std::fgets(line, sizeof(line), f)) {
+        long long k[6];
+        double ms;
+        int v[11], ver;
+        if (std::sscanf(line, "ffuse-plan %d %lld %lld %lld %lld %lld %lld %lf %d %d %d %d %d %d %d %d %d %d %d", &ver, &k[0], &k[1], &k[2],
+                        &k[3], &k[4], &k[5], &ms, &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7], &v[8], &v[9], &v[10]) != 19)
+            continue;
+        if (ver != 1 || k[0] < FFUSE_DT_BF16 || k[0] > FFUSE_DT_F32 || k[5] < 0 || k[5] > 62) continue;
+        ffuse_plan_t p{};
+        p.family = v[0]; p.bm = v[1]; p.bh = v[2]; p.bn2 = v[3]; p.bk = v[4]; p.splits = v[5]; p.h_level = v[6]; p.raster = v[7];
+        p.producers = v[8]; p.ring = v[9]; p.coherent = v[10];
+        if (p.family <= FFUSE_FAMILY_AUTO || p.family > FFUSE_FAMILY_TWOPHASE) continue;
+        // validity for a concrete M is checked again at lookup time
+        g.table[table_key((int)k[0], (int)k[1], k[2], k[3], k[4], k[5])] = {p, ms > 0.0 ? ms : 1e-9};
+        ++n;
+    }
+    std::fclose(f);
     return n;
 }
 

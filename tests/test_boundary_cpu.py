@@ -82,3 +82,36 @@ def test_tune_validates_before_touching_the_device():
     assert rc == -1
     rc = L.ffuse_tune(7, None, None, None, None, 2, 128, 64, 64, 64, None, 4, 3, None, ctypes.byref(p), ctypes.byref(ms))
     assert rc == -4
+
+
+def test_plan_table_set_save_load_round_trip(tmp_path):
+    ff.ffuse_plan_table_clear()
+    plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=128, bh=64, bk=32, bn2=256, splits=4, h_level=2, raster=2)
+    ff.ffuse_plan_table_set(ff.DT_BF16, False, 200, 4096, 16384, 4096, plan, ms=0.125)
+    gated = ff.make_plan(ff.FAMILY_REDUCE, 128, 64, bn2=128, raster=1, splits=86)
+    ff.ffuse_plan_table_set(ff.DT_F16, True, 16, 2048, 5632, 2048, gated, ms=0.05)
+    got, ms = ff.ffuse_plan_lookup(ff.DT_BF16, 2, False, 256, 4096, 16384, 4096)      # same bin as M = 200
+    assert got.as_dict() == plan.as_dict() and ms == 0.125
+    other, ms0 = ff.ffuse_plan_lookup(ff.DT_BF16, 2, False, 64, 4096, 16384, 4096)    # another bin: the model
+    assert ms0 == 0.0
+    path = tmp_path / "plans.txt"
+    assert ff.ffuse_plan_table_save(path) == 2                                         # modelled entries are not stored
+    text = path.read_text().splitlines()
+    assert len(text) == 2 and all(line.startswith("ffuse-plan 1 ") for line in text)
+    ff.ffuse_plan_table_clear()
+    assert ff.ffuse_plan_lookup(ff.DT_BF16, 2, False, 256, 4096, 16384, 4096)[1] == 0.0
+    path.write_text(path.read_text() + "garbage line\nffuse-plan 9 0 0 1 1 1 1 1 1 1 1 1 1 1 1 1 1 1 1\n")
+    assert ff.ffuse_plan_table_load(path) == 2                                         # bad lines are skipped
+    got, ms = ff.ffuse_plan_lookup(ff.DT_BF16, 2, False, 130, 4096, 16384, 4096)
+    assert got.as_dict() == plan.as_dict() and ms == 0.125
+    got, ms = ff.ffuse_plan_lookup(ff.DT_F16, 3, True, 9, 2048, 5632, 2048)
+    assert got.as_dict() == gated.as_dict() and ms == 0.05
+    # an entry that is not valid for a concrete M of its bin is passed over at lookup time
+    small = ff.make_plan(ff.FAMILY_TWOPHASE, bm=32, bh=128, bn2=256, splits=8, h_level=2, raster=1)
+    ff.ffuse_plan_table_set(ff.DT_BF16, False, 20, 4096, 16384, 4096, small, ms=0.07)   # bin 17..32
+    assert ff.ffuse_plan_lookup(ff.DT_BF16, 2, False, 32, 4096, 16384, 4096)[0].as_dict() == small.as_dict()
+    bad = ff.Plan()
+    assert ff.lib().ffuse_plan_table_set(ff.DT_BF16, 0, 100, 4096, 16384, 4096, __import__("ctypes").byref(bad), 1.0) == -8
+    with pytest.raises(ff.FfuseError):
+        ff.ffuse_plan_table_load(tmp_path / "missing.txt")
+    ff.ffuse_plan_table_clear()
