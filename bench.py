@@ -102,10 +102,12 @@ def main():
         kms, kn = ff.ffuse_profile_read()
         return dt_s / steps, (kms / kn * 1e-3 if kn else float("nan"))
 
+    print(f"[bench] {w.name}: timing the fused call", file=sys.stderr, flush=True)
     t_fused, k_fused = timed(fused, args.steps, args.warmup)
     plan = ff.ffuse_last_plan()
     model = ff.ffuse_traffic_model(plan, dt, w.gated, w.M, w.K, w.N1, w.N2).as_dict()
     Y_fused = Y.clone()
+    print(f"[bench] {w.name}: timing the unfused call", file=sys.stderr, flush=True)
     t_unf, k_unf = timed(unfused, max(3, args.steps // 2), 2)
     diff = float((Y_fused.float() - Y.float()).abs().max() / Y.float().abs().max())
 
@@ -171,11 +173,23 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         per_row = flops / w.M
-        nrows = args.oracle_rows or int(max(1, min(w.M, 1.2e12 / per_row)))  # ~10-25 s of oracle work
+        bf = w.dtype == "bf16"
+
+        def oracle_rows(rows):
+            t0 = time.perf_counter()
+            r = oracle.ffn_rows(host["X"], host["W1"], host["W3"], host["W2"], w.act, rows=rows, bf16=bf)
+            return r, time.perf_counter() - t0
+
+        # the oracle's speed depends on the operand type (its exact fp16 widening is slow): a
+        # probe of a few rows sizes the sample to ~15 s of oracle work
+        nrows = args.oracle_rows
+        if not nrows:
+            probe = list(range(min(w.M, 16)))
+            _, t_probe = oracle_rows(probe)
+            nrows = int(max(1, min(w.M, 15.0 * len(probe) / max(t_probe, 1e-3))))
         rows = inputs.sample_rows(w.M, max(1, w.M // max(1, nrows // 2)), 2, seed=7)[:nrows]
-        t0 = time.perf_counter()
-        ref = oracle.ffn_rows(host["X"], host["W1"], host["W3"], host["W2"], w.act, rows=rows, bf16=(w.dtype == "bf16"))
-        t_cpu = time.perf_counter() - t0
+        print(f"[bench] cpu baseline: oracle on {len(rows)} rows", file=sys.stderr, flush=True)
+        ref, t_cpu = oracle_rows(rows)
         got = Y_fused[torch.as_tensor(rows, device="cuda")].float().cpu().numpy().astype(np.float64)
         rel = float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-300))
         out["cpu_baseline"] = {"value": per_row * len(rows) / t_cpu * 1e-12, "unit": "TFLOP/s",

@@ -79,7 +79,7 @@ typedef enum {
     FFUSE_FAMILY_EXCHANGE = 2,/* cooperating workgroups publish activated tiles to an
                                  L2-resident buffer and consume each other's tiles
                                  (Sec. 4.1 "shuffle" strategy, exchange through L2)         */
-    FFUSE_FAMILY_UNFUSED = 3, /* two GEMM launches, intermediate in the workspace          */
+    FFUSE_FAMILY_UNFUSED = 3, /* traffic model only: two GEMM launches of 256-row tiles       */
     FFUSE_FAMILY_SCALAR = 4,  /* fp32 debug kernels (plain FMA, no matrix cores)            */
     FFUSE_FAMILY_TWOPHASE = 5 /* any M: one persistent kernel; every CU computes tiles of the
                                  intermediate into an L2 / Infinity-Cache resident buffer, one
@@ -140,7 +140,12 @@ int ffuse_ffn_f32(const void* X, const void* W1, const void* W3, const void* W2,
 
 /* ---- the unfused comparison path (Evaluation, "Performance Analysis": the baseline writes
  *      the intermediate to global memory and reads it back): GEMM + activation/gate into a
- *      workspace-resident H[M][N1] in the operand type, then H * W2. --------------------- */
+ *      workspace-resident H[M][N1] in the operand type, then H * W2, as two kernel launches
+ *      (plus the plane sum when the second GEMM splits the hidden dimension).  The 16-bit
+ *      types run the two-phase family's kernel one phase per launch in the tile plan the
+ *      model ranks best for the shape: same block GEMMs and tiles as the fused call, so a
+ *      timing difference is the fusion's.  Forced plans do not apply; ffuse_last_plan is
+ *      left unchanged. ---------------------------------------------------------------- */
 int ffuse_ffn_unfused(const void* X, const void* W1, const void* W3, const void* W2, int act,
                       int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
 int ffuse_ffn_unfused_f16(const void* X, const void* W1, const void* W3, const void* W2, int act,
@@ -163,7 +168,8 @@ int ffuse_conv_chain_f16(const void* X, const void* W1, const void* W2, int act,
                          int64_t W, int64_t IC, int64_t OC1, int64_t OC2, int k1, int k2, void* Y, void* stream);
 
 /* ---- workspace.  ffuse_workspace_bytes: bytes the given problem needs (fused path when
- *      unfused == 0).  ffuse_set_workspace: registers a caller-owned device buffer with the
+ *      unfused == 0; with unfused != 0 the two-launch path's intermediate, partial-sum planes
+ *      and flags).  ffuse_set_workspace: registers a caller-owned device buffer with the
  *      library (it is zero-filled once on `stream`); passing NULL unregisters it. --------- */
 size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
                              int unfused);

@@ -34,7 +34,7 @@ struct State {
     uint32_t* exch_err = nullptr;  // device address of the error word of the last exchange launch
     bool log = std::getenv("FFUSE_LOG") != nullptr;  // diagnostics on stderr
     uint64_t* exch_stats = nullptr;
-    uint64_t* gemm_stats = nullptr;
+    bool small_split = false;
     uint64_t* small_stats = nullptr;
     int exch_wgs = 0;
     // plan table (Sec. 4.3: plans are fixed ahead of time per range of the dynamic dimension M
@@ -138,7 +138,7 @@ ffuse_plan_t lookup_plan(int dtype, int act, int gated, int64_t M, int64_t K, in
 }
 
 int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act,
-             int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
+             int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream, bool two_launches = false);
 
 int run_fused(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
               int64_t N1, int64_t N2, void* Y, void* stream) {
@@ -160,9 +160,10 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
     return run_plan(plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
 }
 
-// launches one validated plan; the caller holds the lock
+// launches one validated plan; the caller holds the lock.  two_launches (two-phase family
+// only): each phase is a launch of its own and the kernel boundary replaces the barrier.
 int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act,
-             int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream) {
+             int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream, bool two_launches) {
     const int gated = W3 != nullptr;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     ffuse::FusedArgs a{X, W1, W3, W2, nullptr, M, (int)K, (int)N1, (int)N2, act, plan.raster > 0 ? plan.raster : 1};
@@ -203,20 +204,27 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
         char* base = reinterpret_cast<char*>(g.ws);
         uint32_t* flags = reinterpret_cast<uint32_t*>(base + sg.ysum_bytes + sg.h_bytes);
         if (g.small_flags != flags) {
-            if (ffuse::launch_zero(flags, 256, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+            if (ffuse::launch_zero(flags, ffuse::kTwoPhaseFlagBytes, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
             g.small_flags = flags;
         }
         g.ws_zero = 0;      // planes and H overwrite the region the reduce family keeps at zero
         ffuse::TwoPhaseArgs s{X, W1, W3, W2, base + sg.ysum_bytes, Y, reinterpret_cast<float*>(base), flags,
                               M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, sg.raster, nullptr,
-                              g.conv_ic, g.conv_h, g.conv_w};
-        if (g.log && g.ws_bytes >= sg.ws_bytes + 32768) {
+                              g.conv_ic, g.conv_h, g.conv_w, 3};
+        if (g.log && g.ws_bytes >= sg.ws_bytes + 65536) {
             s.stats = reinterpret_cast<uint64_t*>(base + sg.ws_bytes);
             g.small_stats = s.stats;
+            g.small_split = two_launches;
         }
         g.exch_err = flags + 2;
         {
             Timer t(st);
+            if (two_launches) {
+                s.phases = 1;
+                if (ffuse::launch_fused_two_phase(dtype, s, sg.bm, sg.bh1, sg.bk, g.cus, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+                s.phases = 2;
+                if (s.stats) s.stats += 4 * 1024;
+            }
             if (ffuse::launch_fused_two_phase(dtype, s, sg.bm, sg.bh1, sg.bk, g.cus, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
             t.stop();
         }
@@ -240,6 +248,10 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
     return FFUSE_OK;
 }
 
+// The comparison path: the same two GEMMs with the intermediate written and re-read between
+// two launches.  16-bit types run the two-phase family's kernel one phase per launch, in
+// the tile plan the model ranks best for this shape, so that the only differences from the
+// fused call are the second launch and the kernel boundary in place of the barrier.
 int run_unfused(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M,
                 int64_t K, int64_t N1, int64_t N2, void* Y, void* stream) {
     const int elem = dtype == FFUSE_DT_F32 ? 4 : 2;
@@ -249,25 +261,37 @@ int run_unfused(int dtype, const void* X, const void* W1, const void* W3, const 
     std::lock_guard<std::mutex> lock(g.mu);
     rc = check_arch();
     if (rc != FFUSE_OK) return rc;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (dtype != FFUSE_DT_F32) {
+        const int gated = W3 != nullptr;
+        const auto key = table_key(dtype + 16, gated, K, N1, N2, -M);   // its own slot beside the fused plans
+        auto it = g.table.find(key);
+        if (it == g.table.end()) {
+            std::vector<ffuse::RankedPlan> ranked;
+            ffuse::rank_plans(dtype, act, gated, M, K, N1, N2, &ranked);
+            ffuse_plan_t best{};
+            for (const auto& r : ranked)
+                if (r.plan.family == FFUSE_FAMILY_TWOPHASE) { best = r.plan; break; }
+            if (best.family != FFUSE_FAMILY_TWOPHASE) return FFUSE_ERR_PLAN;
+            if (g.table.size() > 4096) g.table.clear();
+            g.table[key] = {best, 0.0};
+            it = g.table.find(key);
+        }
+        const ffuse_plan_t keep = g.last_plan;
+        rc = run_plan(it->second.plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, stream, true);
+        g.last_plan = keep;   // ffuse_last_plan reports fused calls only
+        return rc;
+    }
     const size_t need = (size_t)elem * (size_t)M * (size_t)N1;
     if (!g.ws || g.ws_bytes < need) return FFUSE_ERR_WORKSPACE;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     g.ws_zero = 0;      // H overwrites whatever the fused path kept at zero
     g.small_flags = nullptr;
     g.exch_err = nullptr;
-    ffuse::GemmArgs g0{X, W1, W3, g.ws, M, (int)K, (int)N1, act, 4, nullptr};
-    ffuse::GemmArgs g1{g.ws, W2, nullptr, Y, M, (int)N1, (int)N2, FFUSE_ACT_IDENTITY, 4, nullptr};
-    if (g.log && dtype != FFUSE_DT_F32 && g.ws_bytes >= need + (1u << 20)) {
-        // diagnostics: per-workgroup phase times of both GEMMs behind the intermediate
-        g0.stats = reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(g.ws) + ((need + 255) & ~(size_t)255));
-        g1.stats = g0.stats + 4 * 16384;
-        g.gemm_stats = g0.stats;
-    }
+    ffuse::GemmArgs g0{X, W1, W3, g.ws, M, (int)K, (int)N1, act};
+    ffuse::GemmArgs g1{g.ws, W2, nullptr, Y, M, (int)N1, (int)N2, FFUSE_ACT_IDENTITY};
     Timer t(st);
-    hipError_t e = dtype == FFUSE_DT_F32 ? ffuse::launch_gemm_act_f32(g0, st) : ffuse::launch_gemm_act(dtype, g0, st);
-    if (e != hipSuccess) return FFUSE_ERR_LAUNCH;
-    e = dtype == FFUSE_DT_F32 ? ffuse::launch_gemm_act_f32(g1, st) : ffuse::launch_gemm_act(dtype, g1, st);
-    if (e != hipSuccess) return FFUSE_ERR_LAUNCH;
+    if (ffuse::launch_gemm_act_f32(g0, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+    if (ffuse::launch_gemm_act_f32(g1, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
     t.stop();
     return FFUSE_OK;
 }
@@ -306,14 +330,14 @@ size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t
     if (M < 1 || N1 < 1 || N2 < 1) return 0;
     const size_t elem = dtype == FFUSE_DT_F32 ? 4 : 2;
     size_t b = unfused ? elem * (size_t)M * (size_t)N1 : (dtype == FFUSE_DT_F32 ? 0 : sizeof(float) * (size_t)M * (size_t)N2);
-    if (!unfused && dtype != FFUSE_DT_F32) {
+    if (dtype != FFUSE_DT_F32) {   // (the 16-bit unfused path runs the two-phase family's kernel)
         // room for the exchange family's flags + ring at its largest ring setting
         const size_t ex = ffuse::kExchangeFlagBytes + (size_t)8 * ffuse::kExchangeMaxRing * 256 * (gated ? 128 : 256) * 2;
-        if (ex > b) b = ex;
+        if (!unfused && ex > b) b = ex;
         // two-phase family: partial-sum planes (at the most splits the chooser uses for this M) | H | flags
         const int sp = ffuse::two_phase_max_splits(M, N2);
         const size_t planes = sp > 1 ? (((size_t)4 * M * N2 * sp + 255) & ~(size_t)255) : 0;
-        const size_t tp = planes + (((size_t)2 * M * N1 + 255) & ~(size_t)255) + 256;
+        const size_t tp = planes + (((size_t)2 * M * N1 + 255) & ~(size_t)255) + ffuse::kTwoPhaseFlagBytes;
         if (tp > b) b = tp;
     }
     return (b + 255) & ~(size_t)255;
@@ -370,32 +394,20 @@ int ffuse_sync_status(void* stream) {
     if (hipStreamSynchronize(reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return FFUSE_ERR_LAUNCH;
     std::lock_guard<std::mutex> lock(g.mu);
     if (g.log && g.small_stats) {
-        std::vector<uint64_t> h(4 * 1024);
+        std::vector<uint64_t> h(8 * 1024);
         if (hipMemcpy(h.data(), g.small_stats, h.size() * 8, hipMemcpyDeviceToHost) == hipSuccess) {
-            double p1 = 0, b = 0, p2 = 0, m1 = 0, m2 = 0; int n = 0;
+            // launched one phase at a time, the second launch's record follows the first's
+            const uint64_t* h2 = h.data() + (g.small_split ? 4 * 1024 : 0);
+            double p1 = 0, b = 0, p2 = 0, m1 = 0, m2 = 0, clk = 0; int n = 0;
             for (int i = 0; i < g.cus && i < 1024; ++i) {
-                p1 += h[4 * i]; b += h[4 * i + 1]; p2 += h[4 * i + 2]; ++n;
-                m1 = std::max(m1, (double)h[4 * i]); m2 = std::max(m2, (double)h[4 * i + 2]);
+                p1 += h[4 * i]; clk += h[4 * i + 3]; b += h[4 * i + 1]; p2 += h2[4 * i + 2]; ++n;
+                m1 = std::max(m1, (double)h[4 * i]); m2 = std::max(m2, (double)h2[4 * i + 2]);
             }
-            std::fprintf(stderr, "[ffuse] two-phase: phase 1 avg %.1f us (max %.1f), barrier wait avg %.1f us, phase 2 avg %.1f us (max %.1f)\n",
-                         p1 / n * 0.01, m1 * 0.01, b / n * 0.01, p2 / n * 0.01, m2 * 0.01);
+            std::fprintf(stderr, "[ffuse] two-phase%s: phase 1 avg %.1f us (max %.1f) at %.0f MHz, barrier wait avg %.1f us, phase 2 avg %.1f us (max %.1f)\n",
+                         g.small_split ? " (one launch per phase)" : "", p1 / n * 0.01, m1 * 0.01, p1 > 0 ? clk / p1 * 100.0 : 0.0,
+                         b / n * 0.01, p2 / n * 0.01, m2 * 0.01);
         }
         g.small_stats = nullptr;
-    }
-    if (g.log && g.gemm_stats) {
-        std::vector<uint64_t> h(8 * 16384);
-        if (hipMemcpy(h.data(), g.gemm_stats, h.size() * 8, hipMemcpyDeviceToHost) == hipSuccess) {
-            for (int k = 0; k < 2; ++k) {
-                double p = 0, l = 0, e = 0, st = 0, lmax = 0; int n = 0;
-                for (int i = 0; i < 16384; ++i) {
-                    const uint64_t* q = &h[(size_t)k * 4 * 16384 + 4 * i];
-                    if (q[3]) { p += q[0]; l += q[1]; e += q[2]; st += q[3]; ++n; if ((double)q[1] > lmax) lmax = (double)q[1]; }
-                }
-                if (n) std::fprintf(stderr, "[ffuse] gemm %d: %d tiles, loop %.2f us avg, %.2f max (%.3f us/step, %.0f cycles/step at %.0f MHz), epilogue %.2f us\n",
-                                    k, n, l / n * 0.01, lmax * 0.01, l / st * 0.01, p / st, p / l * 100.0, e / n * 0.01);
-            }
-        }
-        g.gemm_stats = nullptr;
     }
     if (!g.exch_err) return FFUSE_OK;
     uint32_t word = 0;

@@ -48,6 +48,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
     return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);
 }
+// 16-byte store written through to memory at device scope (cache policy sc1): complete, as
+// counted by vmcnt, means visible to every XCD
+__device__ __forceinline__ void buf_store16_through(u32x4 v, __amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, 16);
+}
 
 // ---------------------------------------------------------------------------------------
 // 8x8 transpose of 16-bit elements held in registers.  in[r] = row r (8 elements, element c

@@ -451,6 +451,9 @@ struct FirstGemm {
     // to them.  8-byte slots of a row are XOR-swizzled with the row so that both the 8-byte
     // writes (32 rows per instruction) and the 16-byte reads are free of bank conflicts.
     // Requires ldc, col0 and col_lim to be multiples of 8 (16-byte aligned chunks).
+    // THROUGH: the global stores are written through the L2 (device scope) as they are issued,
+    // so that workgroups on other XCDs can read the tile after a flag without anybody having
+    // to write back a whole L2 first; C must then be smaller than 2 GiB.
     static constexpr int EPI_RB = WHR * 2;                    // bytes per staged row
     static constexpr int EPI_SLOTS = EPI_RB / 8;
     static constexpr int EPI_SHIFT = EPI_RB >= 256 ? 0 : (EPI_RB == 128 ? 1 : 2);
@@ -460,7 +463,7 @@ struct FirstGemm {
     static __device__ __forceinline__ uint32_t epi_key(uint32_t row) {
         return (row >> EPI_SHIFT) & (uint32_t)((EPI_SLOTS < 32 ? EPI_SLOTS : 32) - 1);
     }
-    template <int ACT>
+    template <int ACT, bool THROUGH = false>
     static __device__ __forceinline__ void store_tile_lds(char* smem, const f32x16 (&acc)[HT][MT],
                                                           const f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
                                                           char* C, int64_t ldc, int64_t row0, int col0,
@@ -500,6 +503,8 @@ struct FirstGemm {
         // in batches of 8 rows-per-lane, fenced: left alone the compiler hoists all the LDS
         // reads above the stores and runs out of registers
         constexpr int NOUT = WMR / EPI_RPI, BATCH = NOUT < 8 ? NOUT : 8;
+        __amdgpu_buffer_rsrc_t rc;
+        if constexpr (THROUGH) rc = make_rsrc(C, (uint32_t)(row_lim * ldc * 2));
 #pragma unroll
         for (int i0 = 0; i0 < NOUT; i0 += BATCH) {
             u32x4 v[BATCH];
@@ -513,20 +518,27 @@ struct FirstGemm {
 #pragma unroll
             for (int i = 0; i < BATCH; ++i) {
                 const int64_t grow = row0 + wm * WMR + (i0 + i) * EPI_RPI + rin;
-                if (grow < row_lim && col < col_lim) *reinterpret_cast<u32x4*>(C + (grow * ldc + col) * 2) = v[i];
+                if constexpr (THROUGH) {
+                    // out-of-range chunks get an offset beyond the buffer: the hardware drops the store
+                    const uint32_t off = (grow < row_lim && col < col_lim) ? (uint32_t)((grow * ldc + col) * 2) : kOob;
+                    buf_store16_through(v[i], rc, off);
+                } else {
+                    if (grow < row_lim && col < col_lim) *reinterpret_cast<u32x4*>(C + (grow * ldc + col) * 2) = v[i];
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+    template <bool THROUGH = false>
     static __device__ __forceinline__ void store_tile_lds_rt(char* smem, int act, const f32x16 (&acc)[HT][MT],
                                                              const f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
                                                              char* C, int64_t ldc, int64_t row0, int col0,
                                                              int64_t row_lim, int col_lim, int tid) {
         switch (act) {
-            case ACT_RELU: store_tile_lds<ACT_RELU>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
-            case ACT_GELU_TANH: store_tile_lds<ACT_GELU_TANH>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
-            case ACT_SILU: store_tile_lds<ACT_SILU>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
-            default: store_tile_lds<ACT_IDENTITY>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
+            case ACT_RELU: store_tile_lds<ACT_RELU, THROUGH>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
+            case ACT_GELU_TANH: store_tile_lds<ACT_GELU_TANH, THROUGH>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
+            case ACT_SILU: store_tile_lds<ACT_SILU, THROUGH>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
+            default: store_tile_lds<ACT_IDENTITY, THROUGH>(smem, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, tid); break;
         }
     }
 };

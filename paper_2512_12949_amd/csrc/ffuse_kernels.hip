@@ -9,8 +9,7 @@
 //     with the XCD as the cluster and its L2 as the shared on-chip pool).
 //   (the two-phase family, the default, lives in ffuse_two_phase.hip)
 //   * finalize_kernel       -- fp32 sums -> Y in the operand type, workspace back to zero.
-//   * gemm_act_kernel       -- plain GEMM with the activation/gate epilogue: the two launches
-//     of the unfused comparison path.
+//   (the 16-bit unfused comparison path is the two-phase kernel launched one phase at a time)
 #include "ffuse_gemm1.h"
 #include "ffuse_launch.h"
 
@@ -210,39 +209,6 @@ template <typename T> __global__ __launch_bounds__(256) void finalize_kernel(flo
     const f32x4 z = {0.f, 0.f, 0.f, 0.f};
     p[0] = z;
     p[1] = z;
-}
-
-// ---------------------------------------------------------------------------------------
-// C[M][N] = act(A * B) [.* (A * B3)], operands and C in type T, fp32 accumulation.
-// 256 x BH tile per workgroup (BH = 256, or 128 when gated), waves 2 x 2.
-// ---------------------------------------------------------------------------------------
-template <typename T, bool GATED, int BM, int BH>
-__global__ __launch_bounds__(256) void gemm_act_kernel(GemmArgs a) {
-    typedef DeepGemm<T, GATED, BM, BH, 2, 2> G0;
-    constexpr int MT = G0::MT, HT = G0::HT;
-    __shared__ __attribute__((aligned(16))) char smem[G0::LDS_BYTES];
-    const int tid = threadIdx.x;
-    const int MB = (int)((a.M + BM - 1) / BM), S = (a.N + BH - 1) / BH;
-    int ui, us;
-    if (!map_unit(MB, S, a.raster, ui, us)) return;
-    const int m0 = ui * BM, n0 = us * BH;
-    f32x16 acc[HT][MT];
-    f32x16 acc3[GATED ? HT : 1][GATED ? MT : 1];
-    typename G0::Ctx c;
-    G0::init_a(c, a.A, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)m0, (uint32_t)a.K, a.K, tid);
-    G0::init_b(c, a.B, a.B3, (uint32_t)((uint64_t)a.K * a.N * 2), (uint32_t)a.N, (uint32_t)a.N, (uint32_t)n0, tid);
-    G0::init_lds(c, tid);
-    uint64_t t0 = 0, t1 = 0, t2 = 0, c0 = 0, c1 = 0;
-    if (a.stats) { t0 = wall_clock64(); c0 = clock64(); }
-    G0::run(smem, c, 0, a.K, acc, acc3, tid, a.stats ? &t1 : nullptr);
-    if (a.stats) { t2 = wall_clock64(); c1 = clock64(); }
-    G0::store_tile_lds_rt(smem, a.act, acc, acc3, reinterpret_cast<char*>(a.C), a.N, m0, n0, a.M, a.N, tid);
-    if (a.stats && tid == 0) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        uint64_t* p = a.stats + 4 * blockIdx.x;
-        // p[0]: core-clock cycles from kernel start to loop end (with p[1]: the sustained clock)
-        p[0] = c1 - c0; p[1] = t2 - t0; p[2] = wall_clock64() - t2; p[3] = (uint64_t)((a.K + 63) / 64);
-    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -507,19 +473,6 @@ hipError_t launch_finalize(int dtype, float* sums, void* Y, int64_t count, hipSt
     else
         hipLaunchKernelGGL(finalize_kernel<_Float16>, dim3(blocks), dim3(256), 0, st, sums, Y, n8);
     return hipGetLastError();
-}
-
-template <typename T> static hipError_t launch_gemm_dt(const GemmArgs& a, hipStream_t st) {
-    if (a.B3) {
-        hipLaunchKernelGGL((gemm_act_kernel<T, true, 256, 128>), dim3(grid_for(a.M, a.N, 256, 128)), dim3(256), 0, st, a);
-    } else {
-        hipLaunchKernelGGL((gemm_act_kernel<T, false, 256, 256>), dim3(grid_for(a.M, a.N, 256, 256)), dim3(256), 0, st, a);
-    }
-    return hipGetLastError();
-}
-
-hipError_t launch_gemm_act(int dtype, const GemmArgs& a, hipStream_t st) {
-    return dtype == 0 ? launch_gemm_dt<__bf16>(a, st) : launch_gemm_dt<_Float16>(a, st);
 }
 
 hipError_t launch_fused_exchange(int dtype, const ExchangeArgs& a, int wgs_per_group, hipStream_t st) {

@@ -26,8 +26,6 @@ struct GemmArgs {
     int64_t M;
     int K, N;
     int act;
-    int raster;
-    uint64_t* stats;  // nullptr, or 4 words per workgroup: ticks of prologue, main loop, epilogue; step count
 };
 
 struct ExchangeArgs {
@@ -50,6 +48,10 @@ struct ExchangeArgs {
     uint64_t* stats;  // nullptr, or 4 words per workgroup: role, total ticks, waiting ticks, items
 };
 
+// two-phase family's flag words (kTwoPhaseFlagBytes in all): 0 = groups arrived at the barrier, 1 = workgroups that have
+// left, 2 = error; kTwoPhaseGroupWord * (1 + g) = arrivals of group g (a cache line apart)
+static constexpr int kTwoPhaseGroupWord = 16;
+
 struct TwoPhaseArgs {
     const void* X;
     const void* W1;
@@ -69,6 +71,8 @@ struct TwoPhaseArgs {
     // 3x3 first product (conv_ic > 0): X is a channels-last image of M pixels (conv_h x conv_w
     // per image) with conv_ic channels, W1 is [3][3][conv_ic][N1], K = 9 * conv_ic
     int conv_ic, conv_h, conv_w;
+    int phases;       // 3: both phases with the device-wide barrier between them (the fused chain);
+                      // 1 / 2: only the first / second phase (two launches = the unfused comparison path)
 };
 
 // 16-bit paths (dtype 0 = bf16, 1 = fp16)
@@ -77,7 +81,6 @@ hipError_t launch_finalize_planes(int dtype, const float* part, void* Y, int64_t
 hipError_t launch_fused_exchange(int dtype, const ExchangeArgs& a, int wgs_per_group, hipStream_t st);
 hipError_t launch_fused_reduce(int dtype, const FusedArgs& a, int bm, int bh, hipStream_t st);
 hipError_t launch_finalize(int dtype, float* sums, void* Y, int64_t count, hipStream_t st);
-hipError_t launch_gemm_act(int dtype, const GemmArgs& a, hipStream_t st);
 
 // Launch of a persistent kernel whose workgroups wait for each other: every workgroup must
 // be resident at once.  The grid is checked against the occupancy the runtime reports

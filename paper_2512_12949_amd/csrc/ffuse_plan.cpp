@@ -114,13 +114,39 @@ bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1,
     g->splits = (int)((N1 + g->ksplit - 1) / g->ksplit);
     g->ysum_bytes = g->splits > 1 ? (((size_t)4 * M * N2 * g->splits + 255) & ~(size_t)255) : 0;
     g->h_bytes = ((size_t)2 * M * N1 + 255) & ~(size_t)255;
-    g->ws_bytes = g->ysum_bytes + g->h_bytes + 256;
+    g->ws_bytes = g->ysum_bytes + g->h_bytes + kTwoPhaseFlagBytes;
     return true;
 }
 
 bool fused_reduce_tile_ok(int gated, int bm, int bh) {
     if (!gated) return (bm == 256 && bh == 256) || (bm == 128 && (bh == 256 || bh == 128 || bh == 64));
     return (bm == 256 && bh == 128) || (bm == 128 && (bh == 128 || bh == 64));
+}
+
+// Fraction of the MFMA peak a block GEMM sustains on a compute-bound problem, by tile shape
+// (measured on the two-phase kernel's first phase, 4096 x 4096 x 16384 and 2048 x 4096 x
+// 2 * 11008).  Four waves share a rows x cols tile 2 x 2; per MFMA a wave reads
+// r ~ 1 / wave rows + 1 / wave cols operand fragments from LDS, and the smaller the tile the
+// more of the loop is LDS reads rather than matrix instructions.  The 256 x 256 tile runs at
+// the chip's power limit; smaller tiles run at a higher clock but stay LDS-bound.
+//     wave tile    r     LDS-direct loop   register-staged loop
+//     128 x 128    1     0.48              --
+//      64 x 128    1.5   0.40              0.40
+//      64 x 64     2     0.31              0.275
+//      64 x 32     3     0.20              0.156
+// 1 / efficiency is interpolated linearly in r (and extrapolated beyond 3).
+static double block_gemm_efficiency(double rows, double cols, bool lds_direct) {
+    const double wr = rows >= 128.0 ? rows / 2.0 : rows, wc = rows >= 128.0 ? cols / 2.0 : cols / 4.0;
+    const double r = 64.0 * (1.0 / wr + 1.0 / wc);
+    static const double rs[4] = {1.0, 1.5, 2.0, 3.0};
+    static const double inv_direct[4] = {1.0 / 0.48, 1.0 / 0.40, 1.0 / 0.31, 1.0 / 0.20};
+    static const double inv_staged[4] = {1.0 / 0.48, 1.0 / 0.40, 1.0 / 0.275, 1.0 / 0.156};
+    const double* inv = lds_direct ? inv_direct : inv_staged;
+    if (r <= rs[0]) return 1.0 / inv[0];
+    int i = 0;
+    while (i < 2 && r > rs[i + 1]) ++i;
+    const double v = inv[i] + (inv[i + 1] - inv[i]) * (r - rs[i]) / (rs[i + 1] - rs[i]);
+    return 1.0 / v;
 }
 
 void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
@@ -280,10 +306,11 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         // planes are written and read once; small transfers reach about half the cache rate
         const double planes = sg.splits > 1 ? 2.0 * 4.0 * m * n2 * sg.splits / (0.5 * d.fabric_bw) : 0.0;
         // matrix-core time of each phase: items run one per CU, at the block GEMM's efficiency
-        // (the LDS-direct GEMM at 256 rows, at 64 / 128 rows, and the register-staged one)
-        const double f_cu = d.mfma_flops * (sg.bm == 256 ? 0.48 : (sg.bk == 32 ? 0.45 : 0.33)) / d.cus;
-        const double m1 = 2.0 * sg.bm * bh1 * g * k / f_cu * cdiv(items1, d.cus);
-        const double m2 = 2.0 * sg.bm * 256.0 * sg.ksplit / f_cu * cdiv(items, d.cus);
+        // for the item's tile shape
+        const double f1 = d.mfma_flops * block_gemm_efficiency(sg.bm, g * bh1, sg.bk == 32 || sg.bm == 256) / d.cus;
+        const double f2 = d.mfma_flops * block_gemm_efficiency(sg.bm, 256.0, sg.bk == 32 || sg.bm == 256) / d.cus;
+        const double m1 = 2.0 * sg.bm * bh1 * g * k / f1 * cdiv(items1, d.cus);
+        const double m2 = 2.0 * sg.bm * 256.0 * sg.ksplit / f2 * cdiv(items, d.cus);
         t->workgroups = d.cus;
         t->fabric_bytes = b1 + b2 + re1 + re2;
         t->t_hbm = t1 + t2;

@@ -26,6 +26,7 @@ extern const Device kDevice;
 
 // Exchange family: derived launch geometry of a plan for one problem.
 constexpr size_t kExchangeFlagBytes = 8192;
+constexpr size_t kTwoPhaseFlagBytes = 1024;   // barrier counters of the two-phase family, behind its H
 constexpr int kExchangeMaxRing = 64;
 struct ExchangeGeometry {
     int wgs_per_group;  // workgroups per XCD group = CUs / 8
@@ -41,7 +42,7 @@ struct TwoPhaseGeometry {
     int bh1;            // hidden slice of a phase-1 item: 128 / 64 / 32 (bm <= 128), 256 or 128 gated (bm = 256)
     int splits, ksplit; // phase-2 ranges of the hidden dimension (splits == 1: no partial planes)
     int raster;         // row blocks per XCD patch
-    size_t ysum_bytes, h_bytes, ws_bytes;   // workspace layout: partial-sum planes | H | 256 bytes of flags
+    size_t ysum_bytes, h_bytes, ws_bytes;   // workspace layout: partial-sum planes | H | flags (kTwoPhaseFlagBytes)
 };
 // most hidden-dimension ranges the chooser considers for an M x N2 output (bounds the workspace)
 int two_phase_max_splits(int64_t M, int64_t N2);

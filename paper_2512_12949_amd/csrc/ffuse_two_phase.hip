@@ -113,11 +113,12 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
     const int G = gridDim.x, GX = G >> 3;             // workgroups, workgroups per XCD
     const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
     const int MB = (int)((a.M + BM - 1) / BM);
-    uint64_t t0 = 0, t1 = 0, t2 = 0;
-    if (a.stats) t0 = wall_clock64();
+    uint64_t t0 = 0, t1 = 0, t2 = 0, c0 = 0, c1 = 0;
+    if (a.stats) { t0 = wall_clock64(); c0 = clock64(); }
+    const bool both = a.phases == 3;
 
     // ---------------------------------------------------------------- phase 1
-    {
+    if (a.phases & 1) {
         f32x16 acc[G1::HT][G1::MT];
         f32x16 acc3[GATED ? G1::HT : 1][GATED ? G1::MT : 1];
         typename G1::Ctx c;
@@ -132,21 +133,30 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
             G1::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1, (uint32_t)s * BH1, tid);
             if constexpr (TG::DEEP) G1::run(smem, c, 0, a.K, acc, acc3, tid);
             else G1::run_deep(smem, c, 0, a.K, acc, acc3, tid);
-            G1::store_tile_lds_rt(smem, a.act, acc, acc3, reinterpret_cast<char*>(a.H), a.N1, (int64_t)rb * BM, s * BH1, a.M, a.N1, tid);
+            G1::template store_tile_lds_rt<true>(smem, a.act, acc, acc3, reinterpret_cast<char*>(a.H), a.N1, (int64_t)rb * BM, s * BH1, a.M, a.N1, tid);
             __syncthreads();   // LDS is free again before the next item's loads
         }
     }
 
-    if (a.stats) t1 = wall_clock64();
+    if (a.stats) { t1 = wall_clock64(); c1 = clock64(); }
     // ---------------------------------------------------------------- device-wide barrier
+    // (only when both phases run in this launch: launched one phase at a time, the kernel
+    // boundary is the barrier -- the unfused comparison path)
+    // The tiles of H were stored write-through, so once this workgroup's stores have completed
+    // they are visible device-wide and arriving takes no L2 write-back (which costs 5+ us when
+    // the L2 holds a few MB of dirty lines).  Arrivals are counted per group of G/8
+    // workgroups first -- 256 atomics on one word take twice as long as 32 on each of 8 -- and
+    // the last of a group arrives for it.
     // bounded: on expiry the error word is set and every workgroup leaves
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (tid == 0) {
+    if (tid == 0 && !both) verdict = 1u;
+    if (tid == 0 && both) {
         uint32_t ok = 1;
-        __hip_atomic_fetch_add(a.flags, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t prev = __hip_atomic_fetch_add(a.flags + kTwoPhaseGroupWord * (1 + xcd), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (prev == (uint32_t)GX - 1u) __hip_atomic_fetch_add(a.flags, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         uint32_t spins = 0;
-        while (__hip_atomic_load(a.flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)G) {
+        while (__hip_atomic_load(a.flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < 8u) {
             __builtin_amdgcn_s_sleep(2);
             if ((++spins & 1023u) == 0 &&
                 (spins > kBarrierSpinLimit || __hip_atomic_load(a.flags + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
@@ -164,7 +174,7 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
     if (a.stats) t2 = wall_clock64();
 
     // ---------------------------------------------------------------- phase 2
-    if (ok) {
+    if (ok && (a.phases & 2)) {
         f32x16 acc[G2::HT][G2::MT];
         f32x16 acc3[1][1];
         typename G2::Ctx c;
@@ -191,6 +201,7 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
             // acc[ht][mt][4q..4q+3]: row wm*WMR + 32*mt + x, columns wn*WHR + 32*ht + 8*q + 4*h + 0..3 of the tile
             // -> one 16-byte store into this range's own partial-sum plane (no atomics: the
             //    planes are summed in a fixed order by the finalize pass)
+            // (ordinary write-back stores: writing the planes or Y through as well measured 3-7 % slower)
             float* plane = a.part + (size_t)sp * (size_t)a.M * a.N2;
 #pragma unroll
             for (int ht = 0; ht < G2::HT; ++ht)
@@ -211,16 +222,18 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
 
     if (a.stats && tid == 0) {
         uint64_t* p = a.stats + 4 * blockIdx.x;
-        p[0] = t1 - t0; p[1] = t2 - t1; p[2] = wall_clock64() - t2; p[3] = 1;
+        p[0] = t1 - t0; p[1] = t2 - t1; p[2] = wall_clock64() - t2; p[3] = c1 - c0;   // p[3]: core clocks of phase 1
     }
     // ---------------------------------------------------------------- leave the flags clean
     // the last workgroup to get here resets the barrier counter for the next launch
     __syncthreads();
-    if (tid == 0) {
+    if (tid == 0 && both) {
         const uint32_t prev = __hip_atomic_fetch_add(a.flags + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (prev == (uint32_t)G - 1u) {
             __hip_atomic_store(a.flags, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(a.flags + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int i = 0; i < 8; ++i)
+                __hip_atomic_store(a.flags + kTwoPhaseGroupWord * (1 + i), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -294,7 +307,7 @@ hipError_t launch_fused_two_phase(int dtype, const TwoPhaseArgs& a, int bm, int 
         fn = dtype == 0 ? (g ? two_phase_fn<__bf16, true>(bm, bh1, bk) : two_phase_fn<__bf16, false>(bm, bh1, bk))
                         : (g ? two_phase_fn<_Float16, true>(bm, bh1, bk) : two_phase_fn<_Float16, false>(bm, bh1, bk));
     }
-    if (!fn || grid < 8 || (grid & 7) || a.raster < 1 || a.splits < 1) return hipErrorInvalidValue;
+    if (!fn || grid < 8 || (grid & 7) || a.raster < 1 || a.splits < 1 || a.phases < 1 || a.phases > 3) return hipErrorInvalidValue;
     TwoPhaseArgs copy = a;
     void* params[] = {&copy};
     return launch_resident(fn, grid, params, st);

@@ -51,14 +51,16 @@ def test_workspace_size_formula():
     # family) and partial planes | H | flags (two-phase family; as many planes as fit in 64 MiB)
     def two_phase(M, N1, N2, planes):
         r = lambda v: (v + 255) // 256 * 256
-        return (r(4 * M * N2 * planes) if planes > 1 else 0) + r(2 * M * N1) + 256
+        return (r(4 * M * N2 * planes) if planes > 1 else 0) + r(2 * M * N1) + 1024
     ring = 8192 + 8 * 64 * 256 * 256 * 2
     assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 4096, 4096, 16384, 4096, False) == max(4 * 4096 * 4096, ring, two_phase(4096, 16384, 4096, 1))
     assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 32768, 1024, 8192, 1024, False) == max(4 * 32768 * 1024, two_phase(32768, 8192, 1024, 1))
     assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 8192, 1024, 8192, 1024, False) == max(4 * 8192 * 1024, ring, two_phase(8192, 8192, 1024, 2))
     assert ff.ffuse_workspace_bytes(ff.DT_BF16, True, 64, 64, 64, 64, False) == max(8192 + 8 * 64 * 256 * 128 * 2, two_phase(64, 64, 64, 32))
     assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 512, 4096, 16384, 4096, False) == max(ring, two_phase(512, 16384, 4096, 8))
-    assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 4096, 4096, 16384, 4096, True) == 2 * 4096 * 16384
+    # unfused, 16-bit: the two-phase family's kernel, one phase per launch
+    assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 4096, 4096, 16384, 4096, True) == two_phase(4096, 16384, 4096, 1)
+    assert ff.ffuse_workspace_bytes(ff.DT_BF16, False, 512, 4096, 16384, 4096, True) == two_phase(512, 16384, 4096, 8)
     assert ff.ffuse_workspace_bytes(ff.DT_F32, False, 128, 256, 1024, 256, True) == 4 * 128 * 1024
     assert ff.ffuse_workspace_bytes(ff.DT_F32, False, 128, 256, 1024, 256, False) == 0
 
