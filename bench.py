@@ -38,6 +38,8 @@ def main():
                     help="before timing, profile the K analytically best plans on the device and use the fastest (0 = model's choice)")
     ap.add_argument("--model-check", type=int, default=0,
                     help="instead of the benchmark line: time the model's N best-ranked plans and print predicted vs measured")
+    ap.add_argument("--fused-only", action="store_true",
+                    help="skip the unfused and vendor comparison legs (for profiler runs: the unfused path launches the same kernel one phase at a time, which would mix into the per-kernel averages)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -107,14 +109,16 @@ def main():
     plan = ff.ffuse_last_plan()
     model = ff.ffuse_traffic_model(plan, dt, w.gated, w.M, w.K, w.N1, w.N2).as_dict()
     Y_fused = Y.clone()
-    print(f"[bench] {w.name}: timing the unfused call", file=sys.stderr, flush=True)
-    t_unf, k_unf = timed(unfused, max(3, args.steps // 2), 2)
-    diff = float((Y_fused.float() - Y.float()).abs().max() / Y.float().abs().max())
+    t_unf = k_unf = diff = float("nan")
+    if not args.fused_only:
+        print(f"[bench] {w.name}: timing the unfused call", file=sys.stderr, flush=True)
+        t_unf, k_unf = timed(unfused, max(3, args.steps // 2), 2)
+        diff = float((Y_fused.float() - Y.float()).abs().max() / Y.float().abs().max())
 
     # context: the vendor library's unfused chain on the same tensors (hipBLASLt GEMMs through
     # torch.matmul plus torch's elementwise kernels); not part of the hot path
     t_vendor = None
-    if w.dtype != "f32":
+    if w.dtype != "f32" and not args.fused_only:
         def vendor_step():
             h = torch.matmul(dev["X"], dev["W1"])
             if w.act == 1:
@@ -162,8 +166,9 @@ def main():
                    "plan": plan.as_dict(), "plan_from": "forced" if args.plan else ("tuned top-%d" % args.tune if args.tune > 0 and w.dtype != "f32" else "model")},
         "pct_mfma_peak": 100.0 * value / MFMA_PEAK_TFLOPS,
         "roofline": roof,
-        "unfused": {"ms_per_step": t_unf * 1e3, "tflops": flops / t_unf * 1e-12, "kernels_ms": k_unf * 1e3,
-                    "max_rel_diff_vs_fused": diff},
+        "unfused": None if args.fused_only else {
+            "ms_per_step": t_unf * 1e3, "tflops": flops / t_unf * 1e-12, "kernels_ms": k_unf * 1e3,
+            "max_rel_diff_vs_fused": diff, "kind": "the same kernel and tile plan as the model's best two-phase plan, one launch per phase"},
         "bytes": {"q_min": w.q_min(), "q_unfused": w.q_unfused(), "model_hbm": model["hbm_bytes"],
                   "model_reduce": model["reduce_bytes"], "model_fabric": model["fabric_bytes"]},
         "model_t_pred_ms": model["t_pred"] * 1e3,
