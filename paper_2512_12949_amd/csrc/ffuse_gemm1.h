@@ -40,7 +40,8 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 // NS_: stages in the ring (a power of two, 4 to 16): loads run NS_ - 1 stages ahead.  Four keeps a
 // 256 x 256 tile fed; eight is for small tiles in the weight-streaming regime, where the
 // bytes a workgroup keeps in flight set the rate at which it can pull weights.
-template <typename T, bool GATED, int BM, int BH, int WM, int WN, int NS_ = 4>
+// NT_: the weight tiles can be loaded with the non-temporal hint (Ctx::nt, see buf_load16_nt)
+template <typename T, bool GATED, int BM, int BH, int WM, int WN, int NS_ = 4, bool NT_ = false>
 struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     typedef FirstGemm<T, GATED, BM, BH, WM, WN> Base;
     typedef typename Base::vec8 vec8;
@@ -81,7 +82,9 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         uint32_t rdx[MT];       // LDS read offsets: A fragments (sub-step 0)
         uint32_t rdw[HT];       //                   B fragments (sub-step 0, first half)
         bool a_lane;            // this lane takes part in A loads (all lanes unless HALF_A)
+        bool nt;                // NT_ only: weight loads carry the non-temporal hint (uniform)
     };
+    static __device__ __forceinline__ void set_nt(Ctx& c, bool nt) { c.nt = NT_ && nt; }
 
     static __device__ __forceinline__ void init_a(Ctx& c, const void* A, uint32_t a_bytes, uint32_t base_bytes,
                                                   uint32_t row0, uint32_t lda, int kx, int tid) {
@@ -144,6 +147,10 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         asm volatile("s_mov_b32 m0, %1\n\tbuffer_load_dwordx4 %0, %2, 0 offen lds"
                      :: "v"(voff), "s"(lds), "s"(r) : "memory", "m0");
     }
+    static __device__ __forceinline__ void lds_dma16_nt(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t lds) {
+        asm volatile("s_mov_b32 m0, %1\n\tbuffer_load_dwordx4 %0, %2, 0 offen nt lds"
+                     :: "v"(voff), "s"(lds), "s"(r) : "memory", "m0");
+    }
     // load instruction i of the step whose A columns start at kx and whose B rows start at kw.
     // A chunks at or past column xlim, and everything when `valid` is false, load nothing from
     // memory (out-of-range offsets: LDS receives zeros) -- the instruction is issued all the
@@ -157,8 +164,10 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         } else {
             const int which = (i - XI) / BI, j = (i - XI) % BI;
             const uint32_t off = c.boff[j];
-            lds_dma16(c.rw[which], (off == kOob || !valid) ? kOob : off + (uint32_t)kw * c.brow,
-                      (uint32_t)(uintptr_t)stage + c.lds_b + (uint32_t)which * WB + (uint32_t)j * 1024u);
+            const uint32_t vo = (off == kOob || !valid) ? kOob : off + (uint32_t)kw * c.brow;
+            const uint32_t la = (uint32_t)(uintptr_t)stage + c.lds_b + (uint32_t)which * WB + (uint32_t)j * 1024u;
+            if (NT_ && c.nt) lds_dma16_nt(c.rw[which], vo, la);
+            else lds_dma16(c.rw[which], vo, la);
         }
     }
     static __device__ __forceinline__ void issue(char* stage, const Ctx& c, int kx, int kw, int xlim, bool valid) {

@@ -71,6 +71,7 @@ struct TwoPhaseArgs {
     // 3x3 first product (conv_ic > 0): X is a channels-last image of M pixels (conv_h x conv_w
     // per image) with conv_ic channels, W1 is [3][3][conv_ic][N1], K = 9 * conv_ic
     int conv_ic, conv_h, conv_w;
+    int nt;           // != 0: the weights are streamed with the non-temporal hint (row blocks below 256 only)
     int phases;       // 3: both phases with the device-wide barrier between them (the fused chain);
                       // 1 / 2: only the first / second phase (two launches = the unfused comparison path)
 };

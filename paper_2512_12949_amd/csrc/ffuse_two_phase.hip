@@ -53,8 +53,8 @@ __device__ __forceinline__ bool map_item(int MB, int S, int raster, int xcd, int
 template <typename T, bool GATED, int BM, bool CONV, int BH1_, bool DEEP_> struct TwoPhaseGemms {
     static constexpr int BH1 = BH1_;
     static constexpr int WM1 = BH1 == 128 ? 1 : (BH1 == 64 ? 2 : 4);
-    typedef FirstGemm<T, GATED, BM, BH1, WM1, 4 / WM1, CONV> G1;   // phase 1: X * W1 (, X * W3); CONV: im2col(X) * W1
-    typedef FirstGemm<T, false, BM, 256, 1, 4> G2;   // phase 2: H * W2
+    typedef FirstGemm<T, GATED, BM, BH1, WM1, 4 / WM1, CONV, true> G1;   // phase 1: X * W1 (, X * W3); CONV: im2col(X) * W1
+    typedef FirstGemm<T, false, BM, 256, 1, 4, false, true> G2;   // phase 2: H * W2
     static constexpr bool DEEP = false;
 };
 template <typename T, bool GATED, int BH1_, bool DEEP_> struct TwoPhaseGemms<T, GATED, 256, false, BH1_, DEEP_> {
@@ -67,32 +67,32 @@ template <typename T, bool GATED, int BH1_, bool DEEP_> struct TwoPhaseGemms<T, 
 // phase: more bytes in flight per workgroup than the register-staged loop can hold
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 128, true> {
     static constexpr int BH1 = 128;
-    typedef DeepGemm<T, GATED, 128, 128, 2, 2, GATED ? 4 : 8> G1;
-    typedef DeepGemm<T, false, 128, 256, 2, 2, 4> G2;
+    typedef DeepGemm<T, GATED, 128, 128, 2, 2, GATED ? 4 : 8, true> G1;
+    typedef DeepGemm<T, false, 128, 256, 2, 2, 4, true> G2;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 64, true> {
     static constexpr int BH1 = 64;
-    typedef DeepGemm<T, GATED, 128, 64, 2, 2, 8> G1;
-    typedef DeepGemm<T, false, 128, 256, 2, 2, 4> G2;
+    typedef DeepGemm<T, GATED, 128, 64, 2, 2, 8, true> G1;
+    typedef DeepGemm<T, false, 128, 256, 2, 2, 4, true> G2;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 64, true> {
     static constexpr int BH1 = 64;
-    typedef DeepGemm<T, GATED, 64, 64, 2, 2, 8> G1;
-    typedef DeepGemm<T, false, 64, 256, 2, 2, 4> G2;
+    typedef DeepGemm<T, GATED, 64, 64, 2, 2, 8, true> G1;
+    typedef DeepGemm<T, false, 64, 256, 2, 2, 4, true> G2;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 32, false, 128, true> {
     static constexpr int BH1 = 128;
-    typedef DeepGemm<T, GATED, 32, 128, 1, 4, 8> G1;   // (a sixteen-stage ring measured no faster)
-    typedef DeepGemm<T, false, 32, 256, 1, 4, 8> G2;
+    typedef DeepGemm<T, GATED, 32, 128, 1, 4, 8, true> G1;   // (a sixteen-stage ring measured no faster)
+    typedef DeepGemm<T, false, 32, 256, 1, 4, 8, true> G2;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 128, true> {
     static constexpr int BH1 = 128;
-    typedef DeepGemm<T, GATED, 64, 128, 2, 2, GATED ? 4 : 8> G1;
-    typedef DeepGemm<T, false, 64, 256, 2, 2, 4> G2;
+    typedef DeepGemm<T, GATED, 64, 128, 2, 2, GATED ? 4 : 8, true> G1;
+    typedef DeepGemm<T, false, 64, 256, 2, 2, 4, true> G2;
     static constexpr bool DEEP = true;
 };
 
@@ -123,6 +123,7 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
         f32x16 acc3[GATED ? G1::HT : 1][GATED ? G1::MT : 1];
         typename G1::Ctx c;
         G1::init_lds(c, tid);
+        G1::set_nt(c, a.nt != 0);
         const int NS = (a.N1 + BH1 - 1) / BH1;
         int rb, s;
         for (int idx = loc; map_item(MB, NS, a.raster, xcd, idx, rb, s); idx += GX) {
@@ -179,6 +180,7 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
         f32x16 acc3[1][1];
         typename G2::Ctx c;
         G2::init_lds(c, tid);
+        G2::set_nt(c, a.nt != 0);
         const int NCB = (a.N2 + BH2 - 1) / BH2;
         const int wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
         constexpr int WM2 = G2::WMR == BM ? 1 : 2;   // waves along the rows of a phase-2 tile
