@@ -26,8 +26,8 @@ namespace ffuse {
 // convolution over a channels-last image (row m = pixel m, column k = tap * IC + channel):
 // the loader adds the tap's pixel shift to the row's address and masks the taps that fall
 // outside the image.  IC must be a multiple of 64, so that a K step of 64 stays in one tap.
-// NT: the weight tiles can be loaded with the non-temporal hint (Ctx::nt, uniform, chosen by the host
-// for weights that are streamed once and too large for the memory-side cache to keep)
+// NT: the weight tiles are loaded with the non-temporal hint (for weights that are streamed once
+// and too large for the memory-side cache to keep; the caller picks the instantiation)
 template <typename T, bool GATED, int BM, int BH, int WM, int WN, bool CONV = false, bool NT = false>
 struct FirstGemm {
     static_assert(WM * WN == 4, "four waves");
@@ -66,9 +66,7 @@ struct FirstGemm {
         // CONV only: channels and width of the image; per row, bit t set = tap t is inside the image
         int conv_ic, conv_w;
         uint32_t vmask[CONV ? XCH : 1];
-        bool nt;              // NT only: load the weight tiles with the non-temporal hint
     };
-    static __device__ __forceinline__ void set_nt(Ctx& c, bool nt) { c.nt = NT && nt; }
 
     // A operand: `rows x lda` elements at `A` (+ base_bytes), first row row0; rows past the
     // end of the buffer read as zero.
@@ -176,7 +174,7 @@ struct FirstGemm {
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
                 const uint32_t off = (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow;
-                s.w[q][r] = (NT && c.nt) ? buf_load16_nt(c.rw[q], off) : buf_load16(c.rw[q], off);
+                s.w[q][r] = NT ? buf_load16_nt(c.rw[q], off) : buf_load16(c.rw[q], off);
             }
         }
     }
@@ -316,7 +314,7 @@ struct FirstGemm {
                         for (int e = (i2 * 8 * WPT) / (H2 > 0 ? H2 : 1); e < ((i2 + 1) * 8 * WPT) / (H2 > 0 ? H2 : 1); ++e) {
                             const int q = e / 8, r = e % 8;
                             const uint32_t base = c.woff[q];
-                            st.w[q][r] = (NT && c.nt) ? buf_load16_nt(c.rw[q], (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow) : buf_load16(c.rw[q], (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow);
+                            st.w[q][r] = NT ? buf_load16_nt(c.rw[q], (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow) : buf_load16(c.rw[q], (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow);
                         }
                     }
                     if (H2 == 0 && i == NM - 1) {   // a single MFMA per sub-step: refill right after the stores
@@ -324,7 +322,7 @@ struct FirstGemm {
                         for (int e = 0; e < 8 * WPT; ++e) {
                             const int q = e / 8, r = e % 8;
                             const uint32_t base = c.woff[q];
-                            st.w[q][r] = (NT && c.nt) ? buf_load16_nt(c.rw[q], (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow) : buf_load16(c.rw[q], (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow);
+                            st.w[q][r] = NT ? buf_load16_nt(c.rw[q], (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow) : buf_load16(c.rw[q], (base == kOob) ? kOob : base + kb + (uint32_t)r * c.wrow);
                         }
                     }
                 }

@@ -40,7 +40,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 // NS_: stages in the ring (a power of two, 4 to 16): loads run NS_ - 1 stages ahead.  Four keeps a
 // 256 x 256 tile fed; eight is for small tiles in the weight-streaming regime, where the
 // bytes a workgroup keeps in flight set the rate at which it can pull weights.
-// NT_: the weight tiles can be loaded with the non-temporal hint (Ctx::nt, see buf_load16_nt)
+// NT_: the weight tiles are loaded with the non-temporal hint (see buf_load16_nt)
 template <typename T, bool GATED, int BM, int BH, int WM, int WN, int NS_ = 4, bool NT_ = false>
 struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     typedef FirstGemm<T, GATED, BM, BH, WM, WN> Base;
@@ -82,9 +82,7 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         uint32_t rdx[MT];       // LDS read offsets: A fragments (sub-step 0)
         uint32_t rdw[HT];       //                   B fragments (sub-step 0, first half)
         bool a_lane;            // this lane takes part in A loads (all lanes unless HALF_A)
-        bool nt;                // NT_ only: weight loads carry the non-temporal hint (uniform)
     };
-    static __device__ __forceinline__ void set_nt(Ctx& c, bool nt) { c.nt = NT_ && nt; }
 
     static __device__ __forceinline__ void init_a(Ctx& c, const void* A, uint32_t a_bytes, uint32_t base_bytes,
                                                   uint32_t row0, uint32_t lda, int kx, int tid) {
@@ -166,7 +164,7 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
             const uint32_t off = c.boff[j];
             const uint32_t vo = (off == kOob || !valid) ? kOob : off + (uint32_t)kw * c.brow;
             const uint32_t la = (uint32_t)(uintptr_t)stage + c.lds_b + (uint32_t)which * WB + (uint32_t)j * 1024u;
-            if (NT_ && c.nt) lds_dma16_nt(c.rw[which], vo, la);
+            if (NT_) lds_dma16_nt(c.rw[which], vo, la);
             else lds_dma16(c.rw[which], vo, la);
         }
     }

@@ -53,57 +53,138 @@ __device__ __forceinline__ bool map_item(int MB, int S, int raster, int xcd, int
 template <typename T, bool GATED, int BM, bool CONV, int BH1_, bool DEEP_> struct TwoPhaseGemms {
     static constexpr int BH1 = BH1_;
     static constexpr int WM1 = BH1 == 128 ? 1 : (BH1 == 64 ? 2 : 4);
-    typedef FirstGemm<T, GATED, BM, BH1, WM1, 4 / WM1, CONV, true> G1;   // phase 1: X * W1 (, X * W3); CONV: im2col(X) * W1
-    typedef FirstGemm<T, false, BM, 256, 1, 4, false, true> G2;   // phase 2: H * W2
+    template <bool NT> using G1 = FirstGemm<T, GATED, BM, BH1, WM1, 4 / WM1, CONV, NT>;   // phase 1: X * W1 (, X * W3); CONV: im2col(X) * W1
+    template <bool NT> using G2 = FirstGemm<T, false, BM, 256, 1, 4, false, NT>;   // phase 2: H * W2
+    static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = false;
 };
 template <typename T, bool GATED, int BH1_, bool DEEP_> struct TwoPhaseGemms<T, GATED, 256, false, BH1_, DEEP_> {
     static constexpr int BH1 = GATED ? 128 : 256;
-    typedef DeepGemm<T, GATED, 256, BH1, 2, 2> G1;
-    typedef DeepGemm<T, false, 256, 256, 2, 2> G2;
+    template <bool NT> using G1 = DeepGemm<T, GATED, 256, BH1, 2, 2>;
+    template <bool NT> using G2 = DeepGemm<T, false, 256, 256, 2, 2>;
+    static constexpr bool HAS_NT = false;   // 256-row blocks re-use their weight tiles through L2
     static constexpr bool DEEP = true;
 };
 // 64 / 128 rows with the LDS-direct block GEMM (2 x 2 waves) and a deeper ring in the first
 // phase: more bytes in flight per workgroup than the register-staged loop can hold
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 128, true> {
     static constexpr int BH1 = 128;
-    typedef DeepGemm<T, GATED, 128, 128, 2, 2, GATED ? 4 : 8, true> G1;
-    typedef DeepGemm<T, false, 128, 256, 2, 2, 4, true> G2;
+    template <bool NT> using G1 = DeepGemm<T, GATED, 128, 128, 2, 2, GATED ? 4 : 8, NT>;
+    template <bool NT> using G2 = DeepGemm<T, false, 128, 256, 2, 2, 4, NT>;
+    static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 64, true> {
     static constexpr int BH1 = 64;
-    typedef DeepGemm<T, GATED, 128, 64, 2, 2, 8, true> G1;
-    typedef DeepGemm<T, false, 128, 256, 2, 2, 4, true> G2;
+    template <bool NT> using G1 = DeepGemm<T, GATED, 128, 64, 2, 2, 8, NT>;
+    template <bool NT> using G2 = DeepGemm<T, false, 128, 256, 2, 2, 4, NT>;
+    static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 64, true> {
     static constexpr int BH1 = 64;
-    typedef DeepGemm<T, GATED, 64, 64, 2, 2, 8, true> G1;
-    typedef DeepGemm<T, false, 64, 256, 2, 2, 4, true> G2;
+    template <bool NT> using G1 = DeepGemm<T, GATED, 64, 64, 2, 2, 8, NT>;
+    template <bool NT> using G2 = DeepGemm<T, false, 64, 256, 2, 2, 4, NT>;
+    static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 32, false, 128, true> {
     static constexpr int BH1 = 128;
-    typedef DeepGemm<T, GATED, 32, 128, 1, 4, 8, true> G1;   // (a sixteen-stage ring measured no faster)
-    typedef DeepGemm<T, false, 32, 256, 1, 4, 8, true> G2;
+    template <bool NT> using G1 = DeepGemm<T, GATED, 32, 128, 1, 4, 8, NT>;   // (a sixteen-stage ring measured no faster)
+    template <bool NT> using G2 = DeepGemm<T, false, 32, 256, 1, 4, 8, NT>;
+    static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 128, true> {
     static constexpr int BH1 = 128;
-    typedef DeepGemm<T, GATED, 64, 128, 2, 2, GATED ? 4 : 8, true> G1;
-    typedef DeepGemm<T, false, 64, 256, 2, 2, 4, true> G2;
+    template <bool NT> using G1 = DeepGemm<T, GATED, 64, 128, 2, 2, GATED ? 4 : 8, NT>;
+    template <bool NT> using G2 = DeepGemm<T, false, 64, 256, 2, 2, 4, NT>;
+    static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
 };
 
+// Phase 1 for one workgroup: its share of the (row block, hidden slice) items.  G1 is the block
+// GEMM (with or without the non-temporal hint on its weight loads).
+template <typename G1, bool CONV, bool DEEP, int BM, int BH1>
+__device__ __forceinline__ void two_phase_first(const TwoPhaseArgs& a, char* smem, int tid, int xcd, int loc, int GX, int MB) {
+    f32x16 acc[G1::HT][G1::MT];
+    f32x16 acc3[G1::G == 2 ? G1::HT : 1][G1::G == 2 ? G1::MT : 1];
+    typename G1::Ctx c;
+    G1::init_lds(c, tid);
+    const int NS = (a.N1 + BH1 - 1) / BH1;
+    int rb, s;
+    for (int idx = loc; map_item(MB, NS, a.raster, xcd, idx, rb, s); idx += GX) {
+        if constexpr (CONV)
+            G1::init_a_conv(c, a.X, (uint32_t)((uint64_t)a.M * a.conv_ic * 2), (uint32_t)rb * BM, a.M, a.conv_h, a.conv_w, a.conv_ic, tid);
+        else
+            G1::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)rb * BM, (uint32_t)a.K, a.K, tid);
+        G1::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1, (uint32_t)s * BH1, tid);
+        if constexpr (DEEP) G1::run(smem, c, 0, a.K, acc, acc3, tid);
+        else G1::run_deep(smem, c, 0, a.K, acc, acc3, tid);
+        G1::template store_tile_lds_rt<true>(smem, a.act, acc, acc3, reinterpret_cast<char*>(a.H), a.N1, (int64_t)rb * BM, s * BH1, a.M, a.N1, tid);
+        __syncthreads();   // LDS is free again before the next item's loads
+    }
+}
+
+// Phase 2 for one workgroup: its share of the (row block, 256 output columns, hidden range) items.
+template <typename G2, bool DEEP, int BM>
+__device__ __forceinline__ void two_phase_second(const TwoPhaseArgs& a, char* smem, int tid, int xcd, int loc, int GX, int MB) {
+    constexpr int BH2 = 256;
+    f32x16 acc[G2::HT][G2::MT];
+    f32x16 acc3[1][1];
+    typename G2::Ctx c;
+    G2::init_lds(c, tid);
+    const int NCB = (a.N2 + BH2 - 1) / BH2;
+    const int wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    constexpr int WM2 = G2::WMR == BM ? 1 : 2;   // waves along the rows of a phase-2 tile
+    const int wm = wave % WM2, wn = wave / WM2;
+    int rb, u;
+    // slices of this phase: u = range * NCB + column block, so that neighbours share their part of H
+    for (int idx = loc; map_item(MB, NCB * a.splits, a.raster, xcd, idx, rb, u); idx += GX) {
+        const int cb = u % NCB, sp = u / NCB;
+        const int k0 = sp * a.ksplit, k1 = min(a.N1, k0 + a.ksplit);
+        G2::init_a(c, a.H, (uint32_t)((uint64_t)a.M * a.N1 * 2), 0u, (uint32_t)rb * BM, (uint32_t)a.N1, a.N1, tid);
+        G2::init_b(c, a.W2, nullptr, (uint32_t)((uint64_t)a.N1 * a.N2 * 2), (uint32_t)a.N2, (uint32_t)a.N2, (uint32_t)cb * BH2, tid);
+        if constexpr (DEEP) G2::run(smem, c, k0, k1, acc, acc3, tid);
+        else G2::run_deep(smem, c, k0, k1, acc, acc3, tid);
+        if (a.splits == 1) {
+            G2::template store_tile_lds<ACT_IDENTITY>(smem, acc, acc3, reinterpret_cast<char*>(a.Y), a.N2, (int64_t)rb * BM,
+                                                      cb * BH2, a.M, a.N2, tid);
+            __syncthreads();
+            continue;
+        }
+        // acc[ht][mt][4q..4q+3]: row wm*WMR + 32*mt + x, columns wn*WHR + 32*ht + 8*q + 4*h + 0..3 of the tile
+        // -> one 16-byte store into this range's own partial-sum plane (no atomics: the
+        //    planes are summed in a fixed order by the finalize pass)
+        // (ordinary write-back stores: writing the planes or Y through as well measured 3-7 % slower)
+        float* plane = a.part + (size_t)sp * (size_t)a.M * a.N2;
+#pragma unroll
+        for (int ht = 0; ht < G2::HT; ++ht)
+#pragma unroll
+            for (int mt = 0; mt < G2::MT; ++mt) {
+                const int64_t row = (int64_t)rb * BM + wm * G2::WMR + 32 * mt + x;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = cb * BH2 + wn * G2::WHR + 32 * ht + 8 * q + 4 * h;
+                    if (row < a.M && col < a.N2) {
+                        f32x4 v = {acc[ht][mt][4 * q], acc[ht][mt][4 * q + 1], acc[ht][mt][4 * q + 2], acc[ht][mt][4 * q + 3]};
+                        *reinterpret_cast<f32x4*>(plane + row * a.N2 + col) = v;
+                    }
+                }
+            }
+    }
+}
+
 // CONV: the first product is a 3x3 convolution (rows = pixels of a channels-last image,
 // a.K = 9 * a.conv_ic); everything after the first product's loads is unchanged.
+// a.nt selects, per launch, the instantiations of the block GEMMs that stream the weights with
+// the non-temporal hint (row blocks below 256 only): the loops themselves stay branch-free.
 template <typename T, bool GATED, int BM, bool CONV = false, int BH1_ = 128, bool DEEP_ = false>
 __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
     typedef TwoPhaseGemms<T, GATED, BM, CONV, BH1_, DEEP_> TG;
-    typedef typename TG::G1 G1;
-    typedef typename TG::G2 G2;
-    constexpr int BH1 = TG::BH1, BH2 = 256;
+    typedef typename TG::template G1<false> G1;
+    typedef typename TG::template G2<false> G2;
+    constexpr int BH1 = TG::BH1;
     constexpr int LDS_BYTES = G1::LDS_BYTES > G2::LDS_BYTES ? G1::LDS_BYTES : G2::LDS_BYTES;
     __shared__ __attribute__((aligned(16))) char smem[LDS_BYTES];
     // the barrier's verdict word lives in the stage memory, which is idle between the phases
@@ -119,24 +200,8 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
 
     // ---------------------------------------------------------------- phase 1
     if (a.phases & 1) {
-        f32x16 acc[G1::HT][G1::MT];
-        f32x16 acc3[GATED ? G1::HT : 1][GATED ? G1::MT : 1];
-        typename G1::Ctx c;
-        G1::init_lds(c, tid);
-        G1::set_nt(c, a.nt != 0);
-        const int NS = (a.N1 + BH1 - 1) / BH1;
-        int rb, s;
-        for (int idx = loc; map_item(MB, NS, a.raster, xcd, idx, rb, s); idx += GX) {
-            if constexpr (CONV)
-                G1::init_a_conv(c, a.X, (uint32_t)((uint64_t)a.M * a.conv_ic * 2), (uint32_t)rb * BM, a.M, a.conv_h, a.conv_w, a.conv_ic, tid);
-            else
-                G1::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)rb * BM, (uint32_t)a.K, a.K, tid);
-            G1::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1, (uint32_t)s * BH1, tid);
-            if constexpr (TG::DEEP) G1::run(smem, c, 0, a.K, acc, acc3, tid);
-            else G1::run_deep(smem, c, 0, a.K, acc, acc3, tid);
-            G1::template store_tile_lds_rt<true>(smem, a.act, acc, acc3, reinterpret_cast<char*>(a.H), a.N1, (int64_t)rb * BM, s * BH1, a.M, a.N1, tid);
-            __syncthreads();   // LDS is free again before the next item's loads
-        }
+        if (TG::HAS_NT && a.nt) two_phase_first<typename TG::template G1<true>, CONV, TG::DEEP, BM, BH1>(a, smem, tid, xcd, loc, GX, MB);
+        else two_phase_first<G1, CONV, TG::DEEP, BM, BH1>(a, smem, tid, xcd, loc, GX, MB);
     }
 
     if (a.stats) { t1 = wall_clock64(); c1 = clock64(); }
@@ -176,50 +241,8 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
 
     // ---------------------------------------------------------------- phase 2
     if (ok && (a.phases & 2)) {
-        f32x16 acc[G2::HT][G2::MT];
-        f32x16 acc3[1][1];
-        typename G2::Ctx c;
-        G2::init_lds(c, tid);
-        G2::set_nt(c, a.nt != 0);
-        const int NCB = (a.N2 + BH2 - 1) / BH2;
-        const int wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
-        constexpr int WM2 = G2::WMR == BM ? 1 : 2;   // waves along the rows of a phase-2 tile
-        const int wm = wave % WM2, wn = wave / WM2;
-        int rb, u;
-        // slices of this phase: u = range * NCB + column block, so that neighbours share their part of H
-        for (int idx = loc; map_item(MB, NCB * a.splits, a.raster, xcd, idx, rb, u); idx += GX) {
-            const int cb = u % NCB, sp = u / NCB;
-            const int k0 = sp * a.ksplit, k1 = min(a.N1, k0 + a.ksplit);
-            G2::init_a(c, a.H, (uint32_t)((uint64_t)a.M * a.N1 * 2), 0u, (uint32_t)rb * BM, (uint32_t)a.N1, a.N1, tid);
-            G2::init_b(c, a.W2, nullptr, (uint32_t)((uint64_t)a.N1 * a.N2 * 2), (uint32_t)a.N2, (uint32_t)a.N2, (uint32_t)cb * BH2, tid);
-            if constexpr (TG::DEEP) G2::run(smem, c, k0, k1, acc, acc3, tid);
-            else G2::run_deep(smem, c, k0, k1, acc, acc3, tid);
-            if (a.splits == 1) {
-                G2::template store_tile_lds<ACT_IDENTITY>(smem, acc, acc3, reinterpret_cast<char*>(a.Y), a.N2, (int64_t)rb * BM,
-                                                          cb * BH2, a.M, a.N2, tid);
-                __syncthreads();
-                continue;
-            }
-            // acc[ht][mt][4q..4q+3]: row wm*WMR + 32*mt + x, columns wn*WHR + 32*ht + 8*q + 4*h + 0..3 of the tile
-            // -> one 16-byte store into this range's own partial-sum plane (no atomics: the
-            //    planes are summed in a fixed order by the finalize pass)
-            // (ordinary write-back stores: writing the planes or Y through as well measured 3-7 % slower)
-            float* plane = a.part + (size_t)sp * (size_t)a.M * a.N2;
-#pragma unroll
-            for (int ht = 0; ht < G2::HT; ++ht)
-#pragma unroll
-                for (int mt = 0; mt < G2::MT; ++mt) {
-                    const int64_t row = (int64_t)rb * BM + wm * G2::WMR + 32 * mt + x;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int col = cb * BH2 + wn * G2::WHR + 32 * ht + 8 * q + 4 * h;
-                        if (row < a.M && col < a.N2) {
-                            f32x4 v = {acc[ht][mt][4 * q], acc[ht][mt][4 * q + 1], acc[ht][mt][4 * q + 2], acc[ht][mt][4 * q + 3]};
-                            *reinterpret_cast<f32x4*>(plane + row * a.N2 + col) = v;
-                        }
-                    }
-                }
-        }
+        if (TG::HAS_NT && a.nt) two_phase_second<typename TG::template G2<true>, TG::DEEP, BM>(a, smem, tid, xcd, loc, GX, MB);
+        else two_phase_second<G2, TG::DEEP, BM>(a, smem, tid, xcd, loc, GX, MB);
     }
 
     if (a.stats && tid == 0) {
