@@ -165,8 +165,7 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
 // cache can keep between calls are not (the hint cost 10-40 % on the 64-270 MB shapes when the
 // same weights are used call after call).
 int stream_weights(int dtype, int gated, int64_t K, int64_t N1, int64_t N2) {
-    static const int forced = [] { const char* e = std::getenv("FFUSE_NT"); return e ? std::atoi(e) : -1; }();
-    if (forced >= 0) return forced;
+    if (const char* env = std::getenv("FFUSE_NT")) return std::atoi(env) != 0;   // read per call: a test can switch it
     const double e = dtype == FFUSE_DT_F32 ? 4.0 : 2.0;
     return e * ((gated ? 2.0 : 1.0) * (double)K * (double)N1 + (double)N1 * (double)N2) > 512.0 * 1024 * 1024 ? 1 : 0;
 }

@@ -146,6 +146,48 @@ def test_two_phase_narrow_hidden_slices(dtype, gated):
             gu.run(w, dev, plan=ff.make_plan(ff.FAMILY_TWOPHASE, bm=128, bh=32, splits=1))
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("gated", [False, True])
+def test_two_phase_non_temporal_weight_streaming(dtype, gated, monkeypatch):
+    """The instantiations that stream the weights with the non-temporal hint (chosen by the
+    library for weights far larger than the memory-side cache; forced here on small ragged
+    shapes): every row block below 256 in both block GEMMs, and the same bits as without
+    the hint."""
+    act = ACT_SILU if gated else ACT_GELU_TANH
+    for (M, K, N1, N2) in [(20, 136, 392, 520), (128, 200, 840, 264), (300, 72, 1304, 136)]:
+        w, host, dev = _case("nt", M, K, N1, N2, dtype, act, gated)
+        ref = gu.oracle_rows(w, host)
+        for bm, bh, bk, splits in ((32, 128, 64, 2), (32, 128, 32, 2), (64, 128, 64, 1), (64, 64, 32, 3), (128, 128, 64, 1),
+                                   (128, 128, 32, 2), (128, 64, 32, 3), (128, 64, 64, 1)):
+            if M > 4 * bm and bm < 128:
+                continue
+            plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=bh, bk=bk, splits=splits, raster=2)
+            print(f"non-temporal {dtype} gated={gated} shape {(M, K, N1, N2)} bm={bm} bh={bh} bk={bk} splits={splits}", flush=True)
+            monkeypatch.setenv("FFUSE_NT", "0")
+            plain = gu.run(w, dev, plan=plan)
+            monkeypatch.setenv("FFUSE_NT", "1")
+            hinted = gu.run(w, dev, plan=plan)
+            gu.check(hinted, ref, dtype, what=f"non-temporal bm={bm} bh={bh} bk={bk}")
+            assert torch.equal(plain, hinted)
+    monkeypatch.delenv("FFUSE_NT")
+
+
+def test_two_launches_give_the_fused_calls_bits():
+    """The unfused comparison path runs the fused kernel one phase per launch in the model's
+    best two-phase plan: forced to that plan, the fused call must produce the same bits."""
+    for (M, K, N1, N2, gated) in [(16, 520, 2056, 264, True), (128, 264, 4104, 520, False), (700, 136, 1304, 264, True)]:
+        act = ACT_SILU if gated else ACT_GELU_TANH
+        w, host, dev = _case("twolaunch", M, K, N1, N2, "bf16", act, gated)
+        ref = gu.oracle_rows(w, host)
+        two = gu.run(w, dev, unfused=True)
+        gu.check(two, ref, "bf16", what="two launches")
+        ranked = ff.ffuse_rank_plans(ff.DT_BF16, act, gated, M, K, N1, N2, 64)
+        best = [p for p, _ in ranked if p.family == ff.FAMILY_TWOPHASE][0]
+        print(f"two launches vs fused, shape {(M, K, N1, N2)} gated={gated}, plan {best.as_dict()}", flush=True)
+        one = gu.run(w, dev, plan=best)
+        assert torch.equal(one, two)
+
+
 @pytest.mark.parametrize("act", [ACT_RELU, ACT_GELU_TANH, ACT_SILU, ACT_IDENTITY])
 @pytest.mark.parametrize("gated", [False, True])
 def test_activations_medium(act, gated):
