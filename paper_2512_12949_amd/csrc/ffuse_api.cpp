@@ -166,8 +166,7 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
 // same weights are used call after call).
 int stream_weights(int dtype, int gated, int64_t K, int64_t N1, int64_t N2) {
     if (const char* env = std::getenv("FFUSE_NT")) return std::atoi(env) != 0;   // read per call: a test can switch it
-    const double e = dtype == FFUSE_DT_F32 ? 4.0 : 2.0;
-    return e * ((gated ? 2.0 : 1.0) * (double)K * (double)N1 + (double)N1 * (double)N2) > 512.0 * 1024 * 1024 ? 1 : 0;
+    return ffuse::weights_streamed(dtype, gated, K, N1, N2) ? 1 : 0;
 }
 
 // launches one validated plan; the caller holds the lock.  two_launches (two-phase family

@@ -78,6 +78,11 @@ bool exchange_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, 
     return true;
 }
 
+bool weights_streamed(int dtype, int gated, int64_t K, int64_t N1, int64_t N2) {
+    const double e = dtype == FFUSE_DT_F32 ? 4.0 : 2.0;
+    return e * ((gated ? 2.0 : 1.0) * (double)K * (double)N1 + (double)N1 * (double)N2) > 512.0 * 1024 * 1024;
+}
+
 int two_phase_max_splits(int64_t M, int64_t N2) {
     // as many partial-sum planes as fit in 64 MiB
     int sp = 32;
@@ -301,8 +306,10 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         const double re2 = b2 * (patches - 1.0) + e * m * n1 * std::max(0.0, ncb / cols_per_patch / 8.0 - 1.0) + e * m * n1;
         // pipeline fill and epilogue per item: the LDS-direct loop primes its ring faster (measured on the m = 128 tables)
         const double per_item = (sg.bk == 32 && sg.bm < 256) ? 1.5e-6 : 3e-6;
-        const double t1 = b1 / std::min(d.hbm_bw, std::min(items1, (double)d.cus) * per_wg1) + re1 / d.fabric_bw + per_item * cdiv(items1, d.cus);
-        const double t2 = b2 / std::min(d.hbm_bw, std::min(items, (double)d.cus) * per_wg2) + re2 / d.fabric_bw + per_item * cdiv(items, d.cus);
+        // weights streamed with the non-temporal hint are not kept for the next row block: each streams its own copy
+        const double copies = (weights_streamed(dtype, gated, K, N1, N2) && sg.bm < 256) ? mb : 1.0;
+        const double t1 = copies * b1 / std::min(d.hbm_bw, std::min(items1, (double)d.cus) * per_wg1) + re1 / d.fabric_bw + per_item * cdiv(items1, d.cus);
+        const double t2 = copies * b2 / std::min(d.hbm_bw, std::min(items, (double)d.cus) * per_wg2) + re2 / d.fabric_bw + per_item * cdiv(items, d.cus);
         // planes are written and read once; small transfers reach about half the cache rate
         const double planes = sg.splits > 1 ? 2.0 * 4.0 * m * n2 * sg.splits / (0.5 * d.fabric_bw) : 0.0;
         // matrix-core time of each phase: items run one per CU, at the block GEMM's efficiency
@@ -356,7 +363,9 @@ void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1,
         static const int bms[] = {32, 64, 128, 256};
         static const int rasters2[] = {4, 2, 8, 1};   // the model does not tell these apart: measured order of preference
         for (int bm : bms) {
-            if (bm < 128 && M > bm) continue;                 // measured: several small row blocks lose to one larger one
+            // measured: two 64-row blocks beat one of 128 on the m = 128 shapes (half the row-operand
+            // bytes per item, half the planes); more, or smaller, blocks lose
+            if (bm < 128 && M > (bm == 64 ? 128 : bm)) continue;
             if (bm > 32 && M <= bm / 2) continue;             // more than half a block of padding
             // 128 / 64 / 32: register-staged loop with that slice width; -128 / -64: LDS-direct loop
             static const int slices[] = {128, 64, 32, -128, -64};

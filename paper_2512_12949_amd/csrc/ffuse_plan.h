@@ -46,6 +46,9 @@ struct TwoPhaseGeometry {
 };
 // most hidden-dimension ranges the chooser considers for an M x N2 output (bounds the workspace)
 int two_phase_max_splits(int64_t M, int64_t N2);
+// Weights far larger than the 256 MB memory-side cache (above 512 MB): the two-phase kernel streams
+// them with the non-temporal hint (row blocks below 256)
+bool weights_streamed(int dtype, int gated, int64_t K, int64_t N1, int64_t N2);
 bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, int64_t N2, TwoPhaseGeometry* out);
 
 bool fused_reduce_tile_ok(int gated, int bm, int bh);
