@@ -117,3 +117,37 @@ def test_plan_table_set_save_load_round_trip(tmp_path):
     with pytest.raises(ff.FfuseError):
         ff.ffuse_plan_table_load(tmp_path / "missing.txt")
     ff.ffuse_plan_table_clear()
+
+
+def test_ranked_plans_are_valid_sorted_and_fit_the_workspace_bound():
+    """Host logic of the chooser (Sec. 4.3): everything it enumerates passes the model's own
+    validity check, comes back sorted by predicted time, starts with what ffuse_choose_plan
+    returns, and -- for the two-phase family, whose workspace depends on the plan -- fits what
+    ffuse_workspace_bytes promises."""
+    for (M, K, N1, N2, gated) in [(1, 4096, 16384, 4096, False), (16, 8192, 28672, 8192, True), (100, 4096, 11008, 4096, True),
+                                  (128, 2048, 8192, 2048, False), (300, 1024, 4096, 1024, False), (2048, 4096, 11008, 4096, True),
+                                  (4096, 4096, 16384, 4096, False)]:
+        ranked = ff.ffuse_rank_plans(ff.DT_BF16, 2, gated, M, K, N1, N2, 1024)
+        assert ranked, (M, K, N1, N2)
+        times = [t for _, t in ranked]
+        assert times == sorted(times)
+        assert ranked[0][0].as_dict() == ff.ffuse_choose_plan(ff.DT_BF16, 2, gated, M, K, N1, N2).as_dict()
+        bound = ff.ffuse_workspace_bytes(ff.DT_BF16, gated, M, K, N1, N2, False)
+        for p, t in ranked:
+            tr = ff.ffuse_traffic_model(p, ff.DT_BF16, gated, M, K, N1, N2).as_dict()   # raises on an invalid plan
+            assert tr["feasible"] and t > 0
+            if p.family == ff.FAMILY_TWOPHASE:
+                r = lambda v: (v + 255) // 256 * 256
+                need = (r(4 * M * N2 * p.splits) if p.splits > 1 else 0) + r(2 * M * N1) + 1024
+                assert need <= bound, p.as_dict()
+
+
+def test_streamed_weights_get_one_row_block():
+    """Weights far larger than the memory-side cache are streamed with the non-temporal hint and
+    are not kept for a second row block: below 256 rows per block the chooser must then cover
+    all rows with one block (decode shapes), while cache-resident shapes may use two 64-row blocks."""
+    for M in (16, 33, 64, 100, 128):
+        p = ff.ffuse_choose_plan(ff.DT_BF16, 3, True, M, 8192, 28672, 8192)
+        assert p.family == ff.FAMILY_TWOPHASE and (p.bm >= M or p.bm == 256), (M, p.as_dict())
+    p = ff.ffuse_choose_plan(ff.DT_BF16, 2, False, 128, 2048, 8192, 2048)
+    assert p.family == ff.FAMILY_TWOPHASE and p.bm in (64, 128)
