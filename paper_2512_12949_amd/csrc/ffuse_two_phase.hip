@@ -24,7 +24,7 @@
 // Work items are dealt to workgroups XCD by XCD (blockIdx % 8 is the XCD): the items in
 // flight on one XCD form a patch of `raster` row blocks x consecutive slices, so that a
 // weight slice is fetched into that XCD's L2 once for all the row blocks of the patch.
-#include "ffuse_gemm1.h"
+#include "ffuse_gemm2.h"
 #include "ffuse_launch.h"
 #include <cstdlib>
 
@@ -69,36 +69,36 @@ template <typename T, bool GATED, int BH1_, bool DEEP_> struct TwoPhaseGemms<T, 
 // phase: more bytes in flight per workgroup than the register-staged loop can hold
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 128, true> {
     static constexpr int BH1 = 128;
-    template <bool NT> using G1 = DeepGemm<T, GATED, 128, 128, 2, 2, GATED ? 4 : 8, NT>;
-    template <bool NT> using G2 = DeepGemm<T, false, 128, 256, 2, 2, 4, NT>;
+    template <bool NT> using G1 = WideGemm<T, GATED, 128, 128, 2, 2, GATED ? 4 : 8, NT>;
+    template <bool NT> using G2 = WideGemm<T, false, 128, 256, 2, 2, 4, NT>;
     static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 64, true> {
     static constexpr int BH1 = 64;
-    template <bool NT> using G1 = DeepGemm<T, GATED, 128, 64, 2, 2, 8, NT>;
-    template <bool NT> using G2 = DeepGemm<T, false, 128, 256, 2, 2, 4, NT>;
+    template <bool NT> using G1 = WideGemm<T, GATED, 128, 64, 2, 2, 8, NT>;
+    template <bool NT> using G2 = WideGemm<T, false, 128, 256, 2, 2, 4, NT>;
     static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 64, true> {
     static constexpr int BH1 = 64;
-    template <bool NT> using G1 = DeepGemm<T, GATED, 64, 64, 2, 2, 8, NT>;
-    template <bool NT> using G2 = DeepGemm<T, false, 64, 256, 2, 2, 4, NT>;
+    template <bool NT> using G1 = WideGemm<T, GATED, 64, 64, 2, 2, 8, NT>;
+    template <bool NT> using G2 = WideGemm<T, false, 64, 256, 2, 2, 4, NT>;
     static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 32, false, 128, true> {
     static constexpr int BH1 = 128;
-    template <bool NT> using G1 = DeepGemm<T, GATED, 32, 128, 1, 4, 8, NT>;   // (a sixteen-stage ring measured no faster)
-    template <bool NT> using G2 = DeepGemm<T, false, 32, 256, 1, 4, 8, NT>;
+    template <bool NT> using G1 = WideGemm<T, GATED, 32, 128, 1, 4, 8, NT>;   // (a sixteen-stage ring measured no faster)
+    template <bool NT> using G2 = WideGemm<T, false, 32, 256, 1, 4, 8, NT>;
     static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 128, true> {
     static constexpr int BH1 = 128;
-    template <bool NT> using G1 = DeepGemm<T, GATED, 64, 128, 2, 2, GATED ? 4 : 8, NT>;
-    template <bool NT> using G2 = DeepGemm<T, false, 64, 256, 2, 2, 4, NT>;
+    template <bool NT> using G1 = WideGemm<T, GATED, 64, 128, 2, 2, GATED ? 4 : 8, NT>;
+    template <bool NT> using G2 = WideGemm<T, false, 64, 256, 2, 2, 4, NT>;
     static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
 };
