@@ -57,8 +57,12 @@ struct WideGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
 
     struct Ctx {
         __amdgpu_buffer_rsrc_t rx, rw[G];
-        uint32_t xoff[XI];      // global byte offset of this lane's A chunk, per instruction of an EVEN step, at k = 0
-        uint32_t xk[XI];        // k of that chunk within the super-stage
+        // this lane's A chunk in the wave's first instruction of an EVEN step: global byte offset at k = 0
+        // and k within the super-stage.  Instruction j is 8 j rows further down, and its rows' swizzle
+        // key differs by 4 when j is odd: chunk ^ 4, i.e. k ^ 32 and the offset +- 64 bytes (xflip).
+        uint32_t xoff, xk;
+        int32_t xflip;
+        uint32_t xstep;         // bytes between the rows of consecutive instructions (8 rows)
         uint32_t xhalf;         // added on odd steps: BM / 2 rows further down
         uint32_t boff[BI];
         uint32_t abase, brow;
@@ -74,16 +78,15 @@ struct WideGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         c.KX = kx;
         c.abase = base_bytes;
         c.xhalf = (uint32_t)(BM / 2) * lda * 2u;
-#pragma unroll
-        for (int j = 0; j < XI; ++j) {
-            // instruction q of a super-stage fills rows 8q .. 8q + 7: lane i -> row 8q + (i >> 3), slot i & 7,
-            // which holds chunk slot ^ ((row >> 1) & 7).  (Rows BM / 2 further down have the same key.)
-            const uint32_t q = wave * XI + j;
-            const uint32_t row = 8u * q + (lane >> 3);
-            const uint32_t chunk = (lane & 7u) ^ ((row >> 1) & 7u);
-            c.xk[j] = 8u * chunk;
-            c.xoff[j] = ((row0 + row) * lda + 8u * chunk) * 2u;
-        }
+        c.xstep = 8u * lda * 2u;
+        // instruction q of a super-stage fills rows 8q .. 8q + 7: lane i -> row 8q + (i >> 3), slot i & 7,
+        // which holds chunk slot ^ ((row >> 1) & 7).  (Rows BM / 2 further down have the same key.)
+        const uint32_t q = wave * XI;
+        const uint32_t row = 8u * q + (lane >> 3);
+        const uint32_t chunk = (lane & 7u) ^ ((row >> 1) & 7u);
+        c.xk = 8u * chunk;
+        c.xoff = ((row0 + row) * lda + 8u * chunk) * 2u;
+        c.xflip = (chunk & 4u) ? -64 : 64;
     }
     static __device__ __forceinline__ void init_b(Ctx& c, const void* B, const void* B3, uint32_t b_bytes,
                                                   uint32_t ldb, uint32_t ncols, uint32_t n0, int tid) {
@@ -139,9 +142,11 @@ struct WideGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     static __device__ __forceinline__ void issue_one(const Ctx& c, const Load& l, int xlim, int i) {
         if (i < XI) {
             if (SMALL_A && l.par != 0) return;
-            const bool ok = (l.kx + (int)c.xk[i]) < xlim && c.abase != kOob;
+            const uint32_t xk = (i & 1) ? (c.xk ^ 32u) : c.xk;
+            const bool ok = (l.kx + (int)xk) < xlim && c.abase != kOob;
             const uint32_t half = SMALL_A ? 0u : (uint32_t)l.par;
-            lds_dma16(c.rx, ok ? c.xoff[i] + half * c.xhalf + c.abase + (uint32_t)l.kx * 2u : kOob,
+            const uint32_t xo = c.xoff + (uint32_t)i * c.xstep + ((i & 1) ? (uint32_t)c.xflip : 0u);
+            lds_dma16(c.rx, ok ? xo + half * c.xhalf + c.abase + (uint32_t)l.kx * 2u : kOob,
                       l.sa + c.lds_a + half * (uint32_t)(QH * 1024) + (uint32_t)i * 1024u);
         } else {
             const int which = (i - XI) / BI, j = (i - XI) % BI;
