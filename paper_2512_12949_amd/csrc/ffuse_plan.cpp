@@ -135,17 +135,19 @@ bool fused_reduce_tile_ok(int gated, int bm, int bh) {
 // more of the loop is LDS reads rather than matrix instructions.  The 256 x 256 tile runs at
 // the chip's power limit; smaller tiles run at a higher clock but stay LDS-bound.
 //     wave tile    r     LDS-direct loop   register-staged loop
-//     128 x 128    1     0.48              --
-//      64 x 128    1.5   0.40              0.40
-//      64 x 64     2     0.31              0.275
-//      64 x 32     3     0.20              0.156
+//     128 x 128    1     0.51              --
+//      64 x 128    1.5   0.46              0.40
+//      64 x 64     2     0.36              0.275
+//      64 x 32     3     0.27              0.156
+// (LDS-direct below 256 rows: the loop that loads the row operand in whole cache lines; with
+// half lines it measured 0.40 / 0.31 / 0.20)
 // 1 / efficiency is interpolated linearly in r (and extrapolated beyond 3).
 static double block_gemm_efficiency(double rows, double cols, bool lds_direct) {
     const double wr = rows >= 128.0 ? rows / 2.0 : rows, wc = rows >= 128.0 ? cols / 2.0 : cols / 4.0;
     const double r = 64.0 * (1.0 / wr + 1.0 / wc);
     static const double rs[4] = {1.0, 1.5, 2.0, 3.0};
-    static const double inv_direct[4] = {1.0 / 0.48, 1.0 / 0.40, 1.0 / 0.31, 1.0 / 0.20};
-    static const double inv_staged[4] = {1.0 / 0.48, 1.0 / 0.40, 1.0 / 0.275, 1.0 / 0.156};
+    static const double inv_direct[4] = {1.0 / 0.51, 1.0 / 0.46, 1.0 / 0.36, 1.0 / 0.27};
+    static const double inv_staged[4] = {1.0 / 0.51, 1.0 / 0.40, 1.0 / 0.275, 1.0 / 0.156};
     const double* inv = lds_direct ? inv_direct : inv_staged;
     if (r <= rs[0]) return 1.0 / inv[0];
     int i = 0;
@@ -316,8 +318,14 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         // for the item's tile shape
         const double f1 = d.mfma_flops * block_gemm_efficiency(sg.bm, g * bh1, sg.bk == 32 || sg.bm == 256) / d.cus;
         const double f2 = d.mfma_flops * block_gemm_efficiency(sg.bm, 256.0, sg.bk == 32 || sg.bm == 256) / d.cus;
-        const double m1 = 2.0 * sg.bm * bh1 * g * k / f1 * cdiv(items1, d.cus);
-        const double m2 = 2.0 * sg.bm * 256.0 * sg.ksplit / f2 * cdiv(items, d.cus);
+        // items are dealt statically, one per CU and round; a last, partly filled round is cheaper than a
+        // full one (fewer CUs share the power budget and the L2: its items run faster) -- fitted exponent
+        const auto rounds = [&](double n) {
+            const double full = std::floor(n / d.cus), frac = n / d.cus - full;
+            return full + (frac > 0.0 ? std::pow(frac, 0.6) : 0.0);
+        };
+        const double m1 = 2.0 * sg.bm * bh1 * g * k / f1 * rounds(items1);
+        const double m2 = 2.0 * sg.bm * 256.0 * sg.ksplit / f2 * rounds(items);
         t->workgroups = d.cus;
         t->fabric_bytes = b1 + b2 + re1 + re2;
         t->t_hbm = t1 + t2;
