@@ -183,6 +183,13 @@ int ffuse_traffic_model(const ffuse_plan_t* plan, int dtype, int gated, int64_t 
 /* Forces every later fused call onto *plan (NULL: back to the chooser).  Also settable with
  * the environment variable FFUSE_FORCE_PLAN="family,bm,bh,bn2,bk,splits,h_level,raster,producers,ring,coherent". */
 int ffuse_force_plan(const ffuse_plan_t* plan);
+/* Other environment variables, read by the fused and unfused calls:
+ *   FFUSE_NT=0|1   two-phase family, row blocks below 256: never / always stream the weights with the
+ *                  non-temporal load hint.  Default: only when the weights exceed 512 MB -- far more than
+ *                  the 256 MB memory-side cache can keep from one call to the next.  A caller that cycles
+ *                  through many layers' weights may want 1 for smaller layers too.
+ *   FFUSE_LOG=1    (read once) per-launch diagnostics on stderr from ffuse_sync_status.
+ *   FFUSE_COOPERATIVE_LAUNCH=1  launch the persistent kernels with the runtime's cooperative launch. */
 /* Plan used by the most recent fused call of this process. */
 int ffuse_last_plan(ffuse_plan_t* out);
 /* Blocks until `stream` is idle, then reports whether the most recent two-phase or
