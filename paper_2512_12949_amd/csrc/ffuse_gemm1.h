@@ -37,11 +37,10 @@ namespace ffuse {
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-// NS_: stages in the ring (a power of two, 4 to 16): loads run NS_ - 1 stages ahead.  Four keeps a
-// 256 x 256 tile fed; eight is for small tiles in the weight-streaming regime, where the
-// bytes a workgroup keeps in flight set the rate at which it can pull weights.
-// NT_: the weight tiles are loaded with the non-temporal hint (see buf_load16_nt)
-template <typename T, bool GATED, int BM, int BH, int WM, int WN, int NS_ = 4, bool NT_ = false>
+// NS_: stages in the ring (a power of two): loads run NS_ - 1 stages ahead.  Four keeps a 256 x 256
+// tile fed.  (Row blocks below 256 rows use WideGemm, ffuse_gemm2.h, which loads the row operand
+// in whole cache lines.)
+template <typename T, bool GATED, int BM, int BH, int WM, int WN, int NS_ = 4>
 struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     typedef FirstGemm<T, GATED, BM, BH, WM, WN> Base;
     typedef typename Base::vec8 vec8;
@@ -52,16 +51,13 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     // the same bank, so each of the four gets its own key; rows of 128 bytes alternate
     // between two banks already, so rows k and k + 2 need different keys.
     static __device__ __forceinline__ uint32_t bkey(uint32_t k) { return BH == 64 ? (k & 2u) : ((k & 3u) << 1); }
-    static_assert(BM == 32 || BM % 64 == 0, "every wave issues the same number of loads");
-    // BM = 32: the A stage is 2 KB, half a load instruction per wave -- every wave issues one
-    // with its upper 32 lanes switched off (8 rows each)
-    static constexpr bool HALF_A = BM == 32;
+    static_assert(BM % 64 == 0, "every wave issues the same number of whole load instructions");
     static constexpr int NS = NS_;                     // stages in the ring
     static constexpr int XB = BM * 64;                 // bytes of one A stage
     static constexpr int WB = BH * 64;                 // bytes of one B stage (one matrix)
     static constexpr int STAGE = XB + G * WB;
     static constexpr int LDS_BYTES = NS * STAGE;
-    static constexpr int XI = HALF_A ? 1 : BM / 64;    // A load instructions per wave per stage
+    static constexpr int XI = BM / 64;                 // A load instructions per wave per stage
     static constexpr int ROWB = BH * 2;                // bytes of one B row in LDS
     static constexpr int RPI = 1024 / ROWB;            // B rows per load instruction
     static constexpr int BI = 32 / RPI / 4;            // B load instructions per wave per matrix
@@ -81,7 +77,6 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         uint32_t lds_a, lds_b;  // uniform LDS byte offsets of this wave's first A / B instruction
         uint32_t rdx[MT];       // LDS read offsets: A fragments (sub-step 0)
         uint32_t rdw[HT];       //                   B fragments (sub-step 0, first half)
-        bool a_lane;            // this lane takes part in A loads (all lanes unless HALF_A)
     };
 
     static __device__ __forceinline__ void init_a(Ctx& c, const void* A, uint32_t a_bytes, uint32_t base_bytes,
@@ -93,10 +88,9 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         // lane i of an instruction fills slot i & 3 of the row (i >> 2) rows below the
         // instruction's first: the chunk that lives there is slot ^ ((row >> 2) & 3), which is
         // the same for every instruction of a wave (their first rows are 16 apart)
-        const uint32_t first = HALF_A ? (uint32_t)wave * 8u : (uint32_t)(wave * XI) * 16u;
+        const uint32_t first = (uint32_t)(wave * XI) * 16u;
         const uint32_t chunk = (lane & 3) ^ (((first + (lane >> 2)) >> 2) & 3u);
         c.xk = 8u * chunk;
-        c.a_lane = !HALF_A || lane < 32;
 #pragma unroll
         for (int j = 0; j < XI; ++j) {
             const uint32_t row = first + (uint32_t)j * 16u + (lane >> 2);
@@ -122,7 +116,7 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // uniform: feeds M0
         const int wm = wave % WM, wn = wave / WM;
         const uint32_t x = lane & 31, h = lane >> 5;
-        c.lds_a = HALF_A ? (uint32_t)wave * 512u : (uint32_t)(wave * XI) * 1024u;
+        c.lds_a = (uint32_t)(wave * XI) * 1024u;
         c.lds_b = XB + (uint32_t)(wave * BI) * 1024u;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -145,10 +139,6 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         asm volatile("s_mov_b32 m0, %1\n\tbuffer_load_dwordx4 %0, %2, 0 offen lds"
                      :: "v"(voff), "s"(lds), "s"(r) : "memory", "m0");
     }
-    static __device__ __forceinline__ void lds_dma16_nt(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t lds) {
-        asm volatile("s_mov_b32 m0, %1\n\tbuffer_load_dwordx4 %0, %2, 0 offen nt lds"
-                     :: "v"(voff), "s"(lds), "s"(r) : "memory", "m0");
-    }
     // load instruction i of the step whose A columns start at kx and whose B rows start at kw.
     // A chunks at or past column xlim, and everything when `valid` is false, load nothing from
     // memory (out-of-range offsets: LDS receives zeros) -- the instruction is issued all the
@@ -156,16 +146,14 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
     static __device__ __forceinline__ void issue_one(char* stage, const Ctx& c, int kx, int kw, int xlim, bool valid, int i) {
         if (i < XI) {
             const bool ok = valid && (kx + (int)c.xk) < xlim && c.abase != kOob;
-            if (!HALF_A || c.a_lane)
-                lds_dma16(c.rx, ok ? c.xoff[i] + c.abase + (uint32_t)kx * 2u : kOob,
+            lds_dma16(c.rx, ok ? c.xoff[i] + c.abase + (uint32_t)kx * 2u : kOob,
                           (uint32_t)(uintptr_t)stage + c.lds_a + (uint32_t)i * 1024u);
         } else {
             const int which = (i - XI) / BI, j = (i - XI) % BI;
             const uint32_t off = c.boff[j];
             const uint32_t vo = (off == kOob || !valid) ? kOob : off + (uint32_t)kw * c.brow;
             const uint32_t la = (uint32_t)(uintptr_t)stage + c.lds_b + (uint32_t)which * WB + (uint32_t)j * 1024u;
-            if (NT_) lds_dma16_nt(c.rw[which], vo, la);
-            else lds_dma16(c.rw[which], vo, la);
+            lds_dma16(c.rw[which], vo, la);
         }
     }
     static __device__ __forceinline__ void issue(char* stage, const Ctx& c, int kx, int kw, int xlim, bool valid) {

@@ -4,7 +4,8 @@
 //
 //   phase 1: work items (row block of BM rows, hidden slice of BH1 columns); each computes,
 //            with K complete, H[rows, slice] = act(X W1[:, slice]) [.* X W3[:, slice]];
-//   barrier : every workgroup has published its tiles (agent-scope release / acquire, once);
+//   barrier : every workgroup has published its tiles (write-through stores, counted arrivals,
+//            one agent-scope acquire);
 //   phase 2: work items (row block, 256 output columns, one of `splits` ranges of the hidden
 //            dimension); each multiplies its part of H with its W2 block.  With splits == 1
 //            the tile goes straight to Y; otherwise every range stores its partial tile into
@@ -17,9 +18,9 @@
 // the hidden dimension all the way (the reduce family) would cost 4 M N2 (N1/128) bytes of
 // atomics: more than the weights themselves at M = 64.
 //
-// Rows are blocked by BM = 32, 64, 128 (all four waves along the columns, register-staged
-// block GEMM with two stages in flight: the weight-streaming regime) or 256 (2 x 2 waves,
-// LDS-direct block GEMM: the compute-bound regime).
+// Rows are blocked by BM = 32, 64, 128 (the weight-streaming and mid-M regime: the LDS-direct
+// block GEMM with whole-line row-operand loads, WideGemm, or the register-staged FirstGemm with
+// two stages in flight) or 256 (2 x 2 waves, DeepGemm: the compute-bound regime).
 //
 // Work items are dealt to workgroups XCD by XCD (blockIdx % 8 is the XCD): the items in
 // flight on one XCD form a patch of `raster` row blocks x consecutive slices, so that a
@@ -47,7 +48,7 @@ __device__ __forceinline__ bool map_item(int MB, int S, int raster, int xcd, int
 }
 
 // BH1: hidden slice of a phase-1 work item.  With few rows the first phase is a weight stream
-// that a single workgroup can only pull at ~20 GB/s, so it wants at least as many items as
+// that a single workgroup can only pull at 20-40 GB/s, so it wants at least as many items as
 // there are CUs: 128-column slices (four waves along the columns), 64 (2 x 2 waves) or 32
 // (four waves along the rows) give N1/128, N1/64 or N1/32 of them.
 template <typename T, bool GATED, int BM, bool CONV, int BH1_, bool DEEP_> struct TwoPhaseGemms {
@@ -65,8 +66,9 @@ template <typename T, bool GATED, int BH1_, bool DEEP_> struct TwoPhaseGemms<T, 
     static constexpr bool HAS_NT = false;   // 256-row blocks re-use their weight tiles through L2
     static constexpr bool DEEP = true;
 };
-// 64 / 128 rows with the LDS-direct block GEMM (2 x 2 waves) and a deeper ring in the first
-// phase: more bytes in flight per workgroup than the register-staged loop can hold
+// 32 / 64 / 128 rows with the LDS-direct block GEMM and a deeper ring in the first phase: more
+// bytes in flight per workgroup than the register-staged loop can hold, the row operand in
+// whole cache lines
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 128, true> {
     static constexpr int BH1 = 128;
     template <bool NT> using G1 = WideGemm<T, GATED, 128, 128, 2, 2, GATED ? 4 : 8, NT>;
