@@ -261,3 +261,30 @@ def test_tune_fills_the_plan_table_for_the_bin():
     other, other_ms = ff.ffuse_plan_lookup(ff.DT_BF16, w.act, False, 64, 264, 1304, 520)
     assert other_ms == 0.0 and other.as_dict() == ff.ffuse_choose_plan(ff.DT_BF16, w.act, False, 64, 264, 1304, 520).as_dict()
     ff.ffuse_plan_table_clear()
+
+
+def test_random_shapes_and_plans(monkeypatch):
+    """Seeded random walk over valid shapes (ragged everything), operand types, activations and
+    forced two-phase plans (row block, slice, block GEMM, hidden ranges, raster, weight-load
+    hint), each against the oracle; the chooser's plan and the two-launch path ride along."""
+    import random
+    rng = random.Random(20251212)
+    for n in range(40):
+        M = rng.choice([1, 3, 16, 31, 33, 64, 65, 100, 128, 129, 200, 256, 300, 513, 700])
+        K, N1, N2 = 8 * rng.randint(1, 80), 8 * rng.randint(1, 260), 8 * rng.randint(1, 90)
+        gated, dtype, act = rng.random() < 0.5, rng.choice(["bf16", "f16"]), rng.choice([ACT_IDENTITY, ACT_RELU, ACT_GELU_TANH, ACT_SILU])
+        w, host, dev = _case("random", M, K, N1, N2, dtype, act, gated, cfg_id=900 + n)
+        ref = gu.oracle_rows(w, host)
+        bm = rng.choice([32, 64, 128, 256])
+        if bm < 128 and M > 4 * bm:
+            bm = 128
+        bh = (128 if gated else 256) if bm == 256 else (128 if bm < 64 else rng.choice([128, 64]))
+        plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=bh, bk=rng.choice([32, 64]), splits=rng.choice([1, 2, 3, 5, 8]),
+                            raster=rng.choice([1, 2, 4]))
+        monkeypatch.setenv("FFUSE_NT", rng.choice(["0", "1"]))
+        what = f"random {n}: {(M, K, N1, N2)} gated={gated} {dtype} act={act} plan={(plan.bm, plan.bh, plan.bk, plan.splits, plan.raster)}"
+        print(what, flush=True)
+        gu.check(gu.run(w, dev, plan=plan), ref, dtype, what=what)
+        gu.check(gu.run(w, dev), ref, dtype, what=what + " (chooser)")
+        gu.check(gu.run(w, dev, unfused=True), ref, dtype, what=what + " (two launches)")
+    monkeypatch.delenv("FFUSE_NT")
