@@ -130,14 +130,22 @@ def main():
             if w.gated:
                 h = h * torch.matmul(dev["X"], dev["W3"])
             return torch.matmul(h, dev["W2"])
+        # generous to the baseline: long warm-up (its first dozen calls run up to 20 % slow), then the
+        # best of three event-timed batches
+        for _ in range(10):
+            vendor_step()
+        torch.cuda.synchronize()
+        nv = max(3, args.steps // 2)
+        best = float("inf")
         for _ in range(3):
-            vendor_step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(max(3, args.steps // 2)):
-            vendor_step()
-        torch.cuda.synchronize()
-        t_vendor = (time.perf_counter() - t0) / max(3, args.steps // 2)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(nv):
+                vendor_step()
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 1e-3 / nv)
+        t_vendor = best
 
     flops = float(w.flops())
     value = flops / t_fused * 1e-12
