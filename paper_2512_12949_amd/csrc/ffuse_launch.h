@@ -48,8 +48,8 @@ struct ExchangeArgs {
     uint64_t* stats;  // nullptr, or 4 words per workgroup: role, total ticks, waiting ticks, items
 };
 
-// two-phase family's flag words (kTwoPhaseFlagBytes in all): 0 = groups arrived at the barrier, 1 = workgroups that have
-// left, 2 = error; kTwoPhaseGroupWord * (1 + g) = arrivals of group g (a cache line apart)
+// two-phase family's flag words (kTwoPhaseFlagBytes in all): 1 = workgroups that have left, 2 = error;
+// kTwoPhaseGroupWord * (1 + g) = arrivals at the barrier of group g (a cache line apart)
 static constexpr int kTwoPhaseGroupWord = 16;
 
 struct TwoPhaseArgs {
