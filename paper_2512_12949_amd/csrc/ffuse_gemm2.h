@@ -222,6 +222,20 @@ struct WideGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         }
     }
 
+    // Issues, ahead of time, this wave's B loads of the first NS - 1 stages of the stream [kbegin, kend): the
+    // data lands where a later run() over the same stream loads it again, which then finds the lines in L2
+    // instead of in DRAM.  The caller must own the LDS (nobody reads or loads it meanwhile).
+    static __device__ __forceinline__ void prefetch_b(char* smem, const Ctx& c, int kbegin, int kend) {
+        const int KT = (kend - kbegin + 31) / 32;
+        const uint32_t b_lds = (uint32_t)(uintptr_t)smem + (uint32_t)A_RING;
+#pragma unroll
+        for (int sb = 0; sb < NS - 1; ++sb) {
+            const Load l{0u, b_lds + (uint32_t)(sb * BST), 0, kbegin + 32 * sb, 0, sb < KT};
+#pragma unroll
+            for (int i = XI; i < NLOAD; ++i) issue_one(c, l, 0, i);
+        }
+    }
+
     static __device__ __forceinline__ void run(char* smem, const Ctx& c, int kbegin, int kend, f32x16 (&acc)[HT][MT],
                                                f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1], int tid) {
         (void)tid;

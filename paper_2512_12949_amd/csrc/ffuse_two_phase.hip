@@ -58,6 +58,7 @@ template <typename T, bool GATED, int BM, bool CONV, int BH1_, bool DEEP_> struc
     template <bool NT> using G2 = FirstGemm<T, false, BM, 256, 1, 4, false, NT>;   // phase 2: H * W2
     static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = false;
+    static constexpr bool PREFETCH = false;
 };
 template <typename T, bool GATED, int BH1_, bool DEEP_> struct TwoPhaseGemms<T, GATED, 256, false, BH1_, DEEP_> {
     static constexpr int BH1 = GATED ? 128 : 256;
@@ -65,6 +66,7 @@ template <typename T, bool GATED, int BH1_, bool DEEP_> struct TwoPhaseGemms<T, 
     template <bool NT> using G2 = DeepGemm<T, false, 256, 256, 2, 2>;
     static constexpr bool HAS_NT = false;   // 256-row blocks re-use their weight tiles through L2
     static constexpr bool DEEP = true;
+    static constexpr bool PREFETCH = false;
 };
 // 32 / 64 / 128 rows with the LDS-direct block GEMM and a deeper ring in the first phase: more
 // bytes in flight per workgroup than the register-staged loop can hold, the row operand in
@@ -75,6 +77,7 @@ template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 128
     template <bool NT> using G2 = WideGemm<T, false, 128, 256, 2, 2, 4, NT>;
     static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
+    static constexpr bool PREFETCH = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 64, true> {
     static constexpr int BH1 = 64;
@@ -82,6 +85,7 @@ template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 128, false, 64,
     template <bool NT> using G2 = WideGemm<T, false, 128, 256, 2, 2, 4, NT>;
     static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
+    static constexpr bool PREFETCH = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 64, true> {
     static constexpr int BH1 = 64;
@@ -89,6 +93,7 @@ template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 64, 
     template <bool NT> using G2 = WideGemm<T, false, 64, 256, 2, 2, 4, NT>;
     static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
+    static constexpr bool PREFETCH = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 32, false, 128, true> {
     static constexpr int BH1 = 128;
@@ -96,6 +101,7 @@ template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 32, false, 128,
     template <bool NT> using G2 = WideGemm<T, false, 32, 256, 1, 4, 8, NT>;
     static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
+    static constexpr bool PREFETCH = true;
 };
 template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 128, true> {
     static constexpr int BH1 = 128;
@@ -103,6 +109,7 @@ template <typename T, bool GATED> struct TwoPhaseGemms<T, GATED, 64, false, 128,
     template <bool NT> using G2 = WideGemm<T, false, 64, 256, 2, 2, 4, NT>;
     static constexpr bool HAS_NT = true;
     static constexpr bool DEEP = true;
+    static constexpr bool PREFETCH = true;
 };
 
 // Phase 1 for one workgroup: its share of the (row block, hidden slice) items.  G1 is the block
@@ -177,6 +184,24 @@ __device__ __forceinline__ void two_phase_second(const TwoPhaseArgs& a, char* sm
     }
 }
 
+// While a workgroup waits at the barrier, the weight tile of its first phase-2 item can already be on
+// its way: the first stages' loads are issued early (by the waves that do not poll), into the place
+// where phase 2 will load them again -- then from L2, not from DRAM.  Only for the block GEMM that has
+// the hook (row blocks below 256 in the LDS-direct loop).
+template <typename G2, int BM>
+__device__ __forceinline__ void two_phase_prefetch(const TwoPhaseArgs& a, char* smem, int tid, int xcd, int loc, int MB) {
+    constexpr int BH2 = 256;
+    const int NCB = (a.N2 + BH2 - 1) / BH2;
+    int rb, u;
+    if ((tid >> 6) == 0 || !map_item(MB, NCB * a.splits, a.raster, xcd, loc, rb, u)) return;
+    const int cb = u % NCB, sp = u / NCB;
+    const int k0 = sp * a.ksplit, k1 = min(a.N1, k0 + a.ksplit);
+    typename G2::Ctx c;
+    G2::init_lds(c, tid);
+    G2::init_b(c, a.W2, nullptr, (uint32_t)((uint64_t)a.N1 * a.N2 * 2), (uint32_t)a.N2, (uint32_t)a.N2, (uint32_t)cb * BH2, tid);
+    G2::prefetch_b(smem, c, k0, k1);
+}
+
 // CONV: the first product is a 3x3 convolution (rows = pixels of a channels-last image,
 // a.K = 9 * a.conv_ic); everything after the first product's loads is unchanged.
 // a.nt selects, per launch, the instantiations of the block GEMMs that stream the weights with
@@ -221,9 +246,16 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0 && !both) verdict = 1u;
+    if (tid == 0 && both)
+        __hip_atomic_fetch_add(a.flags + kTwoPhaseGroupWord * (1 + xcd), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if constexpr (TG::PREFETCH) {
+        if (both) {
+            if (TG::HAS_NT && a.nt) two_phase_prefetch<typename TG::template G2<true>, BM>(a, smem, tid, xcd, loc, MB);
+            else two_phase_prefetch<G2, BM>(a, smem, tid, xcd, loc, MB);
+        }
+    }
     if (tid == 0 && both) {
         uint32_t ok = 1;
-        __hip_atomic_fetch_add(a.flags + kTwoPhaseGroupWord * (1 + xcd), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         uint32_t spins = 0;
         for (;;) {
             uint32_t fewest = ~0u;
@@ -262,6 +294,7 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
         else two_phase_second<G2, TG::DEEP, BM>(a, smem, tid, xcd, loc, GX, MB);
     }
 
+    if constexpr (TG::PREFETCH) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (early loads of a phase 2 that did not run)
     if (a.stats && tid == 0) {
         uint64_t* p = a.stats + 4 * blockIdx.x;
         p[0] = t1 - t0; p[1] = t2 - t1; p[2] = wall_clock64() - t2; p[3] = c1 - c0;   // p[3]: core clocks of phase 1
