@@ -203,9 +203,11 @@ int ffuse_sync_status(void* stream);
  *      fixed ahead of time per range of M and looked up at run time; Algorithm 2: the
  *      analytical ranking is followed by profiling the top-k candidates on the device).
  *      ffuse_tune runs the `top_k` analytically best plans for this problem on `stream` with
- *      the caller's operands (one checked run, then `reps` timed ones each; Y is overwritten
- *      with a valid result every time), records the fastest for M's bin (M <= 16, then one bin
- *      per power of two) and returns it.  Later fused calls with the same dtype, gate, K, N1,
+ *      the caller's operands (one checked run each, then two passes of `reps` timed runs each,
+ *      the second pass in reverse order, a plan's time being the better of its two; Y is
+ *      overwritten with a valid result every time), records the fastest for M's bin (M <= 16,
+ *      then one bin per power of two) and returns it; near-ties go to the analytical order: a
+ *      plan ranked later has to be more than 1 % faster to win.  Later fused calls with the same dtype, gate, K, N1,
  *      N2 and an M of that bin use it when it is valid for their M and fits their workspace;
  *      otherwise, and for bins never tuned, the model's choice for the exact M is used (and
  *      remembered).  The registered workspace bounds which candidates can run.
