@@ -1,5 +1,5 @@
-"""Parity at the benchmark configurations' full sizes, in the launch configurations the
-benchmark times: the chooser's plan, and the plan the on-device tuning of the model's six
+"""Parity at the benchmark configurations' full sizes (and at the paper's own m = 128 shape
+tables), in the launch configurations the benchmark times: the chooser's plan, and the plan the on-device tuning of the model's six
 best candidates settles on (what bench.py runs by default).  The oracle computes a stratified row sample (first,
 last and seeded interior rows of every 256-row block; every output column), and the whole
 output is checked for finiteness and against the unfused path."""
@@ -51,3 +51,33 @@ def test_full_size(name):
     diff = float((Y.float() - Yu.float()).abs().max())
     print(f"[{name}] unfused rel err {relu:.3e}; fused vs unfused {diff / scale:.3e}", flush=True)
     assert diff <= 2 * gu.TOL[w.dtype] * scale
+
+
+TABLE_NAMES = [f"G{i}" for i in range(1, 11)] + [f"S{i}" for i in range(1, 9)]
+
+
+@pytest.mark.parametrize("name", TABLE_NAMES)
+def test_paper_shape_tables(name):
+    """The paper's own shapes (Evaluation, tables of GEMM-chain and gated-FFN configurations, all
+    at m = 128) at full size, in the chooser's plan and in the two-launch comparison path; the
+    oracle computes a stratified row sample (every 32-row block's first and last row plus seeded
+    interior rows, every output column).  A second call with fewer rows (M = 100: the same bin
+    of the plan table, 65..128) is checked as well."""
+    w = inputs.WORKLOADS[name]
+    host = inputs.make(w)
+    dev = {k: gu.to_device(v, w.dtype) for k, v in host.items()}
+    rows = inputs.sample_rows(w.M, 32, 4, seed=w.cfg_id)
+    ref = gu.oracle_rows(w, host, rows)
+    Y = gu.run(w, dev)
+    plan = ff.ffuse_last_plan().as_dict()
+    rel = gu.check(Y, ref, w.dtype, rows=rows, what=f"{name} fused")
+    assert bool(torch.isfinite(Y.float()).all())
+    Yu = gu.run(w, dev, unfused=True)
+    relu = gu.check(Yu, ref, w.dtype, rows=rows, what=f"{name} two launches")
+    print(f"[{name}] {(w.M, w.K, w.N1, w.N2)} plan {plan} rel err {rel:.3e} (two launches {relu:.3e})", flush=True)
+    # fewer rows, same bin: rows are independent, so the first 100 rows of Y are the answer
+    dev100 = dict(dev)
+    dev100["X"] = dev["X"][:100].contiguous()
+    Y100 = gu.run(w, dev100)
+    keep = rows[rows < 100]
+    gu.check(Y100, ref[: len(keep)], w.dtype, rows=keep, what=f"{name} fused, 100 rows")
