@@ -119,18 +119,23 @@ __device__ __forceinline__ void lds_write16(char* smem, uint32_t off, u32x4 v) {
 
 // ---------------------------------------------------------------------------------------
 // Activations in fp32 (inputs are complete K-sums).  exp via v_exp_f32, 1/x via v_rcp_f32:
-// relative error ~1e-6, far below the 16-bit rounding that follows.
+// relative error ~1e-6, far below the 16-bit rounding that follows.  They run in the tile
+// epilogues with one wave per SIMD, where every instruction is exposed (a 256 x 256 tile's
+// epilogue is 256 values per lane), so they are written for instruction count.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ float sigmoid_fast(float z) {  // 1 / (1 + exp(-z))
     return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
 }
 template <int ACT> __device__ __forceinline__ float activate(float x) {
-    if (ACT == ACT_RELU) return fmaxf(x, 0.0f);
+    // median of (x, 0, +inf): one instruction (fmaxf is two: it quiets signalling NaNs first)
+    if (ACT == ACT_RELU) return __builtin_amdgcn_fmed3f(x, 0.0f, __builtin_inff());
     if (ACT == ACT_SILU) return x * sigmoid_fast(x);
     if (ACT == ACT_GELU_TANH) {
-        // 0.5 (1 + tanh z) = sigmoid(2 z),  z = sqrt(2/pi) (x + 0.044715 x^3)
-        const float z2 = 1.5957691216057308f * x * (1.0f + 0.044715f * x * x);
-        return x * sigmoid_fast(z2);
+        // 0.5 (1 + tanh z) = sigmoid(2 z),  z = sqrt(2/pi) (x + 0.044715 x^3); with the constants
+        // folded: x / (1 + 2^(x (A + B x^2))),  A = -2 sqrt(2/pi) log2(e),  B = 0.044715 A
+        const float t = x * x;
+        const float u = __builtin_fmaf(t, -0.10294323958f, -2.3022081983f);
+        return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * u));
     }
     return x;
 }
