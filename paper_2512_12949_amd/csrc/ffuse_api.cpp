@@ -461,14 +461,15 @@ int run_conv_chain(int dtype, const void* X, const void* W1, const void* W2, int
     if (g.forced && g.forced_plan.family == FFUSE_FAMILY_TWOPHASE) {
         plan = g.forced_plan;
         if (plan.bm == 0) plan.bm = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
-        plan.bh = 128; plan.bk = 64;   // the 3x3 loader exists for the register-staged loop with 128-column slices only
+        plan.bk = 64;                  // the 3x3 loader exists for the register-staged loop only
+        if (plan.bh != 64 && plan.bh != 32) plan.bh = 128;
         found = plan.bm <= 128 && ffuse::plan_valid(plan, dtype, 0, M, K, OC1, OC2);
         if (!found) return FFUSE_ERR_PLAN;
     } else {
         std::vector<ffuse::RankedPlan> ranked;
         ffuse::rank_plans(dtype, act, 0, M, K, OC1, OC2, &ranked);
         for (const auto& r : ranked)
-            if (r.plan.family == FFUSE_FAMILY_TWOPHASE && r.plan.bm <= 128 && r.plan.bh == 128 && r.plan.bk != 32 &&
+            if (r.plan.family == FFUSE_FAMILY_TWOPHASE && r.plan.bm <= 128 && r.plan.bk != 32 &&
                 ffuse::plan_workspace_bytes(r.plan, dtype, 0, M, K, OC1, OC2) <= g.ws_bytes) {
                 plan = r.plan;
                 found = true;

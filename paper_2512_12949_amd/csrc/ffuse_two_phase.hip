@@ -363,10 +363,18 @@ template <typename T, bool GATED> static const void* two_phase_fn(int bm, int bh
     return nullptr;
 }
 
-template <typename T> static const void* two_phase_conv_fn(int bm) {
-    if (bm == 32) return (const void*)fused_two_phase_kernel<T, false, 32, true>;
-    if (bm == 64) return (const void*)fused_two_phase_kernel<T, false, 64, true>;
-    if (bm == 128) return (const void*)fused_two_phase_kernel<T, false, 128, true>;
+template <typename T> static const void* two_phase_conv_fn(int bm, int bh1) {
+    if (bh1 == 128) {
+        if (bm == 32) return (const void*)fused_two_phase_kernel<T, false, 32, true>;
+        if (bm == 64) return (const void*)fused_two_phase_kernel<T, false, 64, true>;
+        if (bm == 128) return (const void*)fused_two_phase_kernel<T, false, 128, true>;
+    }
+    // narrow slices: the table's deepest layers have 256 / 512 hidden channels, two or four 128-column items
+    if (bh1 == 64) {
+        if (bm == 64) return (const void*)fused_two_phase_kernel<T, false, 64, true, 64>;
+        if (bm == 128) return (const void*)fused_two_phase_kernel<T, false, 128, true, 64>;
+    }
+    if (bh1 == 32 && bm == 128) return (const void*)fused_two_phase_kernel<T, false, 128, true, 32>;
     return nullptr;
 }
 
@@ -375,8 +383,8 @@ hipError_t launch_fused_two_phase(int dtype, const TwoPhaseArgs& a, int bm, int 
     const void* fn;
     if (a.conv_ic > 0) {
         // 3x3 first product: one tap per K step of 64, and the shifted addresses must fit 32 bits
-        if (g || bh1 != 128 || bk == 32 || a.conv_ic % 64 || a.K != 9 * a.conv_ic || a.conv_h < 1 || a.conv_w < 1) return hipErrorInvalidValue;
-        fn = dtype == 0 ? two_phase_conv_fn<__bf16>(bm) : two_phase_conv_fn<_Float16>(bm);
+        if (g || bk == 32 || a.conv_ic % 64 || a.K != 9 * a.conv_ic || a.conv_h < 1 || a.conv_w < 1) return hipErrorInvalidValue;
+        fn = dtype == 0 ? two_phase_conv_fn<__bf16>(bm, bh1) : two_phase_conv_fn<_Float16>(bm, bh1);
     } else {
         fn = dtype == 0 ? (g ? two_phase_fn<__bf16, true>(bm, bh1, bk) : two_phase_fn<__bf16, false>(bm, bh1, bk))
                         : (g ? two_phase_fn<_Float16, true>(bm, bh1, bk) : two_phase_fn<_Float16, false>(bm, bh1, bk));

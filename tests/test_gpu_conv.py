@@ -61,11 +61,13 @@ def test_ragged_3x3_chains(dtype, act):
         host = inputs.make_conv(w)
         ref = oracle.conv_chain(host["X"], host["W1"], host["W2"], act, bf16=(dtype == "bf16"))
         check(run_conv(w, host), ref, dtype, f"{dtype} {(B, H, W, IC, OC1, OC2)}")
-        for bm, splits in ((32, 2), (64, 1), (128, 3)):
+        # row blocks and hidden slices of the 3x3 loader's kernels (slices of 128, 64 and 32 channels)
+        for bm, bh, splits in ((32, 128, 2), (64, 128, 1), (128, 128, 3), (64, 64, 2), (128, 64, 1), (128, 32, 2)):
             if bm < 128 and B * H * W > bm:
                 continue
-            plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, splits=splits, raster=2)
-            check(run_conv(w, host, plan), ref, dtype, f"{dtype} {(B, H, W, IC, OC1, OC2)} bm={bm} splits={splits}")
+            plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=bh, splits=splits, raster=2)
+            check(run_conv(w, host, plan), ref, dtype, f"{dtype} {(B, H, W, IC, OC1, OC2)} bm={bm} bh={bh} splits={splits}")
+            assert ff.ffuse_last_plan().bh == bh
 
 
 def test_pointwise_chain_and_argument_errors():
