@@ -180,6 +180,13 @@ int ffuse_choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64
                       ffuse_plan_t* out);
 int ffuse_traffic_model(const ffuse_plan_t* plan, int dtype, int gated, int64_t M, int64_t K,
                         int64_t N1, int64_t N2, ffuse_traffic_t* out);
+/* Two-phase family, host logic only: 1 when, under *plan, every second-phase work item of each of the
+ * kernel's eight workgroup groups reads only tiles of the intermediate written by first-phase items of
+ * the same group -- the barrier between the phases then waits for the group's own workgroups only
+ * (Sec. 4.1: the synchronisation scope follows the data dependence) -- 0 when not, or a negative status
+ * (FFUSE_ERR_NULL, FFUSE_ERR_SHAPE, FFUSE_ERR_PLAN: not a valid two-phase plan for this problem). */
+int ffuse_plan_group_local(const ffuse_plan_t* plan, int dtype, int gated, int64_t M, int64_t K,
+                           int64_t N1, int64_t N2);
 /* Forces every later fused call onto *plan (NULL: back to the chooser).  Also settable with
  * the environment variable FFUSE_FORCE_PLAN="family,bm,bh,bn2,bk,splits,h_level,raster,producers,ring,coherent". */
 int ffuse_force_plan(const ffuse_plan_t* plan);
@@ -188,6 +195,8 @@ int ffuse_force_plan(const ffuse_plan_t* plan);
  *                  non-temporal load hint.  Default: only when the weights exceed 512 MB -- far more than
  *                  the 256 MB memory-side cache can keep from one call to the next.  A caller that cycles
  *                  through many layers' weights may want 1 for smaller layers too.
+ *   FFUSE_GROUP_BARRIER=0  the two-phase kernel's barrier always waits for every workgroup (default: only
+ *                  for the workgroup's own group where ffuse_plan_group_local says that suffices).
  *   FFUSE_LOG=1    (read once) per-launch diagnostics on stderr from ffuse_sync_status.
  *   FFUSE_COOPERATIVE_LAUNCH=1  launch the persistent kernels with the runtime's cooperative launch. */
 /* Plan used by the most recent fused call of this process. */

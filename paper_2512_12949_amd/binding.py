@@ -21,7 +21,7 @@ DTYPE_CODE = {"bf16": DT_BF16, "f16": DT_F16, "f32": DT_F32}
 EXPORTS = [
     "ffuse_ffn", "ffuse_ffn_f16", "ffuse_ffn_f32",
     "ffuse_ffn_unfused", "ffuse_ffn_unfused_f16", "ffuse_ffn_unfused_f32",
-    "ffuse_workspace_bytes", "ffuse_set_workspace", "ffuse_choose_plan", "ffuse_traffic_model",
+    "ffuse_workspace_bytes", "ffuse_set_workspace", "ffuse_choose_plan", "ffuse_traffic_model", "ffuse_plan_group_local",
     "ffuse_force_plan", "ffuse_last_plan", "ffuse_sync_status", "ffuse_profile_enable", "ffuse_profile_read",
     "ffuse_tune", "ffuse_plan_lookup", "ffuse_plan_table_clear", "ffuse_conv_chain", "ffuse_conv_chain_f16", "ffuse_rank_plans",
     "ffuse_plan_table_set", "ffuse_plan_table_save", "ffuse_plan_table_load",
@@ -78,6 +78,8 @@ def lib():
         L.ffuse_set_workspace.argtypes = [vp, ctypes.c_size_t, vp]
         L.ffuse_choose_plan.restype = ci
         L.ffuse_choose_plan.argtypes = [ci, ci, ci, i64, i64, i64, i64, ctypes.POINTER(Plan)]
+        L.ffuse_plan_group_local.restype = ci
+        L.ffuse_plan_group_local.argtypes = [ctypes.POINTER(Plan), ci, ci, i64, i64, i64, i64]
         L.ffuse_traffic_model.restype = ci
         L.ffuse_traffic_model.argtypes = [ctypes.POINTER(Plan), ci, ci, i64, i64, i64, i64, ctypes.POINTER(Traffic)]
         L.ffuse_force_plan.restype = ci
@@ -190,6 +192,13 @@ def ffuse_choose_plan(dtype, act, gated, M, K, N1, N2) -> Plan:
     _check(lib().ffuse_choose_plan(int(dtype), int(act), int(bool(gated)), M, K, N1, N2, ctypes.byref(p)),
            "ffuse_choose_plan")
     return p
+
+
+def ffuse_plan_group_local(plan: Plan, dtype, gated, M, K, N1, N2) -> bool:
+    rc = lib().ffuse_plan_group_local(ctypes.byref(plan), int(dtype), int(bool(gated)), M, K, N1, N2)
+    if rc < 0:
+        _check(rc, "ffuse_plan_group_local")
+    return bool(rc)
 
 
 def ffuse_traffic_model(plan: Plan, dtype, gated, M, K, N1, N2) -> Traffic:

@@ -169,6 +169,12 @@ int stream_weights(int dtype, int gated, int64_t K, int64_t N1, int64_t N2) {
     return ffuse::weights_streamed(dtype, gated, K, N1, N2) ? 1 : 0;
 }
 
+// FFUSE_GROUP_BARRIER=0: the barrier between the phases always waits for every workgroup; read per call
+bool group_barrier() {
+    const char* env = std::getenv("FFUSE_GROUP_BARRIER");
+    return !env || std::atoi(env) != 0;
+}
+
 // launches one validated plan; the caller holds the lock.  two_launches (two-phase family
 // only): each phase is a launch of its own and the kernel boundary replaces the barrier.
 int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act,
@@ -219,7 +225,8 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
         g.ws_zero = 0;      // planes and H overwrite the region the reduce family keeps at zero
         ffuse::TwoPhaseArgs s{X, W1, W3, W2, base + sg.ysum_bytes, Y, reinterpret_cast<float*>(base), flags,
                               M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, sg.raster, nullptr,
-                              g.conv_ic, g.conv_h, g.conv_w, stream_weights(dtype, gated, K, N1, N2), 3};
+                              g.conv_ic, g.conv_h, g.conv_w, stream_weights(dtype, gated, K, N1, N2),
+                              (group_barrier() && ffuse::two_phase_groups_independent(sg, M, N1, N2)) ? 1 : 0, 3};
         if (g.log && g.ws_bytes >= sg.ws_bytes + 65536) {
             s.stats = reinterpret_cast<uint64_t*>(base + sg.ws_bytes);
             g.small_stats = s.stats;
@@ -381,6 +388,17 @@ int ffuse_traffic_model(const ffuse_plan_t* plan, int dtype, int gated, int64_t 
     if (!ffuse::plan_valid(*plan, dtype, gated ? 1 : 0, M, K, N1, N2)) return FFUSE_ERR_PLAN;
     ffuse::traffic_model(*plan, dtype, gated ? 1 : 0, M, K, N1, N2, out);
     return FFUSE_OK;
+}
+
+int ffuse_plan_group_local(const ffuse_plan_t* plan, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
+    if (!plan) return FFUSE_ERR_NULL;
+    if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F16) return FFUSE_ERR_ACT;
+    if (M < 1 || K < 8 || N1 < 8 || N2 < 8) return FFUSE_ERR_SHAPE;
+    ffuse::TwoPhaseGeometry sg;
+    if (plan->family != FFUSE_FAMILY_TWOPHASE || !ffuse::plan_valid(*plan, dtype, gated ? 1 : 0, M, K, N1, N2) ||
+        !ffuse::two_phase_geometry(*plan, gated ? 1 : 0, M, N1, N2, &sg))
+        return FFUSE_ERR_PLAN;
+    return ffuse::two_phase_groups_independent(sg, M, N1, N2) ? 1 : 0;
 }
 
 int ffuse_force_plan(const ffuse_plan_t* plan) {

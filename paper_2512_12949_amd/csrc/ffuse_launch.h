@@ -72,6 +72,8 @@ struct TwoPhaseArgs {
     // per image) with conv_ic channels, W1 is [3][3][conv_ic][N1], K = 9 * conv_ic
     int conv_ic, conv_h, conv_w;
     int nt;           // != 0: the weights are streamed with the non-temporal hint (row blocks below 256 only)
+    int group_local;  // != 0: a group's phase-2 items read only what the group's own phase-1 items wrote: the barrier
+                      // between the phases waits for the group's own arrivals only
     int phases;       // 3: both phases with the device-wide barrier between them (the fused chain);
                       // 1 / 2: only the first / second phase (two launches = the unfused comparison path)
 };

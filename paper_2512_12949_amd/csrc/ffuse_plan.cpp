@@ -14,6 +14,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <vector>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -120,6 +121,45 @@ bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1,
     g->ysum_bytes = g->splits > 1 ? (((size_t)4 * M * N2 * g->splits + 255) & ~(size_t)255) : 0;
     g->h_bytes = ((size_t)2 * M * N1 + 255) & ~(size_t)255;
     g->ws_bytes = g->ysum_bytes + g->h_bytes + kTwoPhaseFlagBytes;
+    return true;
+}
+
+namespace {
+// the kernel's item map (fused_two_phase_kernel: map_item): item `idx` of group `grp` -> (row block, slice)
+bool two_phase_item(int MB, int S, int raster, int grp, int idx, int* i, int* s) {
+    const int total = MB * S;
+    const int per = (total + 7) / 8;
+    const int v = grp * per + idx;
+    if (idx >= per || v >= total) return false;
+    const int panel = v / (raster * S);
+    const int rem = v - panel * raster * S;
+    const int rows = std::min(raster, MB - panel * raster);
+    *i = panel * raster + rem % rows;
+    *s = rem / rows;
+    return true;
+}
+}  // namespace
+
+bool two_phase_groups_independent(const TwoPhaseGeometry& g, int64_t M, int64_t N1, int64_t N2) {
+    const int MB = (int)((M + g.bm - 1) / g.bm);
+    const int NS1 = (int)((N1 + g.bh1 - 1) / g.bh1);
+    const int NCB = (int)((N2 + 255) / 256);
+    if ((int64_t)MB * NS1 > 65536 || (int64_t)MB * NCB * g.splits > 65536) return false;   // (not worth the host time)
+    // producer group of every H tile (row block, phase-1 slice)
+    std::vector<signed char> owner((size_t)MB * NS1, (signed char)-1);
+    for (int grp = 0; grp < 8; ++grp) {
+        int i, s;
+        for (int idx = 0; two_phase_item(MB, NS1, g.raster, grp, idx, &i, &s); ++idx) owner[(size_t)i * NS1 + s] = (signed char)grp;
+    }
+    for (int grp = 0; grp < 8; ++grp) {
+        int i, u;
+        for (int idx = 0; two_phase_item(MB, NCB * g.splits, g.raster, grp, idx, &i, &u); ++idx) {
+            const int sp = u / NCB;
+            const int64_t k0 = (int64_t)sp * g.ksplit, k1 = std::min<int64_t>(N1, k0 + g.ksplit);
+            for (int64_t s = k0 / g.bh1; s * g.bh1 < k1; ++s)
+                if (owner[(size_t)i * NS1 + s] != grp) return false;
+        }
+    }
     return true;
 }
 
@@ -333,7 +373,8 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         t->fabric_bytes = b1 + b2 + re1 + re2;
         t->t_hbm = t1 + t2;
         t->t_mfma = m1 + m2;
-        t->t_pred = std::max(t1, m1) + std::max(t2, m2) + planes + 13e-6;
+        // launch, barrier, pipeline fills: 13 us; 2 us less where the barrier is per group (measured on the m = 128 shapes)
+        t->t_pred = std::max(t1, m1) + std::max(t2, m2) + planes + (two_phase_groups_independent(sg, M, N1, N2) ? 11e-6 : 13e-6);
     }
 }
 

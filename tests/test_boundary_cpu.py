@@ -151,3 +151,76 @@ def test_streamed_weights_get_one_row_block():
         assert p.family == ff.FAMILY_TWOPHASE and (p.bm >= M or p.bm == 256), (M, p.as_dict())
     p = ff.ffuse_choose_plan(ff.DT_BF16, 2, False, 128, 2048, 8192, 2048)
     assert p.family == ff.FAMILY_TWOPHASE and p.bm in (64, 128)
+
+
+def test_group_local_barrier_condition_matches_the_item_maps():
+    """Host logic of the two-phase family's barrier scope: ffuse_plan_group_local must say 1
+    exactly when every second-phase item of a workgroup group reads only tiles of the
+    intermediate that first-phase items of the same group write.  Checked against an enumeration
+    written here from the kernel's documented item map (items are dealt group by group, ceil(total/8)
+    consecutive items each; within a group's range, patches of `raster` row blocks x all slices,
+    row block fastest)."""
+    import random
+
+    def item(MB, S, raster, grp, idx):
+        total = MB * S
+        per = -(-total // 8)
+        v = grp * per + idx
+        if idx >= per or v >= total:
+            return None
+        panel, rem = divmod(v, raster * S)
+        rows = min(raster, MB - panel * raster)
+        return panel * raster + rem % rows, rem // rows
+
+    def independent(M, N1, N2, bm, bh1, splits, raster):
+        MB, NS1, NCB = -(-M // bm), -(-N1 // bh1), -(-N2 // 256)
+        raster = min(raster, MB)
+        ksplit = -(-(-(-N1 // splits)) // 64) * 64
+        splits = -(-N1 // ksplit)
+        owner = {}
+        for g in range(8):
+            idx = 0
+            while (it := item(MB, NS1, raster, g, idx)) is not None:
+                owner[it] = g
+                idx += 1
+        for g in range(8):
+            idx = 0
+            while (it := item(MB, NCB * splits, raster, g, idx)) is not None:
+                rb, u = it
+                sp = u // NCB
+                k0, k1 = sp * ksplit, min(N1, (sp + 1) * ksplit)
+                s = k0 // bh1
+                while s * bh1 < k1:
+                    if owner[(rb, s)] != g:
+                        return False
+                    s += 1
+                idx += 1
+        return True
+
+    rng = random.Random(7)
+    cases = [(4096, 4096, 16384, 4096, False, 256, 256, 1, 4), (4096, 4096, 16384, 4096, False, 256, 256, 1, 2),
+             (2048, 4096, 11008, 4096, True, 256, 128, 2, 4), (2048, 4096, 11008, 4096, True, 256, 128, 2, 1),
+             (32768, 1024, 8192, 1024, False, 256, 256, 1, 4), (16, 8192, 28672, 8192, True, 32, 128, 8, 1),
+             (128, 4096, 16384, 4096, False, 64, 128, 8, 2), (128, 4096, 11008, 4096, True, 64, 128, 8, 2)]
+    for _ in range(60):
+        bm = rng.choice([32, 64, 128, 256])
+        M = rng.randint(1, 4 * bm if bm < 128 else 2000)
+        gated = rng.random() < 0.5
+        bh1 = (128 if gated else 256) if bm == 256 else (128 if bm < 64 else rng.choice([128, 64]))
+        cases.append((M, 8 * rng.randint(8, 64), 8 * rng.randint(1, 1500), 8 * rng.randint(1, 300), gated, bm, bh1,
+                      rng.choice([1, 2, 3, 4, 8, 16]), rng.choice([1, 2, 4, 8])))
+    seen = set()
+    for (M, K, N1, N2, gated, bm, bh1, splits, raster) in cases:
+        plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=bh1, bn2=256, bk=32, splits=splits, raster=raster)
+        try:
+            got = ff.ffuse_plan_group_local(plan, ff.DT_BF16, gated, M, K, N1, N2)
+        except ff.FfuseError:
+            continue        # not a plan the kernels implement for this shape
+        want = independent(M, N1, N2, bm, bh1, splits, raster)
+        assert got == want, (M, K, N1, N2, gated, bm, bh1, splits, raster, got, want)
+        seen.add(got)
+    assert seen == {True, False}
+    # the benchmark configurations: gpt with four row blocks per patch is not, with two it is
+    assert not ff.ffuse_plan_group_local(ff.make_plan(ff.FAMILY_TWOPHASE, bm=256, bh=256, bn2=256, bk=32, splits=1, raster=4), ff.DT_BF16, False, 4096, 4096, 16384, 4096)
+    assert ff.ffuse_plan_group_local(ff.make_plan(ff.FAMILY_TWOPHASE, bm=256, bh=256, bn2=256, bk=32, splits=1, raster=2), ff.DT_BF16, False, 4096, 4096, 16384, 4096)
+

@@ -188,6 +188,36 @@ def test_two_launches_give_the_fused_calls_bits():
         assert torch.equal(one, two)
 
 
+def test_group_local_barrier_gives_the_same_bits(monkeypatch):
+    """Where every second-phase item of a workgroup group reads only what the group's own
+    first-phase items wrote (ffuse_plan_group_local), the barrier between the phases waits for
+    the group alone.  Same plan with the device-wide barrier: the same bits; both within
+    tolerance of the oracle; repeated calls (the counters are left clean)."""
+    cases = [(128, 520, 4096, 2048, False, ACT_GELU_TANH, 64, 128, 8, 2), (100, 264, 11008, 1032, True, ACT_SILU, 64, 128, 8, 2),
+             (16, 1032, 7168, 520, True, ACT_SILU, 32, 128, 8, 1), (128, 136, 3072, 768, False, ACT_RELU, 64, 64, 16, 2),
+             (2048, 264, 1024, 520, False, ACT_GELU_TANH, 256, 256, 1, 1), (1000, 136, 2048, 264, True, ACT_SILU, 128, 128, 1, 1),
+             (700, 264, 4104, 520, False, ACT_GELU_TANH, 256, 256, 1, 4)]      # (the last one is not group-local)
+    locals_seen = 0
+    for n, (M, K, N1, N2, gated, act, bm, bh, splits, raster) in enumerate(cases):
+        w, host, dev = _case("grp", M, K, N1, N2, "bf16", act, gated, cfg_id=720 + n)
+        rows = None if M <= 256 else inputs.sample_rows(M, 256, 6, seed=n)
+        ref = gu.oracle_rows(w, host, rows)
+        plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=bh, bn2=256, bk=32, splits=splits, raster=raster)
+        local = ff.ffuse_plan_group_local(plan, ff.DT_BF16, gated, M, K, N1, N2)
+        locals_seen += int(local)
+        print(f"group barrier: {(M, K, N1, N2)} gated={gated} plan {(bm, bh, splits, raster)} group-local={local}", flush=True)
+        monkeypatch.setenv("FFUSE_GROUP_BARRIER", "1")
+        outs = [gu.run(w, dev, plan=plan) for _ in range(3)]
+        monkeypatch.setenv("FFUSE_GROUP_BARRIER", "0")
+        wide = gu.run(w, dev, plan=plan)
+        gu.check(outs[0], ref, "bf16", rows=rows, what="group-local barrier")
+        gu.check(wide, ref, "bf16", rows=rows, what="device-wide barrier")
+        for y in outs:
+            assert torch.equal(y, wide)
+    assert locals_seen >= 4
+    monkeypatch.delenv("FFUSE_GROUP_BARRIER")
+
+
 @pytest.mark.parametrize("act", [ACT_RELU, ACT_GELU_TANH, ACT_SILU, ACT_IDENTITY])
 @pytest.mark.parametrize("gated", [False, True])
 def test_activations_medium(act, gated):
