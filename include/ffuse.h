@@ -195,8 +195,9 @@ int ffuse_force_plan(const ffuse_plan_t* plan);
  *                  non-temporal load hint.  Default: only when the weights exceed 512 MB -- far more than
  *                  the 256 MB memory-side cache can keep from one call to the next.  A caller that cycles
  *                  through many layers' weights may want 1 for smaller layers too.
- *   FFUSE_GROUP_BARRIER=0  the two-phase kernel's barrier always waits for every workgroup (default: only
- *                  for the workgroup's own group where ffuse_plan_group_local says that suffices).
+ *   FFUSE_GROUP_BARRIER=0  the two-phase kernel's barrier always waits for every workgroup (default: a group
+ *                  of workgroups waits for the groups whose tiles of the intermediate its second-phase
+ *                  items read -- for itself alone where ffuse_plan_group_local says 1).
  *   FFUSE_LOG=1    (read once) per-launch diagnostics on stderr from ffuse_sync_status.
  *   FFUSE_COOPERATIVE_LAUNCH=1  launch the persistent kernels with the runtime's cooperative launch. */
 /* Plan used by the most recent fused call of this process. */

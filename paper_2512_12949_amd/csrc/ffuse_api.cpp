@@ -226,7 +226,7 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
         ffuse::TwoPhaseArgs s{X, W1, W3, W2, base + sg.ysum_bytes, Y, reinterpret_cast<float*>(base), flags,
                               M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, sg.raster, nullptr,
                               g.conv_ic, g.conv_h, g.conv_w, stream_weights(dtype, gated, K, N1, N2),
-                              (group_barrier() && ffuse::two_phase_groups_independent(sg, M, N1, N2)) ? 1 : 0, 3};
+                              group_barrier() ? ffuse::two_phase_wait_masks(sg, M, N1, N2) : ~(uint64_t)0, 3};
         if (g.log && g.ws_bytes >= sg.ws_bytes + 65536) {
             s.stats = reinterpret_cast<uint64_t*>(base + sg.ws_bytes);
             g.small_stats = s.stats;

@@ -72,8 +72,8 @@ struct TwoPhaseArgs {
     // per image) with conv_ic channels, W1 is [3][3][conv_ic][N1], K = 9 * conv_ic
     int conv_ic, conv_h, conv_w;
     int nt;           // != 0: the weights are streamed with the non-temporal hint (row blocks below 256 only)
-    int group_local;  // != 0: a group's phase-2 items read only what the group's own phase-1 items wrote: the barrier
-                      // between the phases waits for the group's own arrivals only
+    uint64_t wait_masks;  // byte g, bit h: between the phases, workgroups of group g (blockIdx % 8) wait for the
+                          // arrivals of group h -- the groups whose phase-1 tiles of H group g's phase-2 items read
     int phases;       // 3: both phases with the device-wide barrier between them (the fused chain);
                       // 1 / 2: only the first / second phase (two launches = the unfused comparison path)
 };

@@ -140,27 +140,37 @@ bool two_phase_item(int MB, int S, int raster, int grp, int idx, int* i, int* s)
 }
 }  // namespace
 
-bool two_phase_groups_independent(const TwoPhaseGeometry& g, int64_t M, int64_t N1, int64_t N2) {
+uint64_t two_phase_wait_masks(const TwoPhaseGeometry& g, int64_t M, int64_t N1, int64_t N2) {
     const int MB = (int)((M + g.bm - 1) / g.bm);
     const int NS1 = (int)((N1 + g.bh1 - 1) / g.bh1);
     const int NCB = (int)((N2 + 255) / 256);
-    if ((int64_t)MB * NS1 > 65536 || (int64_t)MB * NCB * g.splits > 65536) return false;   // (not worth the host time)
+    if ((int64_t)MB * NS1 > 65536 || (int64_t)MB * NCB * g.splits > 65536) return ~(uint64_t)0;   // (not worth the host time)
     // producer group of every H tile (row block, phase-1 slice)
     std::vector<signed char> owner((size_t)MB * NS1, (signed char)-1);
     for (int grp = 0; grp < 8; ++grp) {
         int i, s;
         for (int idx = 0; two_phase_item(MB, NS1, g.raster, grp, idx, &i, &s); ++idx) owner[(size_t)i * NS1 + s] = (signed char)grp;
     }
+    uint64_t masks = 0;
     for (int grp = 0; grp < 8; ++grp) {
+        uint64_t m = (uint64_t)1 << grp;   // (a group always waits for its own stores)
         int i, u;
         for (int idx = 0; two_phase_item(MB, NCB * g.splits, g.raster, grp, idx, &i, &u); ++idx) {
             const int sp = u / NCB;
             const int64_t k0 = (int64_t)sp * g.ksplit, k1 = std::min<int64_t>(N1, k0 + g.ksplit);
-            for (int64_t s = k0 / g.bh1; s * g.bh1 < k1; ++s)
-                if (owner[(size_t)i * NS1 + s] != grp) return false;
+            for (int64_t s = k0 / g.bh1; s * g.bh1 < k1; ++s) {
+                const int o = owner[(size_t)i * NS1 + s];
+                if (o < 0) return ~(uint64_t)0;   // (cannot happen: every tile has a producer)
+                m |= (uint64_t)1 << o;
+            }
         }
+        masks |= m << (8 * grp);
     }
-    return true;
+    return masks;
+}
+
+bool two_phase_groups_independent(const TwoPhaseGeometry& g, int64_t M, int64_t N1, int64_t N2) {
+    return two_phase_wait_masks(g, M, N1, N2) == 0x8040201008040201ull;
 }
 
 bool fused_reduce_tile_ok(int gated, int bm, int bh) {
@@ -373,8 +383,10 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         t->fabric_bytes = b1 + b2 + re1 + re2;
         t->t_hbm = t1 + t2;
         t->t_mfma = m1 + m2;
-        // launch, barrier, pipeline fills: 13 us; 2 us less where the barrier is per group (measured on the m = 128 shapes)
-        t->t_pred = std::max(t1, m1) + std::max(t2, m2) + planes + (two_phase_groups_independent(sg, M, N1, N2) ? 11e-6 : 13e-6);
+        // launch, barrier, pipeline fills: 13 us; 2 us less where the barrier is per group (measured on the m = 128
+        // shapes; with 256-row blocks it is lost in the noise, and the measured order of the rasters decides there)
+        t->t_pred = std::max(t1, m1) + std::max(t2, m2) + planes +
+                    ((sg.bm < 256 && two_phase_groups_independent(sg, M, N1, N2)) ? 11e-6 : 13e-6);
     }
 }
 

@@ -50,9 +50,11 @@ int two_phase_max_splits(int64_t M, int64_t N2);
 // them with the non-temporal hint (row blocks below 256)
 bool weights_streamed(int dtype, int gated, int64_t K, int64_t N1, int64_t N2);
 bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, int64_t N2, TwoPhaseGeometry* out);
-// True when, with `grid` workgroups dealt to 8 groups (blockIdx % 8) the way the kernel deals its work items,
-// every phase-2 item of a group reads only tiles of H that the same group's phase-1 items write: the groups
-// then need not wait for each other between the phases.
+// Which groups of workgroups (blockIdx % 8; the kernel deals its work items group by group) a group has to
+// wait for between the phases: byte g of the result has bit h set when some phase-2 item of group g reads a
+// tile of H that a phase-1 item of group h writes.  All ones when the item counts are too large to enumerate.
+uint64_t two_phase_wait_masks(const TwoPhaseGeometry& g, int64_t M, int64_t N1, int64_t N2);
+// every group waits for itself alone
 bool two_phase_groups_independent(const TwoPhaseGeometry& g, int64_t M, int64_t N1, int64_t N2);
 
 bool fused_reduce_tile_ok(int gated, int bm, int bh);

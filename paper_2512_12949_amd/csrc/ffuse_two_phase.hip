@@ -257,18 +257,16 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
     if (tid == 0 && both) {
         uint32_t ok = 1;
         uint32_t spins = 0;
+        const uint32_t wait = (uint32_t)(a.wait_masks >> (8 * xcd)) & 0xffu;
         for (;;) {
+            // (only the groups whose phase-1 tiles this group's phase-2 items read)
             uint32_t fewest = ~0u;
-            if (a.group_local) {
-                // this group's phase-2 items read only H tiles of this group's phase-1 items
-                fewest = __hip_atomic_load(a.flags + kTwoPhaseGroupWord * (1 + xcd), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            } else {
 #pragma unroll
-                for (int g = 0; g < 8; ++g) {
+            for (int g = 0; g < 8; ++g)
+                if ((wait >> g) & 1u) {
                     const uint32_t n = __hip_atomic_load(a.flags + kTwoPhaseGroupWord * (1 + g), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     fewest = n < fewest ? n : fewest;
                 }
-            }
             if (fewest >= (uint32_t)GX) break;
             __builtin_amdgcn_s_sleep(1);
             if ((++spins & 1023u) == 0 &&
