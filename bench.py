@@ -203,11 +203,21 @@ def main():
         rows = inputs.sample_rows(w.M, max(1, w.M // max(1, nrows // 2)), 2, seed=7)[:nrows]
         print(f"[bench] cpu baseline: oracle on {len(rows)} rows", file=sys.stderr, flush=True)
         ref, t_cpu = oracle_rows(rows)
+        # a workload the oracle finishes in well under the target (the decode shapes: all rows in a
+        # fraction of a second) is timed over repeated passes, ~10 s in all, for a steady figure
+        passes = 1
+        if len(rows) == w.M and t_cpu < 5.0:
+            extra = int(min(200, max(0, 10.0 / max(t_cpu, 1e-3) - 1)))
+            for _ in range(extra):
+                _, t = oracle_rows(rows)
+                t_cpu += t
+                passes += 1
         got = Y_fused[torch.as_tensor(rows, device="cuda")].float().cpu().numpy().astype(np.float64)
         rel = float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-300))
-        out["cpu_baseline"] = {"value": per_row * len(rows) / t_cpu * 1e-12, "unit": "TFLOP/s",
+        out["cpu_baseline"] = {"value": per_row * len(rows) * passes / t_cpu * 1e-12, "unit": "TFLOP/s",
                                "cores": oracle.num_threads(), "kind": "oracle",
-                               "sample": f"{len(rows)} of {w.M} rows, all {w.N2} columns, {t_cpu:.1f} s"}
+                               "sample": f"{len(rows)} of {w.M} rows, all {w.N2} columns" +
+                                         (f", {passes} passes" if passes > 1 else "") + f", {t_cpu:.1f} s"}
         out["max_rel_err_vs_oracle"] = rel
     if args.copy_calibration:
         # one plain elementwise copy kernel of known size: reads 256 MiB, writes 256 MiB
