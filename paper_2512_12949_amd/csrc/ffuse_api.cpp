@@ -169,6 +169,23 @@ int stream_weights(int dtype, int gated, int64_t K, int64_t N1, int64_t N2) {
     return ffuse::weights_streamed(dtype, gated, K, N1, N2) ? 1 : 0;
 }
 
+// The barrier's wait masks are an enumeration of the kernel's item maps (thousands of items at the large
+// shapes): remembered for the last few (geometry, shape) pairs, so that a serving loop pays for them once.
+// The caller holds the lock.
+uint64_t wait_masks(const ffuse::TwoPhaseGeometry& sg, int64_t M, int64_t N1, int64_t N2) {
+    struct Entry { int bm, bh1, splits, ksplit, raster; int64_t M, N1, N2; uint64_t masks; bool used; };
+    static Entry cache[8] = {};
+    static int next = 0;
+    for (const Entry& e : cache)
+        if (e.used && e.bm == sg.bm && e.bh1 == sg.bh1 && e.splits == sg.splits && e.ksplit == sg.ksplit && e.raster == sg.raster &&
+            e.M == M && e.N1 == N1 && e.N2 == N2)
+            return e.masks;
+    const uint64_t m = ffuse::two_phase_wait_masks(sg, M, N1, N2);
+    cache[next] = Entry{sg.bm, sg.bh1, sg.splits, sg.ksplit, sg.raster, M, N1, N2, m, true};
+    next = (next + 1) % 8;
+    return m;
+}
+
 // FFUSE_GROUP_BARRIER=0: the barrier between the phases always waits for every workgroup; read per call
 bool group_barrier() {
     const char* env = std::getenv("FFUSE_GROUP_BARRIER");
@@ -226,7 +243,7 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
         ffuse::TwoPhaseArgs s{X, W1, W3, W2, base + sg.ysum_bytes, Y, reinterpret_cast<float*>(base), flags,
                               M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, sg.raster, nullptr,
                               g.conv_ic, g.conv_h, g.conv_w, stream_weights(dtype, gated, K, N1, N2),
-                              group_barrier() ? ffuse::two_phase_wait_masks(sg, M, N1, N2) : ~(uint64_t)0, 3};
+                              group_barrier() ? wait_masks(sg, M, N1, N2) : ~(uint64_t)0, 3};
         if (g.log && g.ws_bytes >= sg.ws_bytes + 65536) {
             s.stats = reinterpret_cast<uint64_t*>(base + sg.ws_bytes);
             g.small_stats = s.stats;
