@@ -240,7 +240,10 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
     // the L2 holds a few MB of dirty lines).  A workgroup arrives with ONE atomic add whose
     // result it does not wait for, on the counter of its group of G/8 workgroups (eight counters
     // a cache line apart: 256 adds on one word take three times as long as 32 on each of 8), and
-    // then polls all eight counters at once.  Measured in isolation: 1.8-3.9 us, against 3.8-6.5
+    // then polls, together, the counters of the groups whose tiles of H its own group's phase-2 items read
+    // (a.wait_masks, enumerated on the host from the two item maps: often its own group alone, and
+    // then a group that is done starts phase 2 while others still stream their weights).  Measured in
+    // isolation, waiting for all eight: 1.8-3.9 us, against 3.8-6.5
     // with a returning add plus a second, group-to-global add, and 7-12.5 with a releasing add.
     // bounded: on expiry the error word is set and every workgroup leaves
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
