@@ -501,15 +501,28 @@ int run_conv_chain(int dtype, const void* X, const void* W1, const void* W2, int
         found = plan.bm <= 128 && ffuse::plan_valid(plan, dtype, 0, M, K, OC1, OC2);
         if (!found) return FFUSE_ERR_PLAN;
     } else {
-        std::vector<ffuse::RankedPlan> ranked;
-        ffuse::rank_plans(dtype, act, 0, M, K, OC1, OC2, &ranked);
-        for (const auto& r : ranked)
-            if (r.plan.family == FFUSE_FAMILY_TWOPHASE && r.plan.bm <= 128 && r.plan.bk != 32 &&
-                ffuse::plan_workspace_bytes(r.plan, dtype, 0, M, K, OC1, OC2) <= g.ws_bytes) {
-                plan = r.plan;
-                found = true;
-                break;
+        // the model's best plan among those the 3x3 loader's kernels implement: ranked once per shape, then
+        // looked up (its own key space in the plan table: dtype + 32)
+        const auto key = table_key(dtype + 32, 0, K, OC1, OC2, -M);
+        auto it = g.table.find(key);
+        if (it != g.table.end() && ffuse::plan_workspace_bytes(it->second.plan, dtype, 0, M, K, OC1, OC2) <= g.ws_bytes) {
+            plan = it->second.plan;
+            found = true;
+        } else {
+            std::vector<ffuse::RankedPlan> ranked;
+            ffuse::rank_plans(dtype, act, 0, M, K, OC1, OC2, &ranked);
+            for (const auto& r : ranked)
+                if (r.plan.family == FFUSE_FAMILY_TWOPHASE && r.plan.bm <= 128 && r.plan.bk != 32 &&
+                    ffuse::plan_workspace_bytes(r.plan, dtype, 0, M, K, OC1, OC2) <= g.ws_bytes) {
+                    plan = r.plan;
+                    found = true;
+                    break;
+                }
+            if (found) {
+                if (g.table.size() > 4096) g.table.clear();
+                g.table[key] = {plan, 0.0};
             }
+        }
     }
     if (!found) return g.ws ? FFUSE_ERR_WORKSPACE : FFUSE_ERR_WORKSPACE;
     g.conv_ic = (int)IC; g.conv_h = (int)H; g.conv_w = (int)W;
