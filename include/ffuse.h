@@ -25,12 +25,22 @@
  *     is fp32, the intermediate is rounded to the operand type (round-to-nearest-even) before
  *     the second product, and Y is rounded once from fp32 to the operand type.
  *   - Shape rules: M >= 1 (any value, row tails are masked); K, N1, N2 >= 8 and multiples
- *     of 8; every tensor smaller than 2 GiB.  Anything else returns FFUSE_ERR_SHAPE.
+ *     of 8; every tensor smaller than 2 GiB, and the M x N1 intermediate counts as one
+ *     ((M + 256) N1 elements of the operand type: rows are independent, a taller problem is two
+ *     calls).  Anything else returns FFUSE_ERR_SHAPE.
  *   - Errors are returned as negative status codes; nothing is written on a validation error.
- *   - The fused and unfused paths need a caller-owned workspace (ffuse_workspace_bytes,
- *     ffuse_set_workspace).  A call leaves the workspace ready for the next call on the
- *     same stream; calls that overlap on different streams need different workspaces,
- *     i.e. must not overlap while sharing one.
+ *   - The fused and unfused paths need a caller-owned workspace of ffuse_workspace_bytes: either
+ *     ONE registered with ffuse_set_workspace and used by every call that does not name another,
+ *     or one passed per call (ffuse_ffn_ws, ffuse_ffn_unfused_ws).  A call leaves its workspace
+ *     ready for the next call on the same stream.  Calls that overlap in time (different
+ *     streams) need different workspaces: give each stream its own through the _ws calls.
+ *     Between calls the library remembers, per workspace address, what it left there (which
+ *     part is zero, where clean barrier flags lie); a caller that writes into a workspace
+ *     itself must hand it over again (ffuse_set_workspace, or any other size in a _ws call).
+ *   - Graph capture: a call recorded while `stream` is capturing records its own clearing of
+ *     the flags or sums it needs, whatever the library believes about the workspace, so the
+ *     graph may be replayed between any other calls on the same workspace (not concurrently
+ *     with them).
  */
 #ifndef FFUSE_H
 #define FFUSE_H
@@ -81,6 +91,13 @@ typedef enum {
                                  (Sec. 4.1 "shuffle" strategy, exchange through L2)         */
     FFUSE_FAMILY_UNFUSED = 3, /* traffic model only: two GEMM launches of 256-row tiles       */
     FFUSE_FAMILY_SCALAR = 4,  /* fp32 debug kernels (plain FMA, no matrix cores)            */
+    FFUSE_FAMILY_ROWS = 6,    /* row-stationary: a workgroup owns bm = 64 rows and ALL N2 output columns
+                                 (N2 <= 1024), keeps its rows of X in registers (K <= 1024), the output
+                                 block in accumulators and one activated chunk of bh = 64 hidden columns in
+                                 LDS while it walks the hidden dimension; nothing is exchanged between
+                                 workgroups, no workspace, Y is the only thing stored (Sec. 4.2: the
+                                 MLNK-style loop order with the intermediate mapped to registers -> shared
+                                 memory).  Not gated.  For large M.                                   */
     FFUSE_FAMILY_TWOPHASE = 5 /* any M: one persistent kernel; every CU computes tiles of the
                                  intermediate into an L2 / Infinity-Cache resident buffer, one
                                  device-wide barrier, then every CU multiplies a row block of it
@@ -137,6 +154,19 @@ int ffuse_ffn_f16(const void* X, const void* W1, const void* W3, const void* W2,
                   int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
 int ffuse_ffn_f32(const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M,
                   int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
+
+/* The same two paths with the workspace named per call (dtype: ffuse_dtype_t).  `workspace` is a
+ * device pointer, 16-byte aligned, of `workspace_bytes` bytes (a multiple of 16); NULL / 0 is
+ * accepted and runs the plans that need none (FFUSE_ERR_WORKSPACE otherwise).  Nothing about
+ * the workspace has to be prepared by the caller: a workspace the library has not seen before
+ * (or sees with another size) is treated as dirty, and the call clears what it needs on `stream`.
+ * Two streams with two workspaces may overlap in time. */
+int ffuse_ffn_ws(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act,
+                 int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* workspace,
+                 size_t workspace_bytes, void* stream);
+int ffuse_ffn_unfused_ws(int dtype, const void* X, const void* W1, const void* W3, const void* W2,
+                         int act, int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y,
+                         void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- the unfused comparison path (Evaluation, "Performance Analysis": the baseline writes
  *      the intermediate to global memory and reads it back): GEMM + activation/gate into a
@@ -242,6 +272,13 @@ int ffuse_plan_table_load(const char* path);
  * status. */
 int ffuse_rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
                      ffuse_plan_t* plans, double* t_pred_s, int capacity);
+
+/* ---- test hook for the failure path of the two-phase family's barrier: later launches wait for
+ *      `extra_arrivals` workgroups more than exist (0 = normal) and give up after `spin_limit`
+ *      polls (default 2^24).  With extra_arrivals > 0 and a small limit every workgroup's bounded
+ *      wait expires, every workgroup leaves normally without running the second phase, and
+ *      ffuse_sync_status reports FFUSE_ERR_TIMEOUT; the next normal launch is unaffected. ------ */
+int ffuse_debug_barrier(int extra_arrivals, unsigned int spin_limit);
 
 /* ---- measurement aid: when enabled, the library brackets the dominant kernel of every
  *      fused / unfused call with HIP events on the call's stream.  ffuse_profile_read

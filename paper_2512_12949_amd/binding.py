@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libffuse.so")
 
 ACT_IDENTITY, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 DT_BF16, DT_F16, DT_F32 = 0, 1, 2
-FAMILY_AUTO, FAMILY_REDUCE, FAMILY_EXCHANGE, FAMILY_UNFUSED, FAMILY_SCALAR, FAMILY_TWOPHASE = 0, 1, 2, 3, 4, 5
+FAMILY_AUTO, FAMILY_REDUCE, FAMILY_EXCHANGE, FAMILY_UNFUSED, FAMILY_SCALAR, FAMILY_TWOPHASE, FAMILY_ROWS = 0, 1, 2, 3, 4, 5, 6
 DTYPE_CODE = {"bf16": DT_BF16, "f16": DT_F16, "f32": DT_F32}
 
 EXPORTS = [
@@ -26,6 +26,7 @@ EXPORTS = [
     "ffuse_tune", "ffuse_plan_lookup", "ffuse_plan_table_clear", "ffuse_conv_chain", "ffuse_conv_chain_f16", "ffuse_rank_plans",
     "ffuse_plan_table_set", "ffuse_plan_table_save", "ffuse_plan_table_load",
     "ffuse_status_string", "ffuse_version",
+    "ffuse_ffn_ws", "ffuse_ffn_unfused_ws", "ffuse_debug_barrier",
 ]
 
 
@@ -113,6 +114,12 @@ def lib():
         L.ffuse_status_string.restype = ctypes.c_char_p
         L.ffuse_status_string.argtypes = [ci]
         L.ffuse_version.restype = ci
+        for name in ("ffuse_ffn_ws", "ffuse_ffn_unfused_ws"):
+            f = getattr(L, name)
+            f.restype = ci
+            f.argtypes = [ci, vp, vp, vp, vp, ci, i64, i64, i64, i64, vp, vp, ctypes.c_size_t, vp]
+        L.ffuse_debug_barrier.restype = ci
+        L.ffuse_debug_barrier.argtypes = [ci, ctypes.c_uint]
         _lib = L
     return _lib
 
@@ -168,6 +175,30 @@ def ffuse_ffn_unfused_f16(X, W1, W3, W2, act, Y, stream=None, check=True):
 
 def ffuse_ffn_unfused_f32(X, W1, W3, W2, act, Y, stream=None, check=True):
     return _call("ffuse_ffn_unfused_f32", X, W1, W3, W2, act, Y, stream, check)
+
+
+def _call_ws(name, dtype, X, W1, W3, W2, act, Y, workspace, stream, check):
+    M, K = X.shape
+    N1, N2 = W2.shape
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = getattr(lib(), name)(int(dtype), _ptr(X), _ptr(W1), _ptr(W3), _ptr(W2), int(act), M, K, N1, N2, _ptr(Y),
+                              _ptr(workspace), nbytes, _stream(stream))
+    if check:
+        _check(rc, name)
+    return rc
+
+
+def ffuse_ffn_ws(dtype, X, W1, W3, W2, act, Y, workspace, stream=None, check=True):
+    """The fused chain with the workspace named per call (``workspace``: a device tensor, or None)."""
+    return _call_ws("ffuse_ffn_ws", dtype, X, W1, W3, W2, act, Y, workspace, stream, check)
+
+
+def ffuse_ffn_unfused_ws(dtype, X, W1, W3, W2, act, Y, workspace, stream=None, check=True):
+    return _call_ws("ffuse_ffn_unfused_ws", dtype, X, W1, W3, W2, act, Y, workspace, stream, check)
+
+
+def ffuse_debug_barrier(extra_arrivals=0, spin_limit=1 << 24):
+    _check(lib().ffuse_debug_barrier(int(extra_arrivals), int(spin_limit)), "ffuse_debug_barrier")
 
 
 FUSED = {"bf16": ffuse_ffn, "f16": ffuse_ffn_f16, "f32": ffuse_ffn_f32}

@@ -17,12 +17,29 @@
 
 namespace {
 
+// What the library remembers about a caller-owned workspace between calls: how much of its start is
+// known to be zero (the reduce family keeps its sums there) and where the two-phase family last left
+// clean barrier flags.  A workspace the library has not seen (or whose size changed) counts as dirty.
+struct Workspace {
+    void* ptr = nullptr;
+    size_t bytes = 0;
+    size_t zero = 0;                  // bytes at the start known to be zero
+    uint32_t* small_flags = nullptr;  // where the two-phase family last left clean barrier flags
+    uint64_t used = 0;                // age, for replacement
+};
+
+// geometry of a 3x3 first convolution (ic == 0: the first product is a plain GEMM)
+struct ConvGeom {
+    int ic = 0, h = 0, w = 0;
+};
+
 struct State {
     std::mutex mu;
-    void* ws = nullptr;
-    size_t ws_bytes = 0;
-    size_t ws_zero = 0;      // bytes at the start of the workspace known to be zero
-    uint32_t* small_flags = nullptr;  // where the two-phase family last left clean barrier flags
+    Workspace reg;           // the workspace registered with ffuse_set_workspace
+    Workspace seen[8];       // workspaces passed per call (ffuse_ffn_ws ...), most recently used kept
+    uint64_t clock = 0;
+    uint32_t spin_limit = 1u << 24;   // bounded waits of the two-phase barrier (ffuse_debug_barrier)
+    int extra_arrivals = 0;
     bool forced = false;
     ffuse_plan_t forced_plan{};
     ffuse_plan_t last_plan{};
@@ -45,9 +62,27 @@ struct State {
         double ms;        // measured time of a tuned plan; 0 for a modelled one
     };
     std::map<std::array<int64_t, 6>, TableEntry> table;
-    int conv_ic = 0, conv_h = 0, conv_w = 0;   // set around a 3x3 convolution-chain call only
 };
 State g;
+
+// the record of a per-call workspace; the caller holds the lock
+Workspace& workspace_record(void* ptr, size_t bytes) {
+    Workspace* oldest = &g.seen[0];
+    for (Workspace& w : g.seen) {
+        if (w.ptr == ptr && w.bytes == bytes) { w.used = ++g.clock; return w; }
+        if (w.used < oldest->used) oldest = &w;
+    }
+    *oldest = Workspace{ptr, bytes, 0, nullptr, ++g.clock};
+    return *oldest;
+}
+// forget what is known about any record that overlaps [ptr, ptr + bytes): its memory is about to change hands
+void forget_overlapping(const void* ptr, size_t bytes) {
+    const char* a = static_cast<const char*>(ptr);
+    for (Workspace& w : g.seen) {
+        const char* b = static_cast<const char*>(w.ptr);
+        if (w.ptr && a < b + w.bytes && b < a + bytes) w = Workspace{};
+    }
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -68,8 +103,10 @@ int validate(const void* X, const void* W1, const void* W3, const void* W2, int 
     if (act < FFUSE_ACT_IDENTITY || act > FFUSE_ACT_SILU) return FFUSE_ERR_ACT;
     if (M < 1 || K < 8 || N1 < 8 || N2 < 8 || (K % 8) || (N1 % 8) || (N2 % 8)) return FFUSE_ERR_SHAPE;
     const int64_t lim = (int64_t)1 << 31;
+    // (the M x N1 intermediate counts as a tensor: the kernels that keep it in the workspace address it, like
+    // the operands, through 32-bit buffer offsets, and mask lanes with an offset of 2^31)
     if ((M + 256) * K * elem >= lim || (K + 128) * N1 * elem >= lim || (N1 + 512) * N2 * elem >= lim ||
-        M * N2 * 4 >= ((int64_t)1 << 40) || M * N2 * elem >= lim)
+        M * N2 * 4 >= ((int64_t)1 << 40) || M * N2 * elem >= lim || (M + 256) * N1 * elem >= lim)
         return FFUSE_ERR_SHAPE;
     if (!aligned16(X) || !aligned16(W1) || !aligned16(W2) || !aligned16(Y) || (W3 && !aligned16(W3)))
         return FFUSE_ERR_ALIGN;
@@ -94,11 +131,19 @@ void read_env_plan() {
 }
 
 // makes the first `need` bytes of the workspace zero (they usually already are)
-bool ensure_zero(size_t need, hipStream_t st) {
-    if (g.ws_zero >= need) return true;
-    if (ffuse::launch_zero(g.ws, (need + 15) & ~(size_t)15, st) != hipSuccess) return false;
-    g.ws_zero = need;
+bool ensure_zero(Workspace& w, size_t need, hipStream_t st) {
+    if (w.zero >= need) return true;
+    if (ffuse::launch_zero(w.ptr, (need + 15) & ~(size_t)15, st) != hipSuccess) return false;
+    w.zero = need;
     return true;
+}
+
+// A launch recorded into a graph runs later, any number of times, between other calls: what the library
+// knows about the workspace now says nothing about its state then, so a captured call always records its
+// own clearing and leaves the record "unknown".
+bool stream_is_capturing(hipStream_t st) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    return hipStreamIsCapturing(st, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone;
 }
 
 struct Timer {  // brackets the dominant kernel with events when profiling is on
@@ -121,11 +166,12 @@ std::array<int64_t, 6> table_key(int dtype, int gated, int64_t K, int64_t N1, in
 }
 
 // a0: the plan for this call -- a tuned plan of M's bin if there is one that fits, else the
-// model's choice for exactly this M (computed once, then looked up)
-ffuse_plan_t lookup_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
+// model's choice for exactly this M (computed once, then looked up).  ws_bytes: the workspace the
+// call will run in (0: none yet, nothing to fit).
+ffuse_plan_t lookup_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, size_t ws_bytes) {
     auto it = g.table.find(table_key(dtype, gated, K, N1, N2, ffuse::m_bin(M)));
     if (it != g.table.end() && ffuse::plan_valid(it->second.plan, dtype, gated, M, K, N1, N2) &&
-        (!g.ws || ffuse::plan_workspace_bytes(it->second.plan, dtype, gated, M, K, N1, N2) <= g.ws_bytes))   // (no workspace yet: nothing to fit)
+        (!ws_bytes || ffuse::plan_workspace_bytes(it->second.plan, dtype, gated, M, K, N1, N2) <= ws_bytes))
         return it->second.plan;
     const auto key = table_key(dtype, gated, K, N1, N2, -M);
     it = g.table.find(key);
@@ -138,15 +184,13 @@ ffuse_plan_t lookup_plan(int dtype, int act, int gated, int64_t M, int64_t K, in
 }
 
 int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act,
-             int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream, bool two_launches = false);
+             int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, Workspace& w, void* stream, bool two_launches = false,
+             const ConvGeom& conv = ConvGeom{});
 
-int run_fused(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
-              int64_t N1, int64_t N2, void* Y, void* stream) {
-    const int elem = dtype == FFUSE_DT_F32 ? 4 : 2;
-    int rc = validate(X, W1, W3, W2, act, M, K, N1, N2, Y, elem);
-    if (rc != FFUSE_OK) return rc;
-    std::lock_guard<std::mutex> lock(g.mu);
-    rc = check_arch();
+// `ws`: the workspace of this call (nullptr: the registered one); the caller holds the lock
+int run_fused_locked(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+                     int64_t N1, int64_t N2, void* Y, Workspace& w, void* stream) {
+    int rc = check_arch();
     if (rc != FFUSE_OK) return rc;
     read_env_plan();
     const int gated = W3 != nullptr;
@@ -155,9 +199,18 @@ int run_fused(int dtype, const void* X, const void* W1, const void* W3, const vo
         plan = g.forced_plan;
         if (!ffuse::plan_valid(plan, dtype, gated, M, K, N1, N2) || plan.family == FFUSE_FAMILY_UNFUSED) return FFUSE_ERR_PLAN;
     } else {
-        plan = lookup_plan(dtype, act, gated, M, K, N1, N2);
+        plan = lookup_plan(dtype, act, gated, M, K, N1, N2, w.ptr ? w.bytes : 0);
     }
-    return run_plan(plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+    return run_plan(plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, w, stream);
+}
+
+int run_fused(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+              int64_t N1, int64_t N2, void* Y, void* stream) {
+    const int elem = dtype == FFUSE_DT_F32 ? 4 : 2;
+    int rc = validate(X, W1, W3, W2, act, M, K, N1, N2, Y, elem);
+    if (rc != FFUSE_OK) return rc;
+    std::lock_guard<std::mutex> lock(g.mu);
+    return run_fused_locked(dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, g.reg, stream);
 }
 
 // Weights far larger than the 256 MB memory-side cache are streamed with the non-temporal
@@ -192,31 +245,52 @@ bool group_barrier() {
     return !env || std::atoi(env) != 0;
 }
 
-// launches one validated plan; the caller holds the lock.  two_launches (two-phase family
-// only): each phase is a launch of its own and the kernel boundary replaces the barrier.
+// launches one validated plan in workspace `w`; the caller holds the lock.  two_launches (two-phase
+// family only): each phase is a launch of its own and the kernel boundary replaces the barrier.
 int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act,
-             int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream, bool two_launches) {
+             int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, Workspace& w, void* stream, bool two_launches,
+             const ConvGeom& conv) {
     const int gated = W3 != nullptr;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const bool capturing = stream_is_capturing(st);
+    if (capturing) { w.zero = 0; w.small_flags = nullptr; }
+    // whatever this call leaves behind, a replay of the recorded launch may find something else
+    struct Forget {
+        Workspace& w; bool on;
+        ~Forget() { if (on) { w.zero = 0; w.small_flags = nullptr; } }
+    } forget{w, capturing};
     ffuse::FusedArgs a{X, W1, W3, W2, nullptr, M, (int)K, (int)N1, (int)N2, act, plan.raster > 0 ? plan.raster : 1};
     if (plan.family == FFUSE_FAMILY_SCALAR) {
         Timer t(st);
         if (ffuse::launch_fused_f32(a, reinterpret_cast<float*>(Y), st) != hipSuccess) return FFUSE_ERR_LAUNCH;
         t.stop();
         g.last_plan = plan;
+        g.exch_err = nullptr;
+        return FFUSE_OK;
+    }
+    if (plan.family == FFUSE_FAMILY_ROWS) {
+        ffuse::RowsGeometry rg;
+        if (!ffuse::rows_geometry(plan, gated, M, K, N1, N2, &rg)) return FFUSE_ERR_PLAN;
+        ffuse::RowsArgs r{X, W1, W3, W2, Y, M, (int)K, (int)N1, (int)N2, act};
+        Timer t(st);
+        const int64_t mb = (M + 63) / 64;
+        if (ffuse::launch_fused_rows(dtype, r, rg.nks, rg.nt2, (int)std::min<int64_t>(mb, g.cus), st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+        t.stop();
+        g.last_plan = plan;
+        g.exch_err = nullptr;
         return FFUSE_OK;
     }
     if (plan.family == FFUSE_FAMILY_EXCHANGE) {
         ffuse::ExchangeGeometry e;
         if (!ffuse::exchange_geometry(plan, gated, M, N1, N2, g.cus, &e)) return FFUSE_ERR_PLAN;
-        if (!g.ws || g.ws_bytes < e.ws_bytes) return FFUSE_ERR_WORKSPACE;
-        char* base = reinterpret_cast<char*>(g.ws);
+        if (!w.ptr || w.bytes < e.ws_bytes) return FFUSE_ERR_WORKSPACE;
+        char* base = reinterpret_cast<char*>(w.ptr);
         if (ffuse::launch_zero(base, ffuse::kExchangeFlagBytes, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
-        g.ws_zero = 0;      // the ring overwrites the region the other families keep at zero
-        g.small_flags = nullptr;
+        w.zero = 0;      // the ring overwrites the region the other families keep at zero
+        w.small_flags = nullptr;
         ffuse::ExchangeArgs x{X, W1, W3, W2, Y, base + ffuse::kExchangeFlagBytes, reinterpret_cast<uint32_t*>(base),
                               M, (int)K, (int)N1, (int)N2, act, e.P, e.NCT, e.PG, e.R, e.NH, plan.coherent, nullptr};
-        if (g.log && g.ws_bytes >= e.ws_bytes + 8192 * 4) {
+        if (g.log && w.bytes >= e.ws_bytes + 8192 * 4) {
             x.stats = reinterpret_cast<uint64_t*>(base + e.ws_bytes);
             g.exch_stats = x.stats;
             g.exch_wgs = 8 * e.wgs_per_group;
@@ -232,24 +306,26 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
     if (plan.family == FFUSE_FAMILY_TWOPHASE) {
         ffuse::TwoPhaseGeometry sg;
         if (!ffuse::two_phase_geometry(plan, gated, M, N1, N2, &sg)) return FFUSE_ERR_PLAN;
-        if (!g.ws || g.ws_bytes < sg.ws_bytes) return FFUSE_ERR_WORKSPACE;
-        char* base = reinterpret_cast<char*>(g.ws);
+        if (!w.ptr || w.bytes < sg.ws_bytes) return FFUSE_ERR_WORKSPACE;
+        char* base = reinterpret_cast<char*>(w.ptr);
         uint32_t* flags = reinterpret_cast<uint32_t*>(base + sg.ysum_bytes + sg.h_bytes);
-        if (g.small_flags != flags) {
+        if (w.small_flags != flags) {
             if (ffuse::launch_zero(flags, ffuse::kTwoPhaseFlagBytes, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
-            g.small_flags = flags;
+            w.small_flags = flags;
         }
-        g.ws_zero = 0;      // planes and H overwrite the region the reduce family keeps at zero
+        w.zero = 0;      // planes and H overwrite the region the reduce family keeps at zero
         ffuse::TwoPhaseArgs s{X, W1, W3, W2, base + sg.ysum_bytes, Y, reinterpret_cast<float*>(base), flags,
                               M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, sg.raster, nullptr,
-                              g.conv_ic, g.conv_h, g.conv_w, stream_weights(dtype, gated, K, N1, N2),
-                              group_barrier() ? wait_masks(sg, M, N1, N2) : ~(uint64_t)0, 3};
-        if (g.log && g.ws_bytes >= sg.ws_bytes + 65536) {
+                              conv.ic, conv.h, conv.w, stream_weights(dtype, gated, K, N1, N2),
+                              group_barrier() ? wait_masks(sg, M, N1, N2) : ~(uint64_t)0, 3,
+                              g.spin_limit, g.extra_arrivals};
+        if (g.log && w.bytes >= sg.ws_bytes + 65536) {
             s.stats = reinterpret_cast<uint64_t*>(base + sg.ws_bytes);
             g.small_stats = s.stats;
             g.small_split = two_launches;
         }
-        g.exch_err = flags + 2;
+        // (launched one phase at a time there is no barrier and no verdict)
+        g.exch_err = two_launches ? nullptr : flags + 3;
         {
             Timer t(st);
             if (two_launches) {
@@ -259,24 +335,25 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
                 if (s.stats) s.stats += 4 * 1024;
             }
             if (ffuse::launch_fused_two_phase(dtype, s, sg.bm, sg.bh1, sg.bk, g.cus, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+            if (sg.splits > 1 && ffuse::launch_finalize_planes(dtype, s.part, Y, M * N2, sg.splits, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
             t.stop();
         }
-        if (sg.splits > 1 && ffuse::launch_finalize_planes(dtype, s.part, Y, M * N2, sg.splits, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
         g.last_plan = plan;
         return FFUSE_OK;
     }
     if (plan.family != FFUSE_FAMILY_REDUCE) return FFUSE_ERR_PLAN;
     const size_t need = sizeof(float) * (size_t)M * (size_t)N2;
-    if (!g.ws || g.ws_bytes < need) return FFUSE_ERR_WORKSPACE;
-    if (!ensure_zero(need, st)) return FFUSE_ERR_LAUNCH;
-    a.Ysum = reinterpret_cast<float*>(g.ws);
+    if (!w.ptr || w.bytes < need) return FFUSE_ERR_WORKSPACE;
+    if (!ensure_zero(w, need, st)) return FFUSE_ERR_LAUNCH;
+    w.small_flags = nullptr;   // (the sums may lie over the two-phase family's flags)
+    a.Ysum = reinterpret_cast<float*>(w.ptr);
     g.exch_err = nullptr;
     {
         Timer t(st);
         if (ffuse::launch_fused_reduce(dtype, a, plan.bm, plan.bh, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
+        if (ffuse::launch_finalize(dtype, a.Ysum, Y, M * N2, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
         t.stop();
     }
-    if (ffuse::launch_finalize(dtype, a.Ysum, Y, M * N2, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
     g.last_plan = plan;
     return FFUSE_OK;
 }
@@ -285,14 +362,10 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
 // two launches.  16-bit types run the two-phase family's kernel one phase per launch, in
 // the tile plan the model ranks best for this shape, so that the only differences from the
 // fused call are the second launch and the kernel boundary in place of the barrier.
-int run_unfused(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M,
-                int64_t K, int64_t N1, int64_t N2, void* Y, void* stream) {
+int run_unfused_locked(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M,
+                       int64_t K, int64_t N1, int64_t N2, void* Y, Workspace& w, void* stream) {
     const int elem = dtype == FFUSE_DT_F32 ? 4 : 2;
-    int rc = validate(X, W1, W3, W2, act, M, K, N1, N2, Y, elem);
-    if (rc != FFUSE_OK) return rc;
-    if (M * N1 * elem >= ((int64_t)1 << 31)) return FFUSE_ERR_SHAPE;
-    std::lock_guard<std::mutex> lock(g.mu);
-    rc = check_arch();
+    int rc = check_arch();
     if (rc != FFUSE_OK) return rc;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (dtype != FFUSE_DT_F32) {
@@ -311,21 +384,38 @@ int run_unfused(int dtype, const void* X, const void* W1, const void* W3, const 
             it = g.table.find(key);
         }
         const ffuse_plan_t keep = g.last_plan;
-        rc = run_plan(it->second.plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, stream, true);
+        rc = run_plan(it->second.plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, w, stream, true);
         g.last_plan = keep;   // ffuse_last_plan reports fused calls only
         return rc;
     }
     const size_t need = (size_t)elem * (size_t)M * (size_t)N1;
-    if (!g.ws || g.ws_bytes < need) return FFUSE_ERR_WORKSPACE;
-    g.ws_zero = 0;      // H overwrites whatever the fused path kept at zero
-    g.small_flags = nullptr;
+    if (!w.ptr || w.bytes < need) return FFUSE_ERR_WORKSPACE;
+    w.zero = 0;      // H overwrites whatever the fused path kept at zero
+    w.small_flags = nullptr;
     g.exch_err = nullptr;
-    ffuse::GemmArgs g0{X, W1, W3, g.ws, M, (int)K, (int)N1, act};
-    ffuse::GemmArgs g1{g.ws, W2, nullptr, Y, M, (int)N1, (int)N2, FFUSE_ACT_IDENTITY};
+    ffuse::GemmArgs g0{X, W1, W3, w.ptr, M, (int)K, (int)N1, act};
+    ffuse::GemmArgs g1{w.ptr, W2, nullptr, Y, M, (int)N1, (int)N2, FFUSE_ACT_IDENTITY};
     Timer t(st);
     if (ffuse::launch_gemm_act_f32(g0, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
     if (ffuse::launch_gemm_act_f32(g1, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
     t.stop();
+    return FFUSE_OK;
+}
+
+int run_unfused(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M,
+                int64_t K, int64_t N1, int64_t N2, void* Y, void* stream) {
+    const int elem = dtype == FFUSE_DT_F32 ? 4 : 2;
+    int rc = validate(X, W1, W3, W2, act, M, K, N1, N2, Y, elem);
+    if (rc != FFUSE_OK) return rc;
+    std::lock_guard<std::mutex> lock(g.mu);
+    return run_unfused_locked(dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, g.reg, stream);
+}
+
+// the workspace argument of a per-call entry point: nullptr / 0 is allowed (families that need none)
+int check_ws_arg(const void* ws, size_t bytes) {
+    if (!ws) return bytes == 0 ? FFUSE_OK : FFUSE_ERR_NULL;
+    if (!aligned16(ws)) return FFUSE_ERR_ALIGN;
+    if (bytes % 16) return FFUSE_ERR_SHAPE;
     return FFUSE_OK;
 }
 
@@ -358,6 +448,35 @@ int ffuse_ffn_unfused_f32(const void* X, const void* W1, const void* W3, const v
     return run_unfused(FFUSE_DT_F32, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
 }
 
+int ffuse_ffn_ws(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+                 int64_t N1, int64_t N2, void* Y, void* workspace, size_t workspace_bytes, void* stream) {
+    if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F32) return FFUSE_ERR_ACT;
+    int rc = validate(X, W1, W3, W2, act, M, K, N1, N2, Y, dtype == FFUSE_DT_F32 ? 4 : 2);
+    if (rc != FFUSE_OK) return rc;
+    if ((rc = check_ws_arg(workspace, workspace_bytes)) != FFUSE_OK) return rc;
+    std::lock_guard<std::mutex> lock(g.mu);
+    Workspace none;
+    return run_fused_locked(dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, workspace ? workspace_record(workspace, workspace_bytes) : none, stream);
+}
+int ffuse_ffn_unfused_ws(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+                         int64_t N1, int64_t N2, void* Y, void* workspace, size_t workspace_bytes, void* stream) {
+    if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F32) return FFUSE_ERR_ACT;
+    int rc = validate(X, W1, W3, W2, act, M, K, N1, N2, Y, dtype == FFUSE_DT_F32 ? 4 : 2);
+    if (rc != FFUSE_OK) return rc;
+    if ((rc = check_ws_arg(workspace, workspace_bytes)) != FFUSE_OK) return rc;
+    std::lock_guard<std::mutex> lock(g.mu);
+    Workspace none;
+    return run_unfused_locked(dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, workspace ? workspace_record(workspace, workspace_bytes) : none, stream);
+}
+
+int ffuse_debug_barrier(int extra_arrivals, unsigned int spin_limit) {
+    if (extra_arrivals < 0 || extra_arrivals > 1024 || spin_limit < 1) return FFUSE_ERR_SHAPE;
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.extra_arrivals = extra_arrivals;
+    g.spin_limit = spin_limit;
+    return FFUSE_OK;
+}
+
 size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, int unfused) {
     (void)gated; (void)K;
     if (M < 1 || N1 < 1 || N2 < 1) return 0;
@@ -379,13 +498,16 @@ size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t
 int ffuse_set_workspace(void* dev_ptr, size_t bytes, void* stream) {
     std::lock_guard<std::mutex> lock(g.mu);
     if (!dev_ptr) {
-        g.ws = nullptr; g.ws_bytes = 0; g.ws_zero = 0; g.small_flags = nullptr; g.exch_err = nullptr;
+        g.reg = Workspace{};
+        g.exch_err = nullptr;
         return FFUSE_OK;
     }
     if (!aligned16(dev_ptr)) return FFUSE_ERR_ALIGN;
     if (bytes % 16) return FFUSE_ERR_SHAPE;
     if (ffuse::launch_zero(dev_ptr, bytes, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return FFUSE_ERR_LAUNCH;
-    g.ws = dev_ptr; g.ws_bytes = bytes; g.ws_zero = bytes; g.small_flags = nullptr; g.exch_err = nullptr;
+    forget_overlapping(dev_ptr, bytes);
+    g.reg = Workspace{dev_ptr, bytes, bytes, nullptr, 0};
+    g.exch_err = nullptr;
     return FFUSE_OK;
 }
 
@@ -480,6 +602,7 @@ int ffuse_sync_status(void* stream) {
 // chain on the pixel rows; a 3x3 one runs the two-phase kernel with implicit-im2col loads.
 int run_conv_chain(int dtype, const void* X, const void* W1, const void* W2, int act, int64_t B, int64_t H, int64_t W,
                    int64_t IC, int64_t OC1, int64_t OC2, int k1, int k2, void* Y, void* stream) {
+    Workspace& ws = g.reg;
     if (B < 1 || H < 1 || W < 1 || IC < 8 || H > 32768 || W > 32768) return FFUSE_ERR_SHAPE;
     if (k2 != 1 || (k1 != 1 && k1 != 3)) return FFUSE_ERR_SHAPE;
     const int64_t M = B * H * W, K = (int64_t)k1 * k1 * IC;
@@ -505,7 +628,7 @@ int run_conv_chain(int dtype, const void* X, const void* W1, const void* W2, int
         // looked up (its own key space in the plan table: dtype + 32)
         const auto key = table_key(dtype + 32, 0, K, OC1, OC2, -M);
         auto it = g.table.find(key);
-        if (it != g.table.end() && ffuse::plan_workspace_bytes(it->second.plan, dtype, 0, M, K, OC1, OC2) <= g.ws_bytes) {
+        if (it != g.table.end() && ffuse::plan_workspace_bytes(it->second.plan, dtype, 0, M, K, OC1, OC2) <= ws.bytes) {
             plan = it->second.plan;
             found = true;
         } else {
@@ -513,7 +636,7 @@ int run_conv_chain(int dtype, const void* X, const void* W1, const void* W2, int
             ffuse::rank_plans(dtype, act, 0, M, K, OC1, OC2, &ranked);
             for (const auto& r : ranked)
                 if (r.plan.family == FFUSE_FAMILY_TWOPHASE && r.plan.bm <= 128 && r.plan.bk != 32 &&
-                    ffuse::plan_workspace_bytes(r.plan, dtype, 0, M, K, OC1, OC2) <= g.ws_bytes) {
+                    ffuse::plan_workspace_bytes(r.plan, dtype, 0, M, K, OC1, OC2) <= ws.bytes) {
                     plan = r.plan;
                     found = true;
                     break;
@@ -524,11 +647,8 @@ int run_conv_chain(int dtype, const void* X, const void* W1, const void* W2, int
             }
         }
     }
-    if (!found) return g.ws ? FFUSE_ERR_WORKSPACE : FFUSE_ERR_WORKSPACE;
-    g.conv_ic = (int)IC; g.conv_h = (int)H; g.conv_w = (int)W;
-    rc = run_plan(plan, dtype, X, W1, nullptr, W2, act, M, K, OC1, OC2, Y, stream);
-    g.conv_ic = g.conv_h = g.conv_w = 0;
-    return rc;
+    if (!found) return FFUSE_ERR_WORKSPACE;
+    return run_plan(plan, dtype, X, W1, nullptr, W2, act, M, K, OC1, OC2, Y, ws, stream, false, ConvGeom{(int)IC, (int)H, (int)W});
 }
 
 // Sec. 4.3, Algorithm 2, second half: time the analytically best `top_k` plans on the device
@@ -563,8 +683,8 @@ int ffuse_tune(int dtype, const void* X, const void* W1, const void* W3, const v
         if ((int)cands.size() >= top_k) break;
         const ffuse_plan_t& p = cand.plan;
         if (!ffuse::plan_valid(p, dtype, gated, M, K, N1, N2)) continue;
-        if (ffuse::plan_workspace_bytes(p, dtype, gated, M, K, N1, N2) > g.ws_bytes) continue;
-        last_rc = run_plan(p, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+        if (ffuse::plan_workspace_bytes(p, dtype, gated, M, K, N1, N2) > g.reg.bytes) continue;
+        last_rc = run_plan(p, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, g.reg, stream);
         if (last_rc != FFUSE_OK) continue;
         if (hipStreamSynchronize(st) != hipSuccess) { last_rc = FFUSE_ERR_LAUNCH; stop = true; break; }
         if (g.exch_err) {
@@ -578,15 +698,15 @@ int ffuse_tune(int dtype, const void* X, const void* W1, const void* W3, const v
         // bring clocks and caches to their steady state before anything is timed, or the first
         // candidate is measured on a different chip than the last
         for (int r = 0; r < 2 * reps && last_rc == FFUSE_OK; ++r)
-            last_rc = run_plan(cands[0].plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+            last_rc = run_plan(cands[0].plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, g.reg, stream);
         // two timed passes, the second in reverse order (drift of the clocks cancels); a candidate's
         // time is the better of its two
         for (int pass = 0; pass < 2 && !stop; ++pass)
             for (size_t n = 0; n < cands.size(); ++n) {
                 Cand& c = cands[pass == 0 ? n : cands.size() - 1 - n];
-                last_rc = run_plan(c.plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);   // (its own warm-up: LDS size, L2 contents)
+                last_rc = run_plan(c.plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, g.reg, stream);   // (its own warm-up: LDS size, L2 contents)
                 (void)hipEventRecord(e0, st);
-                for (int r = 0; r < reps && last_rc == FFUSE_OK; ++r) last_rc = run_plan(c.plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, stream);
+                for (int r = 0; r < reps && last_rc == FFUSE_OK; ++r) last_rc = run_plan(c.plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, g.reg, stream);
                 (void)hipEventRecord(e1, st);
                 if (hipEventSynchronize(e1) != hipSuccess) { last_rc = FFUSE_ERR_LAUNCH; stop = true; break; }
                 if (last_rc != FFUSE_OK) continue;
@@ -689,7 +809,7 @@ int ffuse_plan_table_load(const char* path) {
         ffuse_plan_t p{};
         p.family = v[0]; p.bm = v[1]; p.bh = v[2]; p.bn2 = v[3]; p.bk = v[4]; p.splits = v[5]; p.h_level = v[6]; p.raster = v[7];
         p.producers = v[8]; p.ring = v[9]; p.coherent = v[10];
-        if (p.family <= FFUSE_FAMILY_AUTO || p.family > FFUSE_FAMILY_TWOPHASE) continue;
+        if (p.family <= FFUSE_FAMILY_AUTO || p.family > FFUSE_FAMILY_ROWS) continue;
         // validity for a concrete M is checked again at lookup time
         g.table[table_key((int)k[0], (int)k[1], k[2], k[3], k[4], k[5])] = {p, ms > 0.0 ? ms : 1e-9};
         ++n;
@@ -709,7 +829,7 @@ int ffuse_plan_lookup(int dtype, int act, int gated, int64_t M, int64_t K, int64
     if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F32) return FFUSE_ERR_ACT;
     if (M < 1 || K < 8 || N1 < 8 || N2 < 8) return FFUSE_ERR_SHAPE;
     std::lock_guard<std::mutex> lock(g.mu);
-    *out = lookup_plan(dtype, act, gated ? 1 : 0, M, K, N1, N2);
+    *out = lookup_plan(dtype, act, gated ? 1 : 0, M, K, N1, N2, g.reg.ptr ? g.reg.bytes : 0);
     if (tuned_ms) {
         auto it = g.table.find(table_key(dtype, gated ? 1 : 0, K, N1, N2, ffuse::m_bin(M)));
         *tuned_ms = (it != g.table.end() && std::memcmp(&it->second.plan, out, sizeof(*out)) == 0) ? it->second.ms : 0.0;

@@ -48,8 +48,10 @@ struct ExchangeArgs {
     uint64_t* stats;  // nullptr, or 4 words per workgroup: role, total ticks, waiting ticks, items
 };
 
-// two-phase family's flag words (kTwoPhaseFlagBytes in all): 1 = workgroups that have left, 2 = error;
-// kTwoPhaseGroupWord * (1 + g) = arrivals at the barrier of group g (a cache line apart)
+// two-phase family's flag words (kTwoPhaseFlagBytes in all): 1 = workgroups that have left, 2 = error word of
+// the launch in flight (cleared by the last workgroup to leave), 3 = error word of the most recent finished
+// launch (what the host reads); kTwoPhaseGroupWord * (1 + g) = arrivals at the barrier of group g (a cache
+// line apart)
 static constexpr int kTwoPhaseGroupWord = 16;
 
 struct TwoPhaseArgs {
@@ -60,7 +62,7 @@ struct TwoPhaseArgs {
     void* H;          // [M][N1] intermediate in the operand type (L2 / Infinity Cache resident)
     void* Y;          // [M][N2] output, written by the kernel itself when splits == 1
     float* part;      // splits > 1: fp32 partial sums [splits][M][N2], fully overwritten
-    uint32_t* flags;  // [0] barrier arrivals, [1] exits, [2] error; [0..1] zero on entry and on exit
+    uint32_t* flags;  // [1] exits, [2] error (both zero on entry and on exit), [3] verdict of the last finished launch
     int64_t M;
     int K, N1, N2;
     int act;
@@ -76,9 +78,27 @@ struct TwoPhaseArgs {
                           // arrivals of group h -- the groups whose phase-1 tiles of H group g's phase-2 items read
     int phases;       // 3: both phases with the device-wide barrier between them (the fused chain);
                       // 1 / 2: only the first / second phase (two launches = the unfused comparison path)
+    uint32_t spin_limit;   // polls after which a workgroup gives up waiting at the barrier (error word, FFUSE_ERR_TIMEOUT)
+    int extra_arrivals;    // 0; a test may ask the barrier to wait for arrivals that never come, to see the wait expire
 };
 
+// rows family (row-stationary): no workspace, no flags
+struct RowsArgs {
+    const void* X;
+    const void* W1;
+    const void* W3;   // must be nullptr (the gated chain is not built in this family)
+    const void* W2;
+    void* Y;
+    int64_t M;
+    int K, N1, N2;
+    int act;
+};
+static constexpr int kRowsRing = 6;                                                 // 4 KB weight slots per wave
+static constexpr int kRowsLdsBytes = 4 * kRowsRing * 4096 + 12 * 4096 + 64 * 128;   // rings | partial tiles | H chunk
+
 // 16-bit paths (dtype 0 = bf16, 1 = fp16)
+// nks: 16-k steps of the first product per wave (K <= 64 nks); nt2: 32-column output tiles per wave (N2 <= 128 nt2)
+hipError_t launch_fused_rows(int dtype, const RowsArgs& a, int nks, int nt2, int grid, hipStream_t st);
 hipError_t launch_fused_two_phase(int dtype, const TwoPhaseArgs& a, int bm, int bh1, int bk, int grid, hipStream_t st);
 hipError_t launch_finalize_planes(int dtype, const float* part, void* Y, int64_t count, int planes, hipStream_t st);
 hipError_t launch_fused_exchange(int dtype, const ExchangeArgs& a, int wgs_per_group, hipStream_t st);

@@ -38,6 +38,8 @@ const Device kDevice = {
     /*launch_s*/ 4e-6};
 
 static double cdiv(double a, double b) { return std::ceil(a / b); }
+static constexpr double kRowsEff = 0.40;   // rows family: fraction of the MFMA peak its loop sustains (measured)
+static constexpr double kRowsLdsModel = 4 * 6 * 4096 + 12 * 4096 + 64 * 128;   // rows family: rings, partial tiles, H chunk
 
 bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
     (void)M; (void)K; (void)N1; (void)N2;
@@ -51,6 +53,11 @@ bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t 
             if (dtype == FFUSE_DT_F32) return false;
             TwoPhaseGeometry sg;
             return two_phase_geometry(p, gated, M, N1, N2, &sg);
+        }
+        case FFUSE_FAMILY_ROWS: {
+            if (dtype == FFUSE_DT_F32) return false;
+            RowsGeometry rg;
+            return rows_geometry(p, gated, M, K, N1, N2, &rg);
         }
         case FFUSE_FAMILY_EXCHANGE: {
             if (dtype == FFUSE_DT_F32) return false;
@@ -76,6 +83,17 @@ bool exchange_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, 
     if (e->PG < 1) return false;
     if (e->R < 2 * e->PG + 2 || e->R > kExchangeMaxRing || 16 * e->R + 4 > (int)(kExchangeFlagBytes / 4)) return false;
     e->ws_bytes = kExchangeFlagBytes + (size_t)8 * e->R * 256 * bhp * 2;
+    return true;
+}
+
+// Rows family: 64 rows per workgroup, the whole output width in accumulators (256 registers per lane hold
+// 64 x 1024 fp32), the workgroup's rows of X in registers (128 per lane hold 64 x 1024 16-bit values, a
+// quarter of K per wave).  Two accumulator sets of the first product would not fit beside them: not gated.
+bool rows_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, RowsGeometry* g) {
+    if (gated || M < 1 || K < 8 || N1 < 8 || N2 < 8 || K > 1024 || N2 > 1024) return false;
+    if ((p.bm != 0 && p.bm != 64) || (p.bh != 0 && p.bh != 64)) return false;
+    g->nks = K <= 512 ? 8 : 16;
+    g->nt2 = N2 <= 512 ? 4 : 8;
     return true;
 }
 
@@ -118,6 +136,8 @@ bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1,
     if (splits > 32) return false;
     g->ksplit = (int)(((N1 + splits - 1) / splits + 63) / 64 * 64);
     g->splits = (int)((N1 + g->ksplit - 1) / g->ksplit);
+    // the kernel addresses H through 32-bit buffer offsets and masks lanes with an offset of 2^31
+    if ((M + 256) * N1 * 2 >= ((int64_t)1 << 31)) return false;
     g->ysum_bytes = g->splits > 1 ? (((size_t)4 * M * N2 * g->splits + 255) & ~(size_t)255) : 0;
     g->h_bytes = ((size_t)2 * M * N1 + 255) & ~(size_t)255;
     g->ws_bytes = g->ysum_bytes + g->h_bytes + kTwoPhaseFlagBytes;
@@ -258,7 +278,10 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
             t->lds_bytes = t->l2_bytes * 2.0;
             t->exchange_bytes = 2.0 * e * m * n1;
             t->reduce_bytes = 4.0 * m * n2 * sg.splits;
-            t->hbm_bytes = t->q_min;
+            // H is written through and read back: from the memory-side cache while it fits beside the
+            // operands, else from HBM (the same rule as for the unfused path below)
+            const double hb = e * m * n1;
+            t->hbm_bytes = t->q_min + (hb > 0.5 * d.mall_bytes ? 2.0 * hb : 0.0);
             t->lds_used = 2.0 * (bm * 128.0 + 256 * 128.0);
             t->acc_regs = 2.0 * (bm / 32.0) * 16.0;
         }
@@ -286,6 +309,27 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
             t->hbm_bytes = t->q_min;
             t->lds_used = 2.0 * (256 * 128.0 + 256 * 128.0);
             t->acc_regs = 256;
+        }
+    } else if (p.family == FFUSE_FAMILY_ROWS) {
+        RowsGeometry rg;
+        t->feasible = rows_geometry(p, gated, M, K, N1, N2, &rg) ? 1 : 0;
+        if (t->feasible) {
+            const double mb = cdiv(m, 64.0), kq = 16.0 * rg.nks * 4.0, nw = 128.0 * rg.nt2;
+            t->workgroups = (int)std::min(mb, (double)d.cus);
+            // every row block walks the whole hidden dimension at the kernel's padded K and N2
+            padded = mb * 2.0 * 64.0 * cdiv(n1, 64.0) * 64.0 * (kq + nw);
+            waves = cdiv(mb, d.cus) * d.cus / mb;
+            // L2 -> CU: every row block streams all weights; X once
+            t->l2_bytes = mb * e * (k * n1 + n1 * n2) + e * m * k;
+            // the workgroups of an XCD walk the chunks together: one fill per XCD and round of row blocks
+            t->fabric_bytes = std::min(8.0, mb) * cdiv(mb, d.cus) * e * (k * n1 + n1 * n2) + e * m * k + e * m * n2;
+            // LDS: every weight byte is written once and read once; partial tiles 2 x 48 KB + H per chunk
+            t->lds_bytes = t->l2_bytes + mb * cdiv(n1, 64.0) * (2.0 * 49152.0 + 4.0 * 8192.0 + 8192.0);
+            t->exchange_bytes = 0.0;
+            t->reduce_bytes = 0.0;
+            t->hbm_bytes = t->q_min;
+            t->lds_used = kRowsLdsModel;
+            t->acc_regs = 16.0 * 2.0 * rg.nt2;
         }
     } else if (p.family == FFUSE_FAMILY_UNFUSED) {
         const double bm = 256.0, bh0 = gated ? 128.0 : 256.0, bh1 = 256.0;
@@ -331,6 +375,14 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
     // the reduce family's units run their two products and their atomics one after the other, which this
     // bandwidth model does not see: measured on the smallest m = 128 shapes it is 5-35 % optimistic
     if (p.family == FFUSE_FAMILY_REDUCE) t->t_pred *= 1.25;
+    if (p.family == FFUSE_FAMILY_ROWS && t->feasible) {
+        // The kernel is a weight stream through LDS at 64 flop per weight byte: every byte is written to LDS
+        // once and read once by the matrix pipeline, which together with the partial-tile exchange takes the
+        // whole LDS bandwidth at the full matrix rate.  Measured fraction of the matrix peak on 32768 x 1024 x
+        // 8192 x 1024: kRowsEff; one launch, no second kernel.
+        t->t_mfma = padded * waves / (d.mfma_flops * kRowsEff);
+        t->t_pred = std::max({t->t_mfma, t->t_l2, t->t_fabric, t->t_hbm}) + d.launch_s;
+    }
     if (p.family == FFUSE_FAMILY_TWOPHASE && t->feasible) {
         // two phases back to back, each the longer of its streaming time and its matrix time.
         // Streaming: a workgroup of this kernel keeps ~64 KB in flight and sustains ~25 GB/s on
@@ -455,6 +507,15 @@ void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1,
             }
         }
     }
+    {
+        ffuse_plan_t p;
+        std::memset(&p, 0, sizeof(p));
+        p.family = FFUSE_FAMILY_ROWS;
+        p.bm = 64; p.bh = 64; p.bn2 = (int)std::min<int64_t>(N2, 1024); p.bk = 16; p.h_level = 1; p.raster = 1; p.splits = 1;
+        ffuse_traffic_t t;
+        traffic_model(p, dtype, gated, M, K, N1, N2, &t);
+        if (t.feasible) out->push_back({t.t_pred, p});
+    }
     static const int producers[] = {8, 12, 16, 20, 24};
     for (int pr : producers) {
         ffuse_plan_t p;
@@ -494,6 +555,7 @@ size_t plan_workspace_bytes(const ffuse_plan_t& p, int dtype, int gated, int64_t
             return two_phase_geometry(p, gated, M, N1, N2, &t) ? t.ws_bytes : 0;
         }
         case FFUSE_FAMILY_UNFUSED: return (dtype == FFUSE_DT_F32 ? 4 : 2) * (size_t)M * (size_t)N1;
+        case FFUSE_FAMILY_ROWS: return 0;
         default: return 0;
     }
 }

@@ -57,6 +57,13 @@ uint64_t two_phase_wait_masks(const TwoPhaseGeometry& g, int64_t M, int64_t N1, 
 // every group waits for itself alone
 bool two_phase_groups_independent(const TwoPhaseGeometry& g, int64_t M, int64_t N1, int64_t N2);
 
+// Rows family (row-stationary): which kernel instantiation runs a plan.
+struct RowsGeometry {
+    int nks;   // 16-k steps of the first product per wave: 8 (K <= 512) or 16 (K <= 1024)
+    int nt2;   // 32-column output tiles per wave: 4 (N2 <= 512) or 8 (N2 <= 1024)
+};
+bool rows_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, RowsGeometry* out);
+
 bool fused_reduce_tile_ok(int gated, int bm, int bh);
 bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2);
 void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,

@@ -31,7 +31,6 @@
 
 namespace ffuse {
 
-static constexpr uint32_t kBarrierSpinLimit = 1u << 24;
 
 // item `idx` of XCD `xcd` -> (row block i, slice s); false past the XCD's share
 __device__ __forceinline__ bool map_item(int MB, int S, int raster, int xcd, int idx, int& i, int& s) {
@@ -270,10 +269,11 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
                     const uint32_t n = __hip_atomic_load(a.flags + kTwoPhaseGroupWord * (1 + g), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     fewest = n < fewest ? n : fewest;
                 }
-            if (fewest >= (uint32_t)GX) break;
+            if (fewest >= (uint32_t)(GX + a.extra_arrivals)) break;
             __builtin_amdgcn_s_sleep(1);
-            if ((++spins & 1023u) == 0 &&
-                (spins > kBarrierSpinLimit || __hip_atomic_load(a.flags + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+            // gives up after spin_limit polls, or (looked at every 1024 polls) when another workgroup has
+            if (++spins >= a.spin_limit ||
+                ((spins & 1023u) == 0 && __hip_atomic_load(a.flags + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
                 __hip_atomic_fetch_or(a.flags + 2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 ok = 0;
                 break;
@@ -306,7 +306,8 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
         p[0] = t1 - t0; p[1] = t2 - t1; p[2] = wall_clock64() - t2; p[3] = c1 - c0;   // p[3]: core clocks of phase 1
     }
     // ---------------------------------------------------------------- leave the flags clean
-    // the last workgroup to get here resets the counters for the next launch
+    // the last workgroup to get here resets the counters for the next launch, and moves this launch's
+    // error word to where the host reads it: a wait that expired once must not make the next launch give up
     __syncthreads();
     if (tid == 0 && both) {
         const uint32_t prev = __hip_atomic_fetch_add(a.flags + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -314,6 +315,9 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
             __hip_atomic_store(a.flags + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             for (int i = 0; i < 8; ++i)
                 __hip_atomic_store(a.flags + kTwoPhaseGroupWord * (1 + i), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t verdict_word = __hip_atomic_load(a.flags + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(a.flags + 3, verdict_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(a.flags + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
