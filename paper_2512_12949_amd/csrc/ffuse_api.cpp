@@ -53,6 +53,8 @@ struct State {
     uint64_t* exch_stats = nullptr;
     bool small_split = false;
     uint64_t* small_stats = nullptr;
+    uint64_t* rows_stats = nullptr;
+    int rows_wgs = 0;
     int exch_wgs = 0;
     // plan table (Sec. 4.3: plans are fixed ahead of time per range of the dynamic dimension M
     // and looked up at run time).  Key: dtype, gated, K, N1, N2 and either the M bin (plans
@@ -271,7 +273,14 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
     if (plan.family == FFUSE_FAMILY_ROWS) {
         ffuse::RowsGeometry rg;
         if (!ffuse::rows_geometry(plan, gated, M, K, N1, N2, &rg)) return FFUSE_ERR_PLAN;
-        ffuse::RowsArgs r{X, W1, W3, W2, Y, M, (int)K, (int)N1, (int)N2, act};
+        ffuse::RowsArgs r{X, W1, W3, W2, Y, M, (int)K, (int)N1, (int)N2, act, nullptr};
+        g.rows_stats = nullptr;
+        if (g.log && w.ptr && w.bytes >= 16 * 1024) {   // diagnostics only: the family itself needs no workspace
+            r.stats = reinterpret_cast<uint64_t*>(w.ptr);
+            g.rows_stats = r.stats;
+            g.rows_wgs = (int)std::min<int64_t>((M + 63) / 64, g.cus);
+            w.zero = 0; w.small_flags = nullptr;
+        }
         Timer t(st);
         const int64_t mb = (M + 63) / 64;
         if (ffuse::launch_fused_rows(dtype, r, rg.nks, rg.nt2, (int)std::min<int64_t>(mb, g.cus), st) != hipSuccess) return FFUSE_ERR_LAUNCH;
@@ -574,6 +583,16 @@ int ffuse_sync_status(void* stream) {
                          b / n * 0.01, p2 / n * 0.01, m2 * 0.01);
         }
         g.small_stats = nullptr;
+    }
+    if (g.log && g.rows_stats) {
+        std::vector<uint64_t> h(2 * (size_t)g.rows_wgs);
+        if (hipMemcpy(h.data(), g.rows_stats, h.size() * 8, hipMemcpyDeviceToHost) == hipSuccess) {
+            double wall = 0, core = 0, mx = 0;
+            for (int i = 0; i < g.rows_wgs; ++i) { wall += h[2 * i]; core += h[2 * i + 1]; mx = std::max(mx, (double)h[2 * i]); }
+            std::fprintf(stderr, "[ffuse] rows: workgroup busy avg %.1f us (max %.1f) at %.0f MHz\n", wall / g.rows_wgs * 0.01, mx * 0.01,
+                         wall > 0 ? core / wall * 100.0 : 0.0);
+        }
+        g.rows_stats = nullptr;
     }
     if (!g.exch_err) return FFUSE_OK;
     uint32_t word = 0;

@@ -92,6 +92,7 @@ struct RowsArgs {
     int64_t M;
     int K, N1, N2;
     int act;
+    uint64_t* stats;  // nullptr, or 2 words per workgroup: 100 MHz ticks and core clocks from start to end
 };
 static constexpr int kRowsRing = 6;                                                 // 4 KB weight slots per wave
 static constexpr int kRowsLdsBytes = 4 * kRowsRing * 4096 + 12 * 4096 + 64 * 128;   // rings | partial tiles | H chunk

@@ -80,6 +80,9 @@ template <int N> __device__ __forceinline__ void rows_loads_in_flight_at_most() 
 // the wave has read from: measured on this chip, the load's data can land before reads that were issued
 // ahead of it have been served (the reads queue up when the LDS is saturated, the load's write does not).
 __device__ __forceinline__ void rows_lds_reads_done() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+// the same for all but the N LDS instructions issued last (LDS instructions of a wave complete in order; there
+// must BE at least N younger ones, or the wait says nothing about the older)
+template <int N> __device__ __forceinline__ void rows_lds_reads_older_done() { asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(N) : "memory"); }
 
 // The first product's MFMA with its accumulator in ARCHITECTURAL registers.  The compiler gives all
 // matrix instructions of a kernel one register form; this kernel's running output block fills all 256
@@ -128,11 +131,13 @@ __device__ __forceinline__ void rows_write_h(const f32x16& s, char* hbuf, uint32
 // ([32 k][64 hidden columns]) and then 4 NT2 / 4 slots of W2 ([16 hidden][128 output columns]), chunk after
 // chunk, row block after row block (the weights do not depend on the row block) -- through a ring of
 // kRowsRing positions.  A slot is multiplied in two STEPS of four MFMAs; a step takes its two weight fragments
-// from registers, and while it runs the two fragments of the next step are read from LDS into the other
-// register set.  When the second step of a slot has issued its MFMAs, every read of the slot has delivered
-// (rows_lds_reads_done), and only then are the loads of the slot kRowsRing further down the stream aimed at its
-// position.  The wait for a slot to have landed sits at the top of the step that first reads it.
-template <typename T, int NKS, int NT2>
+// from registers (set t % 3), and before its MFMAs are issued the two fragments of step t + 2 are read from LDS
+// into the set that step t - 1 has just finished with: one step of 128 matrix cycles is less than the LDS latency
+// under load, two cover it.  In the middle of a slot's first step every read of the slot has delivered
+// (rows_lds_reads_older_done), and only then are the loads of the slot kRowsRing further down the stream aimed
+// at its position, two in each of the slot's two steps.  The wait for a slot to have landed sits at the top of the step that first
+// reads it.
+template <typename T, int NKS, int NT2, bool RAGGED>
 __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
     typedef typename Mma<T>::vec8 vec8;
     typedef RowsSlot<64> S1;     // W1 slot: [32 k][64 hidden columns]
@@ -164,6 +169,8 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.X, (uint32_t)((uint64_t)a.M * K * 2));
     const int nrb = (MB > (int)blockIdx.x) ? (MB - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 0;
     if (nrb == 0) return;
+    uint64_t t_wall = 0, t_core = 0;
+    if (a.stats) { t_wall = wall_clock64(); t_core = clock64(); }
 
     // ---- lane constants of the weight stream -------------------------------------------------------
     // Every address of the stream is INSIDE its matrix: rows past the end are clamped to the last row and
@@ -186,29 +193,45 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
     // H fragment of hidden step ks2, rows 32 mt + x: lds_row_off(32 mt + x, 2 ks2 + h) = (hrd ^ (ks2 << 5)) + 4096 mt
     const uint32_t hrd = lds_row_off(lane & 31, lane >> 5);
 
-    // the four loads of slot `idx` (0 .. SPC-1) of chunk `c` into ring position `pos`.  The lane's constants
-    // are made opaque per slot: left alone, the compiler precomputes the addresses of all slots of a chunk and
-    // keeps them in registers that this kernel does not have.
-    auto issue = [&](int idx, int c, int pos) {
-        const uint32_t lds = ring_lds + (uint32_t)pos * SLOT;
+    // Load j (0 .. 3) of slot `idx` (0 .. SPC-1) of chunk `c` into ring position `pos`.  The lane's constants are
+    // made opaque per load: left alone, the compiler precomputes the addresses of all slots of a chunk and keeps
+    // them in registers that this kernel does not have.  RAGGED says that some address of the stream can fall
+    // outside its matrix and has to be clamped (K != 64 NKS, N1 % 64 != 0 or N2 != 128 NT2); for whole tiles the
+    // address is one add.
+    auto issue_one = [&](int idx, int c, int pos, int j) {
+        const uint32_t lds = ring_lds + (uint32_t)pos * SLOT + 1024u * j;
         if (idx < NS1) {
-            uint32_t b = base1, cb = colb1;
-            int kl = klimb1;
-            asm volatile("" : "+v"(b), "+v"(kl), "+v"(cb));
-            b += (128 * c + (int)cb < 2 * N1) ? (uint32_t)c * 128u : 0u - cb;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                rows_dma16(r1, b + (uint32_t)min((32 * idx + 8 * j) * N1 * 2, kl), lds + 1024u * j);
+            uint32_t b = base1;
+            asm volatile("" : "+v"(b));
+            const int rowb = (32 * idx + 8 * j) * N1 * 2;
+            if constexpr (!RAGGED) {
+                rows_dma16(r1, b + (uint32_t)(rowb + c * 128), lds);
+            } else {
+                uint32_t cb = colb1;
+                int kl = klimb1;
+                asm volatile("" : "+v"(kl), "+v"(cb));
+                b += (128 * c + (int)cb < 2 * N1) ? (uint32_t)c * 128u : 0u - cb;
+                rows_dma16(r1, b + (uint32_t)min(rowb, kl), lds);
+            }
         } else {
             const int ks2 = (idx - NS1) / NH2, half = (idx - NS1) % NH2;
-            uint32_t b = base2, cb = colb2;
-            int kl = klimb2;
-            asm volatile("" : "+v"(b), "+v"(kl), "+v"(cb));
-            b += (256 * half + (int)cb < 2 * N2) ? 256u * half : 0u - cb;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                rows_dma16(r2, b + (uint32_t)min((64 * c + 16 * ks2 + 4 * j) * N2 * 2, kl), lds + 1024u * j);
+            uint32_t b = base2;
+            asm volatile("" : "+v"(b));
+            const int rowb = (64 * c + 16 * ks2 + 4 * j) * N2 * 2;
+            if constexpr (!RAGGED) {
+                rows_dma16(r2, b + (uint32_t)(rowb + 256 * half), lds);
+            } else {
+                uint32_t cb = colb2;
+                int kl = klimb2;
+                asm volatile("" : "+v"(kl), "+v"(cb));
+                b += (256 * half + (int)cb < 2 * N2) ? 256u * half : 0u - cb;
+                rows_dma16(r2, b + (uint32_t)min(rowb, kl), lds);
+            }
         }
+    };
+    auto issue = [&](int idx, int c, int pos) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) issue_one(idx, c, pos, j);
     };
     // fragment e (0 / 1) of step t (0 .. NST-1) from the slot at `sb`
     auto read_frag = [&](int t, const char* sb, int e) -> vec8 {
@@ -216,13 +239,15 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
         return S2::template read_frag<vec8>(sb + (rd2 ^ (uint32_t)((2 * ((t - NST1) & 1) + e) << 6)));
     };
 
-    // ---- prime: slots 0 .. RING-1 of chunk 0, then the fragments of step 0
+    // ---- prime: slots 0 .. RING-1 of chunk 0, then the fragments of steps 0 and 1
 #pragma unroll
     for (int s = 0; s < RING; ++s) issue(s, 0, s);
-    vec8 fr[2][2];
+    vec8 fr[3][2];
     rows_loads_in_flight_at_most<(RING - 1) * 4>();
 #pragma unroll
-    for (int e = 0; e < 2; ++e) fr[0][e] = read_frag(0, ring, e);
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) fr[tt][e] = read_frag(tt, ring, e);
     int pos = 0;                                         // ring position of the slot being multiplied
 
     for (int rbi = 0; rbi < nrb; ++rbi) {
@@ -281,14 +306,19 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
             vec8 hb[2][2];                              // H fragments of hidden step ks2, set ks2 & 1
             rows_static_for([&](auto tc) {
                 constexpr int t = decltype(tc)::value;
-                constexpr int cur = t & 1, nxt = cur ^ 1;          // (NST is even: the sets alternate across chunks too)
-                constexpr int tn = t + 1 == NST ? 0 : t + 1;        // the step whose fragments are read now
-                constexpr bool second = (t & 1) != 0;               // second step of its slot: the next step starts a new slot
-                const int pn = pos + 1 == RING ? 0 : pos + 1;
+                constexpr int cur = t % 3, rds = (t + 2) % 3;       // fragment sets: multiplied now / read now (for step t + 2)
+                constexpr int t2 = (t + 2) % NST;                   // the step whose fragments are read now
+                constexpr bool first = (t & 1) == 0;                // first step of its slot
+                const int pn = pos + 1 == RING ? 0 : pos + 1;       // position of the next slot: steps t + 1 (t odd) and t + 2 belong to it
                 // ---- the next slot has landed (all but the youngest RING - 2 slots have)
-                if (second) rows_loads_in_flight_at_most<(RING - 2) * 4>();
-                const char* sbn = ring + (second ? pn : pos) * SLOT;
-                // ---- 4 MFMAs of step t from registers; the 2 fragments of step t + 1 ride under the first 2
+                if (first) rows_loads_in_flight_at_most<(RING - 2) * 4>();
+                // ---- four micro-chunks of one MFMA plus a little other work each (one wave per SIMD: nothing but
+                //      the issue order keeps the matrix pipeline fed): the two fragments of step t + 2 under the first
+                //      two, two of the four loads of the slot RING further down the stream under the last two.  That
+                //      slot takes the position of the slot this step belongs to, whose fragments were read in steps
+                //      t - 2 and t - 1 (t even): before its first load is issued, all LDS reads but the four of this
+                //      step have delivered.
+                constexpr int fi = t / 2 + RING;
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
                     const int e = m >> 1, mt = m & 1;
@@ -299,23 +329,23 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
                         const int ht = 2 * (u & 1) + e;
                         yacc[4 * half + ht][mt] = Mma<T>::mma(fr[cur][e], hb[ks2 & 1][mt], yacc[4 * half + ht][mt]);
                     }
-                    if (m < 2) fr[nxt][m] = read_frag(tn, sbn, m);
-                    if (t >= NST1 && m >= 2) {
-                        // H fragments of the next hidden step, during the last step of this one
-                        constexpr int u = t >= NST1 ? t - NST1 : 0, ks2 = u / (2 * NH2);
-                        if (u % (2 * NH2) == 2 * NH2 - 1 && ks2 + 1 < 4)
-                            hb[(ks2 + 1) & 1][m - 2] = lds_read16<vec8>(hbuf, (hrd ^ (uint32_t)((ks2 + 1) << 5)) + 4096u * (m - 2));
+                    if (m < 2) {
+                        fr[rds][m] = read_frag(t2, ring + pn * SLOT, m);
+                    } else {
+                        if (first && m == 2) rows_lds_reads_older_done<4>();
+                        const int j = 2 * (t & 1) + (m - 2);
+                        if (fi < SPC) issue_one(fi, c, pos, j);
+                        else issue_one(fi - SPC, cn, pos, j);
+                        if (t >= NST1) {
+                            // H fragments of the next hidden step, during the last step of this one (an odd step)
+                            constexpr int u = t >= NST1 ? t - NST1 : 0, ks2 = u / (2 * NH2);
+                            if (u % (2 * NH2) == 2 * NH2 - 1 && ks2 + 1 < 4)
+                                hb[(ks2 + 1) & 1][m - 2] = lds_read16<vec8>(hbuf, (hrd ^ (uint32_t)((ks2 + 1) << 5)) + 4096u * (m - 2));
+                        }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                if (second) {
-                    // ---- every read of this slot has delivered: its position takes the slot RING further down
-                    rows_lds_reads_done();
-                    constexpr int fi = t / 2 + RING;
-                    if (fi < SPC) issue(fi, c, pos);
-                    else issue(fi - SPC, cn, pos);
-                    pos = pn;
-                }
+                if (!first) pos = pn;
                 if (t == NST1 - 1) {
                     // ---- Add exchange of the partial tiles: wave t collects tile t = 2 ht + mt ------------
                     rows_mfma_settle(p);
@@ -364,6 +394,16 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
                     for (int mt = 0; mt < 2; ++mt) hb[0][mt] = lds_read16<vec8>(hbuf, hrd + 4096u * mt);
                 }
             }, std::make_integer_sequence<int, NST>{});
+            // the next chunk's steps 0 and 1 were read into sets NST % 3 and (NST + 1) % 3: rotate them to 0 and 1
+            if constexpr (NST % 3 == 1) {
+                const vec8 a0 = fr[1][0], a1 = fr[1][1];
+                fr[1][0] = fr[2][0]; fr[1][1] = fr[2][1];
+                fr[0][0] = a0; fr[0][1] = a1;
+            } else if constexpr (NST % 3 == 2) {
+                const vec8 a0 = fr[0][0], a1 = fr[0][1];
+                fr[0][0] = fr[2][0]; fr[0][1] = fr[2][1];
+                fr[1][0] = a0; fr[1][1] = a1;
+            }
             // (no barrier at the end of a chunk: the next chunk writes its partial tiles after this chunk's second
             //  barrier, which a wave passes only when all four have summed theirs, and it writes H after its own
             //  first barrier, which a wave reaches only when it has finished reading this chunk's H)
@@ -395,13 +435,17 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
         }
     }
     rows_loads_in_flight_at_most<0>();   // the tail of the stream has landed before LDS is given back
+    if (a.stats && tid == 0) {
+        a.stats[2 * blockIdx.x] = wall_clock64() - t_wall;       // 100 MHz ticks
+        a.stats[2 * blockIdx.x + 1] = clock64() - t_core;        // core clocks
+    }
 }
 
-template <typename T> static const void* rows_fn(int nks, int nt2) {
-    if (nks == 16 && nt2 == 8) return (const void*)fused_rows_kernel<T, 16, 8>;
-    if (nks == 8 && nt2 == 8) return (const void*)fused_rows_kernel<T, 8, 8>;
-    if (nks == 16 && nt2 == 4) return (const void*)fused_rows_kernel<T, 16, 4>;
-    if (nks == 8 && nt2 == 4) return (const void*)fused_rows_kernel<T, 8, 4>;
+template <typename T, bool RAGGED> static const void* rows_fn(int nks, int nt2) {
+    if (nks == 16 && nt2 == 8) return (const void*)fused_rows_kernel<T, 16, 8, RAGGED>;
+    if (nks == 8 && nt2 == 8) return (const void*)fused_rows_kernel<T, 8, 8, RAGGED>;
+    if (nks == 16 && nt2 == 4) return (const void*)fused_rows_kernel<T, 16, 4, RAGGED>;
+    if (nks == 8 && nt2 == 4) return (const void*)fused_rows_kernel<T, 8, 4, RAGGED>;
     return nullptr;
 }
 
@@ -409,7 +453,9 @@ hipError_t launch_fused_rows(int dtype, const RowsArgs& a, int nks, int nt2, int
     if (a.W3 != nullptr) return hipErrorInvalidValue;   // the gated chain is not built in this family
     // what the kernel assumes about its operands
     if (a.K > 64 * nks || a.N2 > 128 * nt2 || grid < 1 || a.M < 1) return hipErrorInvalidValue;
-    const void* fn = dtype == 0 ? rows_fn<__bf16>(nks, nt2) : rows_fn<_Float16>(nks, nt2);
+    const bool ragged = a.K != 64 * nks || (a.N1 & 63) != 0 || a.N2 != 128 * nt2;
+    const void* fn = dtype == 0 ? (ragged ? rows_fn<__bf16, true>(nks, nt2) : rows_fn<__bf16, false>(nks, nt2))
+                                : (ragged ? rows_fn<_Float16, true>(nks, nt2) : rows_fn<_Float16, false>(nks, nt2));
     if (!fn) return hipErrorInvalidValue;
     RowsArgs copy = a;
     void* params[] = {&copy};
