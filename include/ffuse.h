@@ -38,9 +38,10 @@
  *     part is zero, where clean barrier flags lie); a caller that writes into a workspace
  *     itself must hand it over again (ffuse_set_workspace, or any other size in a _ws call).
  *   - Graph capture: a call recorded while `stream` is capturing records its own clearing of
- *     the flags or sums it needs, whatever the library believes about the workspace, so the
- *     graph may be replayed between any other calls on the same workspace (not concurrently
- *     with them).
+ *     the flags or sums it needs, whatever the library believes about the workspace, and from
+ *     then on every call on that workspace clears what it needs too (until the workspace is
+ *     registered or named anew), so the graph may be replayed between any other calls on the
+ *     same workspace (not concurrently with them).
  */
 #ifndef FFUSE_H
 #define FFUSE_H
@@ -217,6 +218,13 @@ int ffuse_traffic_model(const ffuse_plan_t* plan, int dtype, int gated, int64_t 
  * (FFUSE_ERR_NULL, FFUSE_ERR_SHAPE, FFUSE_ERR_PLAN: not a valid two-phase plan for this problem). */
 int ffuse_plan_group_local(const ffuse_plan_t* plan, int dtype, int gated, int64_t M, int64_t K,
                            int64_t N1, int64_t N2);
+/* What the chooser minimises for later fused calls that are not forced and not tuned (Sec. 4.3, Eq. 1-3 put
+ * every level's cost into one objective; this exposes the two ends): FFUSE_OBJECTIVE_TIME (default) -- the
+ * predicted time; FFUSE_OBJECTIVE_BYTES -- among the plans predicted within 35 % of the fastest, the one
+ * that moves the fewest bytes between the L2s and the rest of the memory system (for a chain that shares
+ * the memory system with bandwidth-bound work running beside it). */
+typedef enum { FFUSE_OBJECTIVE_TIME = 0, FFUSE_OBJECTIVE_BYTES = 1 } ffuse_objective_t;
+int ffuse_set_objective(int objective);
 /* Forces every later fused call onto *plan (NULL: back to the chooser).  Also settable with
  * the environment variable FFUSE_FORCE_PLAN="family,bm,bh,bn2,bk,splits,h_level,raster,producers,ring,coherent". */
 int ffuse_force_plan(const ffuse_plan_t* plan);
@@ -272,6 +280,19 @@ int ffuse_plan_table_load(const char* path);
  * status. */
 int ffuse_rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
                      ffuse_plan_t* plans, double* t_pred_s, int capacity);
+
+/* ---- the paper's bookkeeping of its search space, restated (host arithmetic only).
+ *      ffuse_loop_schedule_count: Sec. 4.2 LoopSchedule / Sec. 4.3 table of spatial and temporal partitions --
+ *      the number of schedules of the four loop dimensions (m, n, k, l) with `spatial_dims` of them spatial and
+ *      the rest ordered temporally; 0 asks for the total over 1..4 spatial dimensions.
+ *      ffuse_cluster_exchange: Sec. 4.1 -- for a cluster that splits n, k and l over cls_n, cls_k, cls_l blocks,
+ *      the number of blocks in a shuffle group (cls_l / cls_k) and the number of shuffle groups whose partial
+ *      outputs are reduced (cls_n cls_k / cls_l); FFUSE_ERR_SHAPE when the sizes do not divide.  In these terms
+ *      the two-phase family is a shuffle over the whole device followed by a reduce over `splits` groups, the
+ *      reduce family has cls_shuffle = 1, and the rows family splits k over its four waves (an Add exchange in
+ *      LDS) with nothing left to shuffle or reduce between workgroups. ------------------------------------ */
+int ffuse_loop_schedule_count(int spatial_dims);
+int ffuse_cluster_exchange(int cls_n, int cls_k, int cls_l, int* cls_shuffle, int* cls_reduce);
 
 /* ---- test hook for the failure path of the two-phase family's barrier: later launches wait for
  *      `extra_arrivals` workgroups more than exist (0 = normal) and give up after `spin_limit`

@@ -26,7 +26,8 @@ EXPORTS = [
     "ffuse_tune", "ffuse_plan_lookup", "ffuse_plan_table_clear", "ffuse_conv_chain", "ffuse_conv_chain_f16", "ffuse_rank_plans",
     "ffuse_plan_table_set", "ffuse_plan_table_save", "ffuse_plan_table_load",
     "ffuse_status_string", "ffuse_version",
-    "ffuse_ffn_ws", "ffuse_ffn_unfused_ws", "ffuse_debug_barrier",
+    "ffuse_ffn_ws", "ffuse_ffn_unfused_ws", "ffuse_debug_barrier", "ffuse_set_objective",
+    "ffuse_loop_schedule_count", "ffuse_cluster_exchange",
 ]
 
 
@@ -118,6 +119,12 @@ def lib():
             f = getattr(L, name)
             f.restype = ci
             f.argtypes = [ci, vp, vp, vp, vp, ci, i64, i64, i64, i64, vp, vp, ctypes.c_size_t, vp]
+        L.ffuse_loop_schedule_count.restype = ci
+        L.ffuse_loop_schedule_count.argtypes = [ci]
+        L.ffuse_cluster_exchange.restype = ci
+        L.ffuse_cluster_exchange.argtypes = [ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
+        L.ffuse_set_objective.restype = ci
+        L.ffuse_set_objective.argtypes = [ci]
         L.ffuse_debug_barrier.restype = ci
         L.ffuse_debug_barrier.argtypes = [ci, ctypes.c_uint]
         _lib = L
@@ -195,6 +202,24 @@ def ffuse_ffn_ws(dtype, X, W1, W3, W2, act, Y, workspace, stream=None, check=Tru
 
 def ffuse_ffn_unfused_ws(dtype, X, W1, W3, W2, act, Y, workspace, stream=None, check=True):
     return _call_ws("ffuse_ffn_unfused_ws", dtype, X, W1, W3, W2, act, Y, workspace, stream, check)
+
+
+def ffuse_loop_schedule_count(spatial_dims=0) -> int:
+    return int(lib().ffuse_loop_schedule_count(int(spatial_dims)))
+
+
+def ffuse_cluster_exchange(cls_n, cls_k, cls_l):
+    """Returns (cls_shuffle, cls_reduce)."""
+    a, b = ctypes.c_int(), ctypes.c_int()
+    _check(lib().ffuse_cluster_exchange(int(cls_n), int(cls_k), int(cls_l), ctypes.byref(a), ctypes.byref(b)), "ffuse_cluster_exchange")
+    return a.value, b.value
+
+
+OBJECTIVE_TIME, OBJECTIVE_BYTES = 0, 1
+
+
+def ffuse_set_objective(objective):
+    _check(lib().ffuse_set_objective(int(objective)), "ffuse_set_objective")
 
 
 def ffuse_debug_barrier(extra_arrivals=0, spin_limit=1 << 24):

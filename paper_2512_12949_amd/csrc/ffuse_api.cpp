@@ -26,6 +26,8 @@ struct Workspace {
     size_t zero = 0;                  // bytes at the start known to be zero
     uint32_t* small_flags = nullptr;  // where the two-phase family last left clean barrier flags
     uint64_t used = 0;                // age, for replacement
+    bool in_graph = false;            // a call on this workspace was recorded into a graph: replays the library does
+                                      // not see may dirty it at any time, so nothing above is trusted any more
 };
 
 // geometry of a 3x3 first convolution (ic == 0: the first product is a plain GEMM)
@@ -40,6 +42,7 @@ struct State {
     uint64_t clock = 0;
     uint32_t spin_limit = 1u << 24;   // bounded waits of the two-phase barrier (ffuse_debug_barrier)
     int extra_arrivals = 0;
+    int objective = FFUSE_OBJECTIVE_TIME;
     bool forced = false;
     ffuse_plan_t forced_plan{};
     ffuse_plan_t last_plan{};
@@ -74,7 +77,7 @@ Workspace& workspace_record(void* ptr, size_t bytes) {
         if (w.ptr == ptr && w.bytes == bytes) { w.used = ++g.clock; return w; }
         if (w.used < oldest->used) oldest = &w;
     }
-    *oldest = Workspace{ptr, bytes, 0, nullptr, ++g.clock};
+    *oldest = Workspace{ptr, bytes, 0, nullptr, ++g.clock, false};
     return *oldest;
 }
 // forget what is known about any record that overlaps [ptr, ptr + bytes): its memory is about to change hands
@@ -142,7 +145,8 @@ bool ensure_zero(Workspace& w, size_t need, hipStream_t st) {
 
 // A launch recorded into a graph runs later, any number of times, between other calls: what the library
 // knows about the workspace now says nothing about its state then, so a captured call always records its
-// own clearing and leaves the record "unknown".
+// own clearing -- and from then on every call on that workspace, recorded or not, clears what it needs: a
+// replay may have run since the last call the library saw.
 bool stream_is_capturing(hipStream_t st) {
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     return hipStreamIsCapturing(st, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone;
@@ -175,11 +179,11 @@ ffuse_plan_t lookup_plan(int dtype, int act, int gated, int64_t M, int64_t K, in
     if (it != g.table.end() && ffuse::plan_valid(it->second.plan, dtype, gated, M, K, N1, N2) &&
         (!ws_bytes || ffuse::plan_workspace_bytes(it->second.plan, dtype, gated, M, K, N1, N2) <= ws_bytes))
         return it->second.plan;
-    const auto key = table_key(dtype, gated, K, N1, N2, -M);
+    const auto key = table_key(dtype + 64 * g.objective, gated, K, N1, N2, -M);   // (modelled plans: one slot per objective)
     it = g.table.find(key);
     if (it != g.table.end()) return it->second.plan;
     ffuse_plan_t plan;
-    ffuse::choose_plan(dtype, act, gated, M, K, N1, N2, &plan);
+    ffuse::choose_plan(dtype, act, gated, M, K, N1, N2, &plan, g.objective);
     if (g.table.size() > 4096) g.table.clear();
     g.table[key] = {plan, 0.0};
     return plan;
@@ -254,13 +258,13 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
              const ConvGeom& conv) {
     const int gated = W3 != nullptr;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const bool capturing = stream_is_capturing(st);
-    if (capturing) { w.zero = 0; w.small_flags = nullptr; }
-    // whatever this call leaves behind, a replay of the recorded launch may find something else
+    if (stream_is_capturing(st)) w.in_graph = true;
+    if (w.in_graph) { w.zero = 0; w.small_flags = nullptr; }
+    // (and whatever this call leaves behind, a replay may find something else)
     struct Forget {
-        Workspace& w; bool on;
-        ~Forget() { if (on) { w.zero = 0; w.small_flags = nullptr; } }
-    } forget{w, capturing};
+        Workspace& w;
+        ~Forget() { if (w.in_graph) { w.zero = 0; w.small_flags = nullptr; } }
+    } forget{w};
     ffuse::FusedArgs a{X, W1, W3, W2, nullptr, M, (int)K, (int)N1, (int)N2, act, plan.raster > 0 ? plan.raster : 1};
     if (plan.family == FFUSE_FAMILY_SCALAR) {
         Timer t(st);
@@ -515,7 +519,7 @@ int ffuse_set_workspace(void* dev_ptr, size_t bytes, void* stream) {
     if (bytes % 16) return FFUSE_ERR_SHAPE;
     if (ffuse::launch_zero(dev_ptr, bytes, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return FFUSE_ERR_LAUNCH;
     forget_overlapping(dev_ptr, bytes);
-    g.reg = Workspace{dev_ptr, bytes, bytes, nullptr, 0};
+    g.reg = Workspace{dev_ptr, bytes, bytes, nullptr, 0, false};
     g.exch_err = nullptr;
     return FFUSE_OK;
 }
@@ -547,6 +551,20 @@ int ffuse_plan_group_local(const ffuse_plan_t* plan, int dtype, int gated, int64
         !ffuse::two_phase_geometry(*plan, gated ? 1 : 0, M, N1, N2, &sg))
         return FFUSE_ERR_PLAN;
     return ffuse::two_phase_groups_independent(sg, M, N1, N2) ? 1 : 0;
+}
+
+int ffuse_loop_schedule_count(int spatial_dims) { return ffuse::loop_schedule_count(spatial_dims); }
+
+int ffuse_cluster_exchange(int cls_n, int cls_k, int cls_l, int* cls_shuffle, int* cls_reduce) {
+    if (!cls_shuffle || !cls_reduce) return FFUSE_ERR_NULL;
+    return ffuse::cluster_exchange(cls_n, cls_k, cls_l, cls_shuffle, cls_reduce) ? FFUSE_OK : FFUSE_ERR_SHAPE;
+}
+
+int ffuse_set_objective(int objective) {
+    if (objective != FFUSE_OBJECTIVE_TIME && objective != FFUSE_OBJECTIVE_BYTES) return FFUSE_ERR_ACT;
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.objective = objective;
+    return FFUSE_OK;
 }
 
 int ffuse_force_plan(const ffuse_plan_t* plan) {

@@ -38,7 +38,7 @@ const Device kDevice = {
     /*launch_s*/ 4e-6};
 
 static double cdiv(double a, double b) { return std::ceil(a / b); }
-static constexpr double kRowsEff = 0.40;   // rows family: fraction of the MFMA peak its loop sustains (measured)
+static constexpr double kRowsEff = 0.34;   // rows family: fraction of the MFMA peak its loop sustains (measured: LDS-bound)
 static constexpr double kRowsLdsModel = 4 * 6 * 4096 + 12 * 4096 + 64 * 128;   // rows family: rings, partial tiles, H chunk
 
 bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
@@ -429,10 +429,18 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
             const double full = std::floor(n / d.cus), frac = n / d.cus - full;
             return full + (frac > 0.0 ? std::pow(frac, 0.6) : 0.0);
         };
-        const double m1 = 2.0 * sg.bm * bh1 * g * k / f1 * rounds(items1);
-        const double m2 = 2.0 * sg.bm * 256.0 * sg.ksplit / f2 * rounds(items);
+        // the efficiencies above were measured on items whose inner loop runs over 4096: they contain those items'
+        // ring fill and epilogue (about 10 us of a 256-row item, a tenth of it).  An item with a shorter loop
+        // pays the same fixed part on less work: the part the calibration does not already contain is added.
+        const double item_fixed = sg.bm == 256 ? 10e-6 : 0.0;
+        const auto short_loop = [&](double loop) { return item_fixed * std::max(0.0, 1.0 - loop / 4096.0); };
+        const double m1 = (2.0 * sg.bm * bh1 * g * k / f1 + short_loop(k)) * rounds(items1);
+        const double m2 = (2.0 * sg.bm * 256.0 * sg.ksplit / f2 + short_loop(sg.ksplit)) * rounds(items);
         t->workgroups = d.cus;
-        t->fabric_bytes = b1 + b2 + re1 + re2;
+        // weights (and their repeats per patch), X once and its repeats, the intermediate written through and read
+        // back, the output (through fp32 planes, written and read, when the hidden dimension is split)
+        t->fabric_bytes = b1 + b2 + re1 + re2 + e * m * k + e * m * n1 + e * m * n2 +
+                          (sg.splits > 1 ? 2.0 * 4.0 * m * n2 * sg.splits : 0.0);
         t->t_hbm = t1 + t2;
         t->t_mfma = m1 + m2;
         // launch, barrier, pipeline fills: 13 us.  (Where the barrier is per group the kernel is 2-3 us faster, but
@@ -532,7 +540,7 @@ void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1,
     std::stable_sort(out->begin(), out->end(), [](const RankedPlan& x, const RankedPlan& y) { return x.t_pred < y.t_pred; });
 }
 
-void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* out) {
+void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* out, int objective) {
     std::vector<RankedPlan> r;
     rank_plans(dtype, act, gated, M, K, N1, N2, &r);
     if (r.empty()) {
@@ -540,6 +548,18 @@ void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1
         return;
     }
     *out = r.front().plan;
+    if (objective != FFUSE_OBJECTIVE_BYTES) return;
+    // fewest bytes between the L2s and the rest of the memory system among the plans predicted within
+    // kBytesObjectiveSlack of the fastest (the ranking is sorted: stop at the first plan beyond the slack)
+    double best_bytes = 0.0;
+    bool have = false;
+    for (const RankedPlan& c : r) {
+        if (c.t_pred > kBytesObjectiveSlack * r.front().t_pred) break;
+        ffuse_traffic_t t;
+        traffic_model(c.plan, dtype, gated, M, K, N1, N2, &t);
+        if (!t.feasible) continue;
+        if (!have || t.fabric_bytes < best_bytes) { best_bytes = t.fabric_bytes; *out = c.plan; have = true; }
+    }
 }
 
 size_t plan_workspace_bytes(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
@@ -558,6 +578,27 @@ size_t plan_workspace_bytes(const ffuse_plan_t& p, int dtype, int gated, int64_t
         case FFUSE_FAMILY_ROWS: return 0;
         default: return 0;
     }
+}
+
+// Sec. 4.2 (LoopSchedule) and the table of spatial / temporal partitions in Sec. 4.3: a schedule picks which
+// of the four loop dimensions (m, n, k, l) are spatial -- at least one -- and orders the temporal rest.
+int loop_schedule_count(int spatial_dims) {
+    const auto fact = [](int n) { int f = 1; for (int i = 2; i <= n; ++i) f *= i; return f; };
+    const auto choose = [&](int n, int r) { return fact(n) / (fact(r) * fact(n - r)); };
+    if (spatial_dims < 0 || spatial_dims > 4) return 0;
+    if (spatial_dims > 0) return choose(4, spatial_dims) * fact(4 - spatial_dims);
+    int total = 0;
+    for (int sdim = 1; sdim <= 4; ++sdim) total += choose(4, sdim) * fact(4 - sdim);
+    return total;
+}
+
+// Sec. 4.1: blocks of a shuffle group exchange their slices of the intermediate; the groups that hold
+// partial sums of the same output block are reduced.  cls_shuffle = cls_l / cls_k, cls_reduce = cls_n cls_k / cls_l.
+bool cluster_exchange(int cls_n, int cls_k, int cls_l, int* cls_shuffle, int* cls_reduce) {
+    if (cls_n < 1 || cls_k < 1 || cls_l < 1 || cls_l % cls_k || (cls_n * cls_k) % cls_l) return false;
+    *cls_shuffle = cls_l / cls_k;
+    *cls_reduce = cls_n * cls_k / cls_l;
+    return true;
 }
 
 int m_bin(int64_t M) {

@@ -76,9 +76,18 @@ struct RankedPlan {
     ffuse_plan_t plan;
 };
 void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, std::vector<RankedPlan>* out);
-void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* out);
+// objective: FFUSE_OBJECTIVE_TIME -- the plan with the smallest predicted time; FFUSE_OBJECTIVE_BYTES -- among the
+// plans predicted within kBytesObjectiveSlack of that time, the one that moves the fewest bytes between the L2s
+// and the rest of the memory system
+constexpr double kBytesObjectiveSlack = 1.35;
+void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, ffuse_plan_t* out,
+                 int objective = FFUSE_OBJECTIVE_TIME);
 // Bytes of workspace a plan needs for this problem.
 size_t plan_workspace_bytes(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2);
+// The paper's bookkeeping of the search space (host arithmetic only; the chooser above enumerates the few
+// schedules that survive its pruning rules on this device, these two functions restate the full space)
+int loop_schedule_count(int spatial_dims);   // schedules with that many spatial dimensions (0: all of them)
+bool cluster_exchange(int cls_n, int cls_k, int cls_l, int* cls_shuffle, int* cls_reduce);
 // Bin of the row count for the plan table (Sec. 4.3: plans are chosen offline per range of
 // the dynamic dimension M and looked up at run time): 0 for M <= 16, then one per power of two.
 int m_bin(int64_t M);

@@ -17,8 +17,14 @@
 //   second product: Y[:, cols(w)] += H * W2[chunk, cols(w)], wave w owning N2/4 output columns, H
 //   from LDS and W2 from the same private ring.
 // Every weight element is used by exactly one wave, so the weight stream needs no workgroup barrier:
-// each wave issues LDS-direct loads (buffer_load ... lds) five 4 KB slots ahead into its own ring and
-// waits on its own vmcnt.  The only barriers are the two around the partial-tile exchange.
+// each wave issues LDS-direct loads (buffer_load ... lds) into its own ring of 4 KB slots, four to five
+// slots ahead, and waits on its own vmcnt.  The only barriers are the two around the partial-tile exchange.
+//
+// What bounds it (measured, 32768 x 1024 x 8192 x 1024: LDS busy 91 % of the time, matrix pipelines about
+// half): with 64 rows per workgroup a weight fragment feeds two MFMAs, so per 64 matrix cycles every wave
+// pulls 1 KB through a transposing LDS read -- the whole rate of those reads -- and the same bytes arrive
+// through LDS-direct writes beside them.  The family trades that for memory traffic: the weights are filled
+// into an XCD's L2 once per round of row blocks, X and Y cross the fabric once, nothing else does.
 //
 // Why X sits in registers: measured on this chip, 32 workgroups per XCD that each re-read a private
 // 128 KB row block once per chunk evict each other from the 4 MB L2 completely (2 GiB of refills per
@@ -313,11 +319,12 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
                 // ---- the next slot has landed (all but the youngest RING - 2 slots have)
                 if (first) rows_loads_in_flight_at_most<(RING - 2) * 4>();
                 // ---- four micro-chunks of one MFMA plus a little other work each (one wave per SIMD: nothing but
-                //      the issue order keeps the matrix pipeline fed): the two fragments of step t + 2 under the first
-                //      two, two of the four loads of the slot RING further down the stream under the last two.  That
-                //      slot takes the position of the slot this step belongs to, whose fragments were read in steps
-                //      t - 2 and t - 1 (t even): before its first load is issued, all LDS reads but the four of this
-                //      step have delivered.
+                //      the issue order keeps the matrix pipeline fed): a fragment of step t + 2 under the first and the
+                //      third, one of the four loads of the slot RING further down the stream under the second and the
+                //      fourth (evenly spaced: the load path of the compute unit is as busy as its matrix pipelines).
+                //      That slot takes the position of the slot this step belongs to, whose fragments were read in steps
+                //      t - 2 and t - 1 (t even): before its first load is issued, all LDS reads but the two of this
+                //      step's first fragment have delivered.
                 constexpr int fi = t / 2 + RING;
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
@@ -329,18 +336,18 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
                         const int ht = 2 * (u & 1) + e;
                         yacc[4 * half + ht][mt] = Mma<T>::mma(fr[cur][e], hb[ks2 & 1][mt], yacc[4 * half + ht][mt]);
                     }
-                    if (m < 2) {
-                        fr[rds][m] = read_frag(t2, ring + pn * SLOT, m);
+                    if ((m & 1) == 0) {
+                        fr[rds][m >> 1] = read_frag(t2, ring + pn * SLOT, m >> 1);
                     } else {
-                        if (first && m == 2) rows_lds_reads_older_done<4>();
-                        const int j = 2 * (t & 1) + (m - 2);
+                        if (first && m == 1) rows_lds_reads_older_done<2>();
+                        const int j = 2 * (t & 1) + (m >> 1);
                         if (fi < SPC) issue_one(fi, c, pos, j);
                         else issue_one(fi - SPC, cn, pos, j);
                         if (t >= NST1) {
                             // H fragments of the next hidden step, during the last step of this one (an odd step)
                             constexpr int u = t >= NST1 ? t - NST1 : 0, ks2 = u / (2 * NH2);
                             if (u % (2 * NH2) == 2 * NH2 - 1 && ks2 + 1 < 4)
-                                hb[(ks2 + 1) & 1][m - 2] = lds_read16<vec8>(hbuf, (hrd ^ (uint32_t)((ks2 + 1) << 5)) + 4096u * (m - 2));
+                                hb[(ks2 + 1) & 1][m >> 1] = lds_read16<vec8>(hbuf, (hrd ^ (uint32_t)((ks2 + 1) << 5)) + 4096u * (m >> 1));
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0);
