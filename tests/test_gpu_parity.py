@@ -258,14 +258,15 @@ def test_back_to_back_calls_share_one_workspace():
 
 
 def test_workspace_errors_on_device():
-    w, host, dev = _case("ws", 64, 64, 64, 64, "bf16", ACT_RELU, False)
+    # a gated chain: every family that runs it needs a workspace (the rows family, which needs none, is not gated)
+    w, host, dev = _case("ws", 64, 64, 64, 64, "bf16", ACT_SILU, True)
     Y = torch.empty((64, 64), dtype=torch.bfloat16, device="cuda")
     ff.ffuse_set_workspace(None)
     gu.Workspace.buf = None
-    assert ff.ffuse_ffn(dev["X"], dev["W1"], None, dev["W2"], ACT_RELU, Y, check=False) == -5
+    assert ff.ffuse_ffn(dev["X"], dev["W1"], dev["W3"], dev["W2"], ACT_SILU, Y, check=False) == -5
     small = torch.empty(256, dtype=torch.uint8, device="cuda")
     ff.ffuse_set_workspace(small)
-    assert ff.ffuse_ffn(dev["X"], dev["W1"], None, dev["W2"], ACT_RELU, Y, check=False) == -5
+    assert ff.ffuse_ffn(dev["X"], dev["W1"], dev["W3"], dev["W2"], ACT_SILU, Y, check=False) == -5
     ff.ffuse_set_workspace(None)
 
 
