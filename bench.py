@@ -1,14 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the fused FFN hot path on ONE MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt] [--also llama,large,...] [--no-cpu-baseline]
+    python bench.py --workload large --ablation | --model-check [N]
 
 A step is one pass of the whole fused chain (first product, activation/gate, second
 product, cross-workgroup sum, output conversion) over one batch of seeded synthetic input
 that is already resident in HBM.  Prints ONE JSON line.  `value` is useful TFLOP/s
 (2*M*N1*(g*K+N2) per step); `roofline` prices the dominant kernel, timed with HIP events on
-the launch stream inside the library, against the MI355X peak; `cpu_baseline` times the fp64
-CPU oracle on a bounded row sample of the same workload on this machine's host cores.
+the launch stream inside the library, against the MI355X peak and against what the bare
+matrix-core loop / a streaming read sustain on this device now; `workloads` holds the same
+measurement of the other benchmark configurations; `cpu_baseline` times the fp64 CPU oracle on
+a bounded row sample of the headline workload on this machine's host cores.
 """
 import argparse
 import json
@@ -25,48 +28,47 @@ HBM_PEAK_GBS = 8000.0
 ACT_NAMES = {0: "identity", 1: "relu", 2: "gelu_tanh", 3: "silu"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="gpt")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--oracle-rows", type=int, default=0, help="rows of the CPU-baseline sample (0 = auto)")
-    ap.add_argument("--plan", default="", help="force a plan: family,bm,bh[,raster[,splits[,producers[,ring]]]]")
-    ap.add_argument("--tune", type=int, default=6,
-                    help="before timing, profile the K analytically best plans on the device and use the fastest (0 = model's choice)")
-    ap.add_argument("--model-check", type=int, default=0,
-                    help="instead of the benchmark line: time the model's N best-ranked plans and print predicted vs measured")
-    ap.add_argument("--fused-only", action="store_true",
-                    help="skip the unfused and vendor comparison legs (for profiler runs: the unfused path launches the same kernel one phase at a time, which would mix into the per-kernel averages)")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also launch one plain 256 MiB device copy (reference for HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path would shard by rows or by hidden slices; that is not built).", file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
-    import torch
-    from paper_2512_12949_amd import binding as ff
-    from paper_2512_12949_amd import inputs
-
-    torch.cuda.set_device(0)
-    if args.workload in inputs.CONV_WORKLOADS:
-        return conv_main(args, ff, inputs, np, torch)
-    w = inputs.WORKLOADS[args.workload]
-    host = inputs.make(w)
-
+def upload(w, host, np, torch):
     def up(a):
         if a is None:
             return None
         if w.dtype == "bf16":
             return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
         return torch.from_numpy(a).cuda()
+    return {k: up(v) for k, v in host.items()}
 
-    dev = {k: up(v) for k, v in host.items()}
+
+def calibrate(ff, torch):
+    """What the device sustains, measured now: the bare matrix-core issue loop over ~2 ms (the clock
+    the power limit allows a kernel that does nothing else) and a streaming read of 1 GiB."""
+    scratch = torch.zeros(16384, dtype=torch.uint8, device="cuda")
+    buf = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+    def mfma(dtype, iters):   # best of three: the rate wanders by +-8 % with the chip's temperature and power state
+        return max(ff.ffuse_calibrate(ff.CAL_MFMA, dtype, None, iters, scratch) for _ in range(3)) * 1e-12
+    cal = {"mfma_bf16_burst_tflops": mfma(ff.DT_BF16, 256), "mfma_bf16_tflops": mfma(ff.DT_BF16, 16384),
+           "mfma_f16_tflops": mfma(ff.DT_F16, 16384),
+           "read_gbs": ff.ffuse_calibrate(ff.CAL_READ, ff.DT_BF16, buf, 4, scratch) * 1e-9,
+           "kind": "ffuse_calibrate, best of 3: 32x32x16 issue loop on every SIMD over pseudo-random operands, 16384 rounds of 4 "
+                   "products (about 2 ms: the power-limited rate) and a burst of 256 rounds (about 30 us); streaming read of 1 GiB, 4 passes"}
+    del buf
+    return cal
+
+
+def traffic_record(name):
+    """L2<->fabric bytes per call from the committed counter runs (rocprofv3 cannot run inside this process)."""
+    tf = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        return json.load(open(tf)).get(name, {})
+    except Exception:
+        return {}
+
+
+def measure(name, args, ff, inputs, np, torch, cal, *, steps, warmup, tune, headline):
+    """One workload: the fused call, the library's own two-launch path, (headline only) the vendor
+    library's chain; returns the record and what the CPU baseline needs."""
+    w = inputs.WORKLOADS[name]
+    host = inputs.make(w)
+    dev = upload(w, host, np, torch)
     dt = ff.DTYPE_CODE[w.dtype]
     tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[w.dtype]
     nws = max(ff.ffuse_workspace_bytes(dt, w.gated, w.M, w.K, w.N1, w.N2, False),
@@ -74,51 +76,82 @@ def main():
     ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
     ff.ffuse_set_workspace(ws)
     Y = torch.empty((w.M, w.N2), dtype=tdt, device="cuda")
-    if args.plan:
+    plan_from = "model"
+    if args.plan and headline:
         v = [int(x) for x in args.plan.split(",")]
         v += [0] * (7 - len(v))
         ff.ffuse_force_plan(ff.make_plan(v[0], v[1], v[2], bn2=256 if v[0] == 2 else 128, raster=v[3] or 4, splits=v[4],
                                          producers=v[5], ring=v[6]))
-    elif args.tune > 0 and w.dtype != "f32":
+        plan_from = "forced"
+    elif tune > 0 and w.dtype != "f32" and not args.model_check:
         # offline step of the method (plans are fixed per M bin ahead of time): not part of the timed region
-        ff.ffuse_tune(dt, dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y, top_k=args.tune, reps=5)
+        ff.ffuse_tune(dt, dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y, top_k=tune, reps=5)
+        plan_from = "tuned top-%d" % tune
     fused, unfused = ff.FUSED[w.dtype], ff.UNFUSED[w.dtype]
     if args.model_check > 0:
-        return model_check(args, ff, w, dev, Y, dt, nws, torch)
-
-    def step(fn):
-        fn(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y)
+        return model_check(args, ff, w, dev, Y, dt, nws, torch), None
+    if args.ablation:
+        return ablation(args, ff, w, dev, Y, dt, torch), None
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
-            step(fn)
+            fn(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y)
         torch.cuda.synchronize()
         ff.ffuse_profile_read()
         ff.ffuse_profile_enable(True)
         t0 = time.perf_counter()
         for _ in range(steps):
-            step(fn)
+            fn(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y)
         torch.cuda.synchronize()
         dt_s = time.perf_counter() - t0
         ff.ffuse_profile_enable(False)
         kms, kn = ff.ffuse_profile_read()
         return dt_s / steps, (kms / kn * 1e-3 if kn else float("nan"))
 
+    if args.fused_only and args.leg == "unfused":
+        fused = unfused
+    elif args.fused_only and args.leg == "bytes":
+        ff.ffuse_set_objective(ff.OBJECTIVE_BYTES)
+        ff.ffuse_force_plan(ff.ffuse_choose_plan(dt, w.act, w.gated, w.M, w.K, w.N1, w.N2))
+        ff.ffuse_set_objective(ff.OBJECTIVE_TIME)
+        plan_from = "bytes objective"
     print(f"[bench] {w.name}: timing the fused call", file=sys.stderr, flush=True)
-    t_fused, k_fused = timed(fused, args.steps, args.warmup)
+    t_fused, k_fused = timed(fused, steps, warmup)
+    ff.ffuse_sync_status()
     plan = ff.ffuse_last_plan()
-    model = ff.ffuse_traffic_model(plan, dt, w.gated, w.M, w.K, w.N1, w.N2).as_dict()
+    try:
+        model = ff.ffuse_traffic_model(plan, dt, w.gated, w.M, w.K, w.N1, w.N2).as_dict()
+    except ff.FfuseError:       # (--leg unfused: the two-launch path records the unfused family, which has no fused model)
+        model = {"hbm_bytes": None, "reduce_bytes": None, "fabric_bytes": None, "t_pred": float("nan")}
     Y_fused = Y.clone()
     t_unf = k_unf = diff = float("nan")
     if not args.fused_only:
-        print(f"[bench] {w.name}: timing the unfused call", file=sys.stderr, flush=True)
-        t_unf, k_unf = timed(unfused, max(3, args.steps // 2), 2)
+        print(f"[bench] {w.name}: timing the two-launch path", file=sys.stderr, flush=True)
+        t_unf, k_unf = timed(unfused, max(3, steps // 2), 2)
         diff = float((Y_fused.float() - Y.float()).abs().max() / Y.float().abs().max())
+
+    # the byte-minimal schedule, where the chooser's two objectives disagree (the intermediate kept on chip
+    # at the price of a slower loop): timed beside the time-optimal one
+    by_bytes = None
+    if w.dtype != "f32" and not args.fused_only and plan_from != "forced":
+        ff.ffuse_set_objective(ff.OBJECTIVE_BYTES)
+        pb = ff.ffuse_choose_plan(dt, w.act, w.gated, w.M, w.K, w.N1, w.N2)
+        ff.ffuse_set_objective(ff.OBJECTIVE_TIME)
+        if pb.as_dict() != plan.as_dict():
+            ff.ffuse_force_plan(pb)
+            if fused(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y, check=False) == 0:
+                t_b, k_b = timed(fused, max(3, steps // 2), 2)
+                mb = ff.ffuse_traffic_model(pb, dt, w.gated, w.M, w.K, w.N1, w.N2).as_dict()
+                by_bytes = {"plan": pb.as_dict(), "ms_per_step": t_b * 1e3, "kernel_ms": k_b * 1e3,
+                            "tflops": float(w.flops()) / t_b * 1e-12, "model_fabric": mb["fabric_bytes"], "model_hbm": mb["hbm_bytes"],
+                            "max_rel_diff_vs_fused": float((Y_fused.float() - Y.float()).abs().max() / Y_fused.float().abs().max()),
+                            "measured_fabric_bytes": traffic_record(w.name).get("bytes_objective_kernel_bytes")}
+            ff.ffuse_force_plan(None)
 
     # context: the vendor library's unfused chain on the same tensors (hipBLASLt GEMMs through
     # torch.matmul plus torch's elementwise kernels); not part of the hot path
     t_vendor = None
-    if w.dtype != "f32" and not args.fused_only:
+    if w.dtype != "f32" and not args.fused_only and headline:
         def vendor_step():
             h = torch.matmul(dev["X"], dev["W1"])
             if w.act == 1:
@@ -135,7 +168,7 @@ def main():
         for _ in range(10):
             vendor_step()
         torch.cuda.synchronize()
-        nv = max(3, args.steps // 2)
+        nv = max(3, steps // 2)
         best = float("inf")
         for _ in range(3):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -148,39 +181,100 @@ def main():
         t_vendor = best
 
     flops = float(w.flops())
-    value = flops / t_fused * 1e-12
     decode = w.M <= 128 and flops / w.q_min() < 300.0
+    # the priced time is every kernel of the fused call (a split plan's plane sum included), timed with
+    # events on the launch stream inside the library
     if decode:
         roof = {"bound": "hbm", "achieved": w.q_min() / k_fused * 1e-9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+        cal_peak = cal["read_gbs"] if cal else None
     else:
         roof = {"bound": "mfma", "achieved": flops / k_fused * 1e-12, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
+        cal_peak = cal["mfma_f16_tflops" if w.dtype == "f16" else "mfma_bf16_tflops"] if cal else None
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
-    tf = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tf):
-        try:
-            roof["traffic"] = json.load(open(tf)).get(w.name, {}).get("fused_kernel_bytes")
-        except Exception:
-            pass
+    tr = traffic_record(w.name)
+    roof["traffic"] = tr.get("fused_kernel_bytes")
     roof["kernel_ms"] = k_fused * 1e3
-
-    out = {
-        "metric": "fused FFN TFLOP/s (% MFMA peak) + HBM bytes vs unfused, 1 MI355X",
-        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": t_fused * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name}: M={w.M} K={w.K} N1={w.N1} N2={w.N2} {w.dtype} "
-                               f"{ACT_NAMES[w.act]}{' gated' if w.gated else ''}",
-                   "plan": plan.as_dict(), "plan_from": "forced" if args.plan else ("tuned top-%d" % args.tune if args.tune > 0 and w.dtype != "f32" else "model")},
-        "pct_mfma_peak": 100.0 * value / MFMA_PEAK_TFLOPS,
+    roof["calibrated_peak"] = cal_peak
+    roof["frac_of_calibrated"] = None if not cal_peak else roof["achieved"] / cal_peak
+    rec = {
+        "workload": f"{w.name}: M={w.M} K={w.K} N1={w.N1} N2={w.N2} {w.dtype} {ACT_NAMES[w.act]}{' gated' if w.gated else ''}",
+        "plan": plan.as_dict(), "plan_from": plan_from,
+        "ms_per_step": t_fused * 1e3, "tflops": flops / t_fused * 1e-12, "pct_mfma_peak": 100.0 * flops / t_fused * 1e-12 / MFMA_PEAK_TFLOPS,
         "roofline": roof,
         "unfused": None if args.fused_only else {
             "ms_per_step": t_unf * 1e3, "tflops": flops / t_unf * 1e-12, "kernels_ms": k_unf * 1e3,
-            "max_rel_diff_vs_fused": diff, "kind": "the same kernel and tile plan as the model's best two-phase plan, one launch per phase"},
+            "max_rel_diff_vs_fused": diff, "traffic": tr.get("two_launch_bytes"),
+            "kind": "the same kernel and tile plan as the model's best two-phase plan, one launch per phase"},
+        "bytes_objective": by_bytes,
         "bytes": {"q_min": w.q_min(), "q_unfused": w.q_unfused(), "model_hbm": model["hbm_bytes"],
                   "model_reduce": model["reduce_bytes"], "model_fabric": model["fabric_bytes"]},
         "model_t_pred_ms": model["t_pred"] * 1e3,
         "vendor_unfused_ms": None if t_vendor is None else t_vendor * 1e3,
+    }
+    ff.ffuse_set_workspace(None)
+    return rec, (w, host, Y_fused)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="gpt")
+    ap.add_argument("--also", default="llama,large,decode16,decode64",
+                    help="further workloads measured after the headline one (shorter runs), reported under `workloads`; '' for none")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--oracle-rows", type=int, default=0, help="rows of the CPU-baseline sample (0 = auto)")
+    ap.add_argument("--plan", default="", help="force a plan: family,bm,bh[,raster[,splits[,producers[,ring]]]]")
+    ap.add_argument("--tune", type=int, default=6,
+                    help="before timing, profile the K analytically best plans on the device and use the fastest (0 = model's choice)")
+    ap.add_argument("--model-check", type=int, nargs="?", const=11, default=0,
+                    help="instead of the benchmark line: time the model's N best-ranked plans (11 when no N is given, as the paper's top-K) and print predicted vs measured")
+    ap.add_argument("--ablation", action="store_true",
+                    help="instead of the benchmark line: the chosen fused plan against untuned fused plans, the workgroup-local schedule and the unfused paths")
+    ap.add_argument("--fused-only", action="store_true",
+                    help="only the headline workload's fused call (for profiler runs: the other legs launch the same kernels, which would mix into the per-kernel averages)")
+    ap.add_argument("--leg", default="fused", choices=["fused", "unfused", "bytes"],
+                    help="with --fused-only: which call the timed loop runs -- the fused call, the library's two-launch path, or the fused call under the bytes objective")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain 256 MiB device copy (reference for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path would shard by rows or by hidden slices; that is not built).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2512_12949_amd import binding as ff
+    from paper_2512_12949_amd import inputs
+
+    torch.cuda.set_device(0)
+    if args.workload in inputs.CONV_WORKLOADS:
+        return conv_main(args, ff, inputs, np, torch)
+    side_run = args.model_check > 0 or args.ablation
+    cal = None if (args.fused_only or side_run) else calibrate(ff, torch)
+    rec, state = measure(args.workload, args, ff, inputs, np, torch, cal, steps=args.steps, warmup=args.warmup, tune=args.tune, headline=True)
+    if side_run:
+        print(json.dumps(rec))
+        return
+    w, host, Y_fused = state
+    flops = float(w.flops())
+
+    out = {
+        "metric": "fused FFN TFLOP/s (% MFMA peak) + HBM bytes vs unfused, 1 MI355X",
+        "value": rec["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": rec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": rec["workload"], "plan": rec["plan"], "plan_from": rec["plan_from"]},
+        "pct_mfma_peak": rec["pct_mfma_peak"],
+        "roofline": rec["roofline"],
+        "unfused": rec["unfused"],
+        "bytes_objective": rec["bytes_objective"],
+        "bytes": rec["bytes"],
+        "model_t_pred_ms": rec["model_t_pred_ms"],
+        "vendor_unfused_ms": rec["vendor_unfused_ms"],
+        "calibration": cal,
     }
 
     if not args.no_cpu_baseline:
@@ -219,6 +313,15 @@ def main():
                                "sample": f"{len(rows)} of {w.M} rows, all {w.N2} columns" +
                                          (f", {passes} passes" if passes > 1 else "") + f", {t_cpu:.1f} s"}
         out["max_rel_err_vs_oracle"] = rel
+    del state, host, Y_fused
+    # the other benchmark configurations, each a shorter run of the same measurement (no vendor leg, no CPU leg)
+    if not args.fused_only and args.also:
+        out["workloads"] = {}
+        for name in [n for n in args.also.split(",") if n and n != args.workload]:
+            torch.cuda.empty_cache()
+            r, st = measure(name, args, ff, inputs, np, torch, cal, steps=max(5, args.steps // 2), warmup=3, tune=min(args.tune, 4), headline=False)
+            del st
+            out["workloads"][name] = r
     if args.copy_calibration:
         # one plain elementwise copy kernel of known size: reads 256 MiB, writes 256 MiB
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
@@ -228,6 +331,67 @@ def main():
         torch.cuda.synchronize()
     ff.ffuse_set_workspace(None)
     print(json.dumps(out))
+
+
+def ablation(args, ff, w, dev, Y, dt, torch):
+    """The evaluation's ablation in this build's terms: the chosen plan (model + on-device tuning of its
+    best few), fused plans nobody chose (the middle and the end of the model's ranking: what an
+    untuned configuration costs), the schedule without any cross-workgroup exchange (the rows family,
+    where the shape allows it), the library's two-launch path and the vendor library's chain."""
+    fn, unf = ff.FUSED[w.dtype], ff.UNFUSED[w.dtype]
+    flops = float(w.flops())
+
+    def time_call(f, steps):
+        if f(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y, check=False) != 0 or ff.ffuse_sync_status(check=False) != 0:
+            return None
+        for _ in range(3):
+            f(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            f(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    legs = []
+
+    def leg(kind, plan, ms):
+        if ms is None:
+            return
+        d = None if plan is None else {k: plan.as_dict()[k] for k in ("family", "bm", "bh", "bk", "splits", "raster", "producers")}
+        legs.append({"kind": kind, "plan": d, "ms": ms, "tflops": flops / ms * 1e-9})
+
+    ff.ffuse_force_plan(None)
+    ms = time_call(fn, args.steps)
+    leg("fused, chosen plan", ff.ffuse_last_plan(), ms)
+    ranked = ff.ffuse_rank_plans(dt, w.act, w.gated, w.M, w.K, w.N1, w.N2)
+    for kind, idx in (("fused, the model's first choice untuned", 0), ("fused, middle of the ranking", len(ranked) // 2), ("fused, last of the ranking", len(ranked) - 1)):
+        ff.ffuse_force_plan(ranked[idx][0])
+        leg(kind, ranked[idx][0], time_call(fn, max(3, args.steps // 2)))
+    rows = [p for p, _ in ranked if p.family == ff.FAMILY_ROWS]
+    if rows:
+        ff.ffuse_force_plan(rows[0])
+        leg("fused, no cross-workgroup exchange (rows family)", rows[0], time_call(fn, max(3, args.steps // 2)))
+    ff.ffuse_force_plan(None)
+    leg("unfused, the library's two launches", None, time_call(unf, max(3, args.steps // 2)))
+
+    def vendor(X, W1, W3, W2, act, Y, check=True):
+        h = torch.matmul(X, W1)
+        h = torch.relu(h) if act == 1 else torch.nn.functional.gelu(h, approximate="tanh") if act == 2 else torch.nn.functional.silu(h) if act == 3 else h
+        if W3 is not None:
+            h = h * torch.matmul(X, W3)
+        torch.matmul(h, W2, out=Y)
+        return 0
+    for _ in range(8):
+        vendor(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y)
+    leg("unfused, vendor library chain", None, time_call(vendor, max(3, args.steps // 2)))
+    ff.ffuse_set_workspace(None)
+    base = legs[0]["ms"]
+    for l in legs:
+        l["vs_chosen"] = l["ms"] / base
+    return {"workload": w.name, "ablation": legs}
 
 
 def model_check(args, ff, w, dev, Y, dt, nws, torch):
@@ -275,7 +439,7 @@ def model_check(args, ff, w, dev, Y, dt, nws, torch):
            "regret_of_first_choice": rows[0]["measured_us"] / best - 1.0,
            "best_measured_is_model_rank": 1 + min(range(n), key=lambda i: rows[i]["measured_us"]), "plans": rows}
     ff.ffuse_set_workspace(None)
-    print(json.dumps(out))
+    return out
 
 
 def conv_main(args, ff, inputs, np, torch):

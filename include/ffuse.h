@@ -169,6 +169,20 @@ int ffuse_ffn_unfused_ws(int dtype, const void* X, const void* W1, const void* W
                          int act, int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- for callers that cannot allocate device memory and have no workspace to hand over (code under
+ *      HIP graph capture, tight serving loops, harnesses that forbid allocation): ffuse_ffn_ws with the
+ *      workspace built into the library -- 32 MiB of device memory per GPU that the library's code object
+ *      brings with it and that stays until the process ends.  The call allocates and frees nothing, on the
+ *      host side of the device or on the device.  It runs the best-ranked plan whose workspace fits those
+ *      32 MiB (all the m = 128 shapes of the paper's tables, the decode shapes, and every shape the rows
+ *      family runs, which needs none) and returns FFUSE_ERR_WORKSPACE when no plan for the problem fits.
+ *      All calls on one GPU share that GPU's memory, which keeps what the last call left in it (each call
+ *      clears what it needs to start from zero, on `stream`): calls that overlap in time on one GPU
+ *      race.  The first call on a device resolves the address of the memory and must not be made
+ *      while a stream of that device is capturing; later calls may be captured. ------------------- */
+int ffuse_ffn_static(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act,
+                     int64_t M, int64_t K, int64_t N1, int64_t N2, void* Y, void* stream);
+
 /* ---- the unfused comparison path (Evaluation, "Performance Analysis": the baseline writes
  *      the intermediate to global memory and reads it back): GEMM + activation/gate into a
  *      workspace-resident H[M][N1] in the operand type, then H * W2, as two kernel launches
@@ -206,7 +220,8 @@ size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t
                              int unfused);
 int ffuse_set_workspace(void* dev_ptr, size_t bytes, void* stream);
 
-/* ---- host-side schedule chooser and traffic model (Sec. 4.2 / 4.3); no device work. ---- */
+/* ---- host-side schedule chooser and traffic model (Sec. 4.2 / 4.3); no device work.
+ *      ffuse_choose_plan: the model's choice under the objective in force (ffuse_set_objective). ---- */
 int ffuse_choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
                       ffuse_plan_t* out);
 int ffuse_traffic_model(const ffuse_plan_t* plan, int dtype, int gated, int64_t M, int64_t K,
@@ -309,6 +324,19 @@ int ffuse_profile_enable(int on);
 int ffuse_profile_read(double* kernel_ms_total, int64_t* launches);
 
 const char* ffuse_status_string(int status);
+/* ---- calibration probes (Sec. 4.4: the cost model prices every level with a bandwidth; these measure
+ *      the two ends on the device at hand).  FFUSE_CAL_MFMA: every SIMD of the device issues `iters`
+ *      rounds of four independent 32x32x16 products of `dtype` (bf16 or fp16) on pseudo-random operands and
+ *      nothing else -- the matrix rate no kernel can exceed at the clock the power limit allows; *result is
+ *      flop/s (buf and bytes are ignored).  FFUSE_CAL_READ: `buf` (device, 16-byte aligned, `bytes` a
+ *      multiple of 16) is streamed through the device once as a warm-up and `iters` more times, timed;
+ *      *result is bytes/s.  `scratch16k` is 16 KiB of device memory the probes may write (they do not in
+ *      practice); `result` is a host pointer.  The call times its own launches with events on `stream` and
+ *      waits for them.  Status as elsewhere (FFUSE_ERR_ACT: unknown probe or dtype). --------------------- */
+enum { FFUSE_CAL_MFMA = 0, FFUSE_CAL_READ = 1 };
+int ffuse_calibrate(int what, int dtype, const void* buf, int64_t bytes, int64_t iters, void* scratch16k,
+                    double* result, void* stream);
+
 int ffuse_version(void);
 
 #ifdef __cplusplus

@@ -27,7 +27,7 @@ EXPORTS = [
     "ffuse_plan_table_set", "ffuse_plan_table_save", "ffuse_plan_table_load",
     "ffuse_status_string", "ffuse_version",
     "ffuse_ffn_ws", "ffuse_ffn_unfused_ws", "ffuse_debug_barrier", "ffuse_set_objective",
-    "ffuse_loop_schedule_count", "ffuse_cluster_exchange",
+    "ffuse_loop_schedule_count", "ffuse_cluster_exchange", "ffuse_ffn_static", "ffuse_calibrate",
 ]
 
 
@@ -125,6 +125,10 @@ def lib():
         L.ffuse_cluster_exchange.argtypes = [ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
         L.ffuse_set_objective.restype = ci
         L.ffuse_set_objective.argtypes = [ci]
+        L.ffuse_ffn_static.restype = ci
+        L.ffuse_ffn_static.argtypes = [ci, vp, vp, vp, vp, ci, i64, i64, i64, i64, vp, vp]
+        L.ffuse_calibrate.restype = ci
+        L.ffuse_calibrate.argtypes = [ci, ci, vp, i64, i64, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.ffuse_debug_barrier.restype = ci
         L.ffuse_debug_barrier.argtypes = [ci, ctypes.c_uint]
         _lib = L
@@ -220,6 +224,28 @@ OBJECTIVE_TIME, OBJECTIVE_BYTES = 0, 1
 
 def ffuse_set_objective(objective):
     _check(lib().ffuse_set_objective(int(objective)), "ffuse_set_objective")
+
+
+def ffuse_ffn_static(dtype, X, W1, W3, W2, act, Y, stream=None, check=True):
+    """The fused chain in the library's built-in 32 MiB of scratch memory: nothing is allocated."""
+    M, K = X.shape
+    N1, N2 = W2.shape
+    rc = lib().ffuse_ffn_static(int(dtype), _ptr(X), _ptr(W1), _ptr(W3), _ptr(W2), int(act), M, K, N1, N2, _ptr(Y), _stream(stream))
+    if check:
+        _check(rc, "ffuse_ffn_static")
+    return rc
+
+
+CAL_MFMA, CAL_READ = 0, 1
+
+
+def ffuse_calibrate(what, dtype=DT_BF16, buf=None, iters=1, scratch=None, stream=None):
+    """flop/s of the bare matrix-core issue loop (CAL_MFMA) or bytes/s of a streaming read of `buf` (CAL_READ)."""
+    out = ctypes.c_double(0.0)
+    nbytes = 0 if buf is None else buf.numel() * buf.element_size()
+    _check(lib().ffuse_calibrate(int(what), int(dtype), _ptr(buf), nbytes, int(iters), _ptr(scratch), ctypes.byref(out), _stream(stream)),
+           "ffuse_calibrate")
+    return out.value
 
 
 def ffuse_debug_barrier(extra_arrivals=0, spin_limit=1 << 24):

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libffuse.so")
-SOURCES = ["ffuse_kernels.hip", "ffuse_two_phase.hip", "ffuse_rows.hip", "ffuse_kernels_f32.hip", "ffuse_plan.cpp", "ffuse_api.cpp"]
+SOURCES = ["ffuse_kernels.hip", "ffuse_two_phase.hip", "ffuse_rows.hip", "ffuse_kernels_f32.hip", "ffuse_calib.hip", "ffuse_plan.cpp", "ffuse_api.cpp"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-fno-gpu-rdc"]
 

@@ -43,6 +43,7 @@ struct State {
     uint32_t spin_limit = 1u << 24;   // bounded waits of the two-phase barrier (ffuse_debug_barrier)
     int extra_arrivals = 0;
     int objective = FFUSE_OBJECTIVE_TIME;
+    bool no_alloc_call = false;   // inside ffuse_ffn_static: nothing that could allocate (no profiling events)
     bool forced = false;
     ffuse_plan_t forced_plan{};
     ffuse_plan_t last_plan{};
@@ -98,6 +99,7 @@ int check_arch() {
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return FFUSE_ERR_LAUNCH;
         g.arch_ok = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 0;
         g.cus = prop.multiProcessorCount;
+        ffuse::set_device_units(g.cus);
     }
     return g.arch_ok == 1 ? FFUSE_OK : FFUSE_ERR_ARCH;
 }
@@ -156,7 +158,7 @@ struct Timer {  // brackets the dominant kernel with events when profiling is on
     hipStream_t st;
     hipEvent_t a = nullptr, b = nullptr;
     explicit Timer(hipStream_t s) : st(s) {
-        if (g.profiling && hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) (void)hipEventRecord(a, st);
+        if (g.profiling && !g.no_alloc_call && hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) (void)hipEventRecord(a, st);
     }
     void stop() {
         if (a && b) {
@@ -482,6 +484,65 @@ int ffuse_ffn_unfused_ws(int dtype, const void* X, const void* W1, const void* W
     return run_unfused_locked(dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, workspace ? workspace_record(workspace, workspace_bytes) : none, stream);
 }
 
+}  // extern "C"
+
+// ---- the entry point that allocates nothing ---------------------------------------------------------
+// Its workspace is this array: device memory that exists from the moment the library is loaded on a
+// device until the process ends (every device the library runs on holds its own copy, at its own
+// address).  In host code the name `scratch` is a stand-in, not a device address: the address is asked
+// for once per device and only that pointer is ever used.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+Workspace static_ws[kMaxDevices];   // per device: address of its copy of `scratch`, and what the library left there
+
+// the record of the current device's scratch array (address resolved on first use); the caller holds the lock
+int static_workspace(Workspace** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FFUSE_ERR_LAUNCH;
+    Workspace& w = static_ws[dev];
+    if (!w.ptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return FFUSE_ERR_LAUNCH;
+        w = Workspace{ptr, kStaticScratchBytes, 0, nullptr, 0, false};   // (nothing assumed about its contents)
+    }
+    *out = &w;
+    return FFUSE_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int ffuse_ffn_static(int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act, int64_t M, int64_t K,
+                     int64_t N1, int64_t N2, void* Y, void* stream) {
+    if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F32) return FFUSE_ERR_ACT;
+    int rc = validate(X, W1, W3, W2, act, M, K, N1, N2, Y, dtype == FFUSE_DT_F32 ? 4 : 2);
+    if (rc != FFUSE_OK) return rc;
+    std::lock_guard<std::mutex> lock(g.mu);
+    if ((rc = check_arch()) != FFUSE_OK) return rc;
+    Workspace* w = nullptr;
+    if ((rc = static_workspace(&w)) != FFUSE_OK) return rc;
+    // the best-ranked plan whose workspace fits the array (looked up after the first call for a shape)
+    const int gated = W3 != nullptr;
+    const auto key = table_key(dtype + 128, gated, K, N1, N2, -M);
+    auto it = g.table.find(key);
+    if (it == g.table.end()) {
+        std::vector<ffuse::RankedPlan> ranked;
+        ffuse::rank_plans(dtype, act, gated, M, K, N1, N2, &ranked);
+        const ffuse::RankedPlan* fit = nullptr;
+        for (const auto& r : ranked)
+            if (ffuse::plan_workspace_bytes(r.plan, dtype, gated, M, K, N1, N2) <= kStaticScratchBytes) { fit = &r; break; }
+        if (!fit) return FFUSE_ERR_WORKSPACE;     // the problem is too large for the built-in scratch memory
+        if (g.table.size() > 4096) g.table.clear();
+        it = g.table.insert({key, {fit->plan, 0.0}}).first;
+    }
+    g.no_alloc_call = true;
+    rc = run_plan(it->second.plan, dtype, X, W1, W3, W2, act, M, K, N1, N2, Y, *w, stream);
+    g.no_alloc_call = false;
+    return rc;
+}
+
 int ffuse_debug_barrier(int extra_arrivals, unsigned int spin_limit) {
     if (extra_arrivals < 0 || extra_arrivals > 1024 || spin_limit < 1) return FFUSE_ERR_SHAPE;
     std::lock_guard<std::mutex> lock(g.mu);
@@ -528,7 +589,12 @@ int ffuse_choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64
     if (!out) return FFUSE_ERR_NULL;
     if (dtype < FFUSE_DT_BF16 || dtype > FFUSE_DT_F32 || act < FFUSE_ACT_IDENTITY || act > FFUSE_ACT_SILU) return FFUSE_ERR_ACT;
     if (M < 1 || K < 8 || N1 < 8 || N2 < 8 || (K % 8) || (N1 % 8) || (N2 % 8)) return FFUSE_ERR_SHAPE;
-    ffuse::choose_plan(dtype, act, gated ? 1 : 0, M, K, N1, N2, out);
+    int objective;
+    {
+        std::lock_guard<std::mutex> lock(g.mu);
+        objective = g.objective;
+    }
+    ffuse::choose_plan(dtype, act, gated ? 1 : 0, M, K, N1, N2, out, objective);
     return FFUSE_OK;
 }
 

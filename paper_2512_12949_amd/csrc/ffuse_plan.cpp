@@ -24,7 +24,7 @@ namespace ffuse {
 
 // Calibrated on an MI355X (standalone probes: MFMA issue loop, streaming read, LDS b128
 // read, coalesced fp32 atomic adds).  Datasheet peaks are 2516 TFLOP/s and 8 TB/s.
-const Device kDevice = {
+Device kDevice = {
     /*cus*/ 256, /*xcds*/ 8,
     /*mfma_flops*/ 2.40e15,     // 32x32x16 issue loop
     /*hbm_bw*/ 5.6e12,          // streaming read of 2 GiB
@@ -36,6 +36,15 @@ const Device kDevice = {
     /*mall_bytes*/ 256.0 * 1024 * 1024,
     /*mfma_eff*/ 0.45,          // measured: the register-staged 256x256x64 main loop
     /*launch_s*/ 4e-6};
+
+void set_device_units(int cus) {
+    if (cus <= 0 || cus == kDevice.cus) return;
+    const double f = (double)cus / kDevice.cus;
+    kDevice.mfma_flops *= f;
+    kDevice.l2_bw *= f;
+    kDevice.lds_bw *= f;
+    kDevice.cus = cus;
+}
 
 static double cdiv(double a, double b) { return std::ceil(a / b); }
 static constexpr double kRowsEff = 0.34;   // rows family: fraction of the MFMA peak its loop sustains (measured: LDS-bound)

@@ -22,7 +22,10 @@ struct Device {
     double mfma_eff;     // fraction of mfma_flops the library's main loop sustains
     double launch_s;     // fixed cost of one kernel launch
 };
-extern const Device kDevice;
+extern Device kDevice;              // starts as a whole MI355X (256 CUs in 8 XCDs)
+// Unit counts of the device the library runs on (a partitioned or harvested part has fewer): the
+// per-unit rates stay, everything that scales with the unit count is rescaled.
+void set_device_units(int cus);
 
 // Exchange family: derived launch geometry of a plan for one problem.
 constexpr size_t kExchangeFlagBytes = 8192;
