@@ -47,7 +47,7 @@ void set_device_units(int cus) {
 }
 
 static double cdiv(double a, double b) { return std::ceil(a / b); }
-static constexpr double kRowsEff = 0.34;   // rows family: fraction of the MFMA peak its loop sustains (measured: LDS-bound)
+static constexpr double kRowsEff = 0.41;   // rows family: fraction of the MFMA peak its loop sustains (measured: bound by LDS issue and the load path)
 static constexpr double kRowsLdsModel = 4 * 6 * 4096 + 12 * 4096 + 64 * 128;   // rows family: rings, partial tiles, H chunk
 
 bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
