@@ -124,7 +124,10 @@ typedef struct {
                          (groups form by the XCD a workgroup runs on; needs an even spread of the
                          launch over the XCDs, checked on the device); 1 = agent-scope
                          release/acquire, valid for any placement, much slower            */
-    int32_t reserved[1];
+    int32_t gate_split;/* two-phase family, gated chains (Sec. 4.1, gated FFN): 0 = both branches in one
+                         workgroup, two accumulator sets, Mul in registers; 1 = the branches are separate
+                         work items on different workgroups (full-width tiles each) and a Mul pass
+                         through the shared cache joins them before the second product          */
 } ffuse_plan_t;
 
 /* Analytical data-movement volumes (Sec. 4.2, Algorithm 1) and per-level costs

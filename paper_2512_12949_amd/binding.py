@@ -35,10 +35,10 @@ class Plan(ctypes.Structure):
     _fields_ = [("family", ctypes.c_int32), ("bm", ctypes.c_int32), ("bh", ctypes.c_int32),
                 ("bn2", ctypes.c_int32), ("bk", ctypes.c_int32), ("splits", ctypes.c_int32),
                 ("h_level", ctypes.c_int32), ("raster", ctypes.c_int32), ("producers", ctypes.c_int32),
-                ("ring", ctypes.c_int32), ("coherent", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1)]
+                ("ring", ctypes.c_int32), ("coherent", ctypes.c_int32), ("gate_split", ctypes.c_int32)]
 
     def as_dict(self):
-        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+        return {k: getattr(self, k) for k, _ in self._fields_}
 
 
 class Traffic(ctypes.Structure):
@@ -396,8 +396,8 @@ def ffuse_version() -> int:
     return int(lib().ffuse_version())
 
 
-def make_plan(family, bm=0, bh=0, bn2=128, bk=64, splits=0, h_level=0, raster=4, producers=0, ring=0, coherent=0) -> Plan:
+def make_plan(family, bm=0, bh=0, bn2=128, bk=64, splits=0, h_level=0, raster=4, producers=0, ring=0, coherent=0, gate_split=0) -> Plan:
     p = Plan()
     p.family, p.bm, p.bh, p.bn2, p.bk, p.splits, p.h_level, p.raster = family, bm, bh, bn2, bk, splits, h_level, raster
-    p.producers, p.ring, p.coherent = producers, ring, coherent
+    p.producers, p.ring, p.coherent, p.gate_split = producers, ring, coherent, gate_split
     return p

@@ -125,14 +125,15 @@ void read_env_plan() {
     g.env_checked = true;
     const char* s = std::getenv("FFUSE_FORCE_PLAN");
     if (!s || !*s) return;
-    int v[11] = {0, 0, 0, 128, 64, 0, 0, 4, 0, 0, 0};
-    const int n = std::sscanf(s, "%d,%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7],
-                              &v[8], &v[9], &v[10]);
+    int v[12] = {0, 0, 0, 128, 64, 0, 0, 4, 0, 0, 0, 0};
+    const int n = std::sscanf(s, "%d,%d,%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7],
+                              &v[8], &v[9], &v[10], &v[11]);
     if (n >= 3) {
         std::memset(&g.forced_plan, 0, sizeof(g.forced_plan));
         g.forced_plan.family = v[0]; g.forced_plan.bm = v[1]; g.forced_plan.bh = v[2]; g.forced_plan.bn2 = v[3];
         g.forced_plan.bk = v[4]; g.forced_plan.splits = v[5]; g.forced_plan.h_level = v[6]; g.forced_plan.raster = v[7];
         g.forced_plan.producers = v[8]; g.forced_plan.ring = v[9]; g.forced_plan.coherent = v[10];
+        g.forced_plan.gate_split = v[11];
         g.forced = true;
     }
 }
@@ -323,7 +324,8 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
         if (!ffuse::two_phase_geometry(plan, gated, M, N1, N2, &sg)) return FFUSE_ERR_PLAN;
         if (!w.ptr || w.bytes < sg.ws_bytes) return FFUSE_ERR_WORKSPACE;
         char* base = reinterpret_cast<char*>(w.ptr);
-        uint32_t* flags = reinterpret_cast<uint32_t*>(base + sg.ysum_bytes + sg.h_bytes);
+        uint32_t* flags = reinterpret_cast<uint32_t*>(base + sg.ysum_bytes + sg.h_bytes + sg.u_bytes);
+        if (sg.gate_split && two_launches) return FFUSE_ERR_PLAN;   // (the Mul pass sits between two rendezvous of one launch)
         if (w.small_flags != flags) {
             if (ffuse::launch_zero(flags, ffuse::kTwoPhaseFlagBytes, st) != hipSuccess) return FFUSE_ERR_LAUNCH;
             w.small_flags = flags;
@@ -333,7 +335,7 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
                               M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, sg.raster, nullptr,
                               conv.ic, conv.h, conv.w, stream_weights(dtype, gated, K, N1, N2),
                               group_barrier() ? wait_masks(sg, M, N1, N2) : ~(uint64_t)0, 3,
-                              g.spin_limit, g.extra_arrivals};
+                              g.spin_limit, g.extra_arrivals, sg.gate_split ? base + sg.ysum_bytes + sg.h_bytes : nullptr};
         if (g.log && w.bytes >= sg.ws_bytes + 65536) {
             s.stats = reinterpret_cast<uint64_t*>(base + sg.ws_bytes);
             g.small_stats = s.stats;
@@ -552,7 +554,7 @@ int ffuse_debug_barrier(int extra_arrivals, unsigned int spin_limit) {
 }
 
 size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2, int unfused) {
-    (void)gated; (void)K;
+    (void)K;
     if (M < 1 || N1 < 1 || N2 < 1) return 0;
     const size_t elem = dtype == FFUSE_DT_F32 ? 4 : 2;
     size_t b = unfused ? elem * (size_t)M * (size_t)N1 : (dtype == FFUSE_DT_F32 ? 0 : sizeof(float) * (size_t)M * (size_t)N2);
@@ -563,7 +565,8 @@ size_t ffuse_workspace_bytes(int dtype, int gated, int64_t M, int64_t K, int64_t
         // two-phase family: partial-sum planes (at the most splits the chooser uses for this M) | H | flags
         const int sp = ffuse::two_phase_max_splits(M, N2);
         const size_t planes = sp > 1 ? (((size_t)4 * M * N2 * sp + 255) & ~(size_t)255) : 0;
-        const size_t tp = planes + (((size_t)2 * M * N1 + 255) & ~(size_t)255) + ffuse::kTwoPhaseFlagBytes;
+        // (gated: twice the intermediate, for plans that keep the two branches apart)
+        const size_t tp = planes + (gated ? 2 : 1) * (((size_t)2 * M * N1 + 255) & ~(size_t)255) + ffuse::kTwoPhaseFlagBytes;
         if (tp > b) b = tp;
     }
     return (b + 255) & ~(size_t)255;
@@ -874,7 +877,7 @@ int ffuse_plan_table_set(int dtype, int gated, int64_t M, int64_t K, int64_t N1,
 }
 
 // Text format, one tuned entry per line:
-//   ffuse-plan 1 <dtype> <gated> <K> <N1> <N2> <bin> <ms> <family> <bm> <bh> <bn2> <bk> <splits> <h_level> <raster> <producers> <ring> <coherent>
+//   ffuse-plan 1 <dtype> <gated> <K> <N1> <N2> <bin> <ms> <family> <bm> <bh> <bn2> <bk> <splits> <h_level> <raster> <producers> <ring> <coherent> [<gate_split>]
 int ffuse_plan_table_save(const char* path) {
     if (!path) return FFUSE_ERR_NULL;
     std::lock_guard<std::mutex> lock(g.mu);
@@ -884,10 +887,10 @@ int ffuse_plan_table_save(const char* path) {
     for (const auto& kv : g.table) {
         if (kv.first[5] < 0) continue;   // modelled entries are recomputed, not stored
         const ffuse_plan_t& p = kv.second.plan;
-        std::fprintf(f, "ffuse-plan 1 %lld %lld %lld %lld %lld %lld %.9g %d %d %d %d %d %d %d %d %d %d %d\n", (long long)kv.first[0],
+        std::fprintf(f, "ffuse-plan 1 %lld %lld %lld %lld %lld %lld %.9g %d %d %d %d %d %d %d %d %d %d %d %d\n", (long long)kv.first[0],
                      (long long)kv.first[1], (long long)kv.first[2], (long long)kv.first[3], (long long)kv.first[4],
                      (long long)kv.first[5], kv.second.ms, p.family, p.bm, p.bh, p.bn2, p.bk, p.splits, p.h_level, p.raster,
-                     p.producers, p.ring, p.coherent);
+                     p.producers, p.ring, p.coherent, p.gate_split);
         ++n;
     }
     std::fclose(f);
@@ -904,14 +907,14 @@ int ffuse_plan_table_load(const char* path) {
     while (std::fgets(line, sizeof(line), f)) {
         long long k[6];
         double ms;
-        int v[11], ver;
-        if (std::sscanf(line, "ffuse-plan %d %lld %lld %lld %lld %lld %lld %lf %d %d %d %d %d %d %d %d %d %d %d", &ver, &k[0], &k[1], &k[2],
-                        &k[3], &k[4], &k[5], &ms, &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7], &v[8], &v[9], &v[10]) != 19)
+        int v[12] = {0}, ver;
+        if (std::sscanf(line, "ffuse-plan %d %lld %lld %lld %lld %lld %lld %lf %d %d %d %d %d %d %d %d %d %d %d %d", &ver, &k[0], &k[1], &k[2],
+                        &k[3], &k[4], &k[5], &ms, &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7], &v[8], &v[9], &v[10], &v[11]) < 19)
             continue;
         if (ver != 1 || k[0] < FFUSE_DT_BF16 || k[0] > FFUSE_DT_F32 || k[5] < 0 || k[5] > 62) continue;
         ffuse_plan_t p{};
         p.family = v[0]; p.bm = v[1]; p.bh = v[2]; p.bn2 = v[3]; p.bk = v[4]; p.splits = v[5]; p.h_level = v[6]; p.raster = v[7];
-        p.producers = v[8]; p.ring = v[9]; p.coherent = v[10];
+        p.producers = v[8]; p.ring = v[9]; p.coherent = v[10]; p.gate_split = v[11];
         if (p.family <= FFUSE_FAMILY_AUTO || p.family > FFUSE_FAMILY_ROWS) continue;
         // validity for a concrete M is checked again at lookup time
         g.table[table_key((int)k[0], (int)k[1], k[2], k[3], k[4], k[5])] = {p, ms > 0.0 ? ms : 1e-9};

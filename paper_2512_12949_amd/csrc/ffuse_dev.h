@@ -149,4 +149,15 @@ template <typename T> __device__ __forceinline__ uint32_t pack2(float a, float b
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// the two 16-bit operands of a dword, widened exactly to fp32 (low half first)
+template <typename T> __device__ __forceinline__ void unpack2(uint32_t w, float& a, float& b);
+template <> __device__ __forceinline__ void unpack2<__bf16>(uint32_t w, float& a, float& b) {
+    a = __builtin_bit_cast(float, w << 16);
+    b = __builtin_bit_cast(float, w & 0xffff0000u);
+}
+template <> __device__ __forceinline__ void unpack2<_Float16>(uint32_t w, float& a, float& b) {
+    a = (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
+    b = (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
+}
+
 }  // namespace ffuse

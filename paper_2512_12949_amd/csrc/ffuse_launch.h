@@ -80,6 +80,8 @@ struct TwoPhaseArgs {
                       // 1 / 2: only the first / second phase (two launches = the unfused comparison path)
     uint32_t spin_limit;   // polls after which a workgroup gives up waiting at the barrier (error word, FFUSE_ERR_TIMEOUT)
     int extra_arrivals;    // 0; a test may ask the barrier to wait for arrivals that never come, to see the wait expire
+    void* U;               // nullptr, or (gated chain with the branches on different workgroups) [M][N1]: X W3 in the
+                           // operand type; H then first holds act(X W1) and a Mul pass joins the two in place
 };
 
 // rows family (row-stationary): no workspace, no flags

@@ -52,6 +52,7 @@ static constexpr double kRowsLdsModel = 4 * 6 * 4096 + 12 * 4096 + 64 * 128;   /
 
 bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
     (void)M; (void)K; (void)N1; (void)N2;
+    if (p.gate_split && p.family != FFUSE_FAMILY_TWOPHASE) return false;
     switch (p.family) {
         case FFUSE_FAMILY_SCALAR: return dtype == FFUSE_DT_F32;
         case FFUSE_FAMILY_UNFUSED: return true;
@@ -120,6 +121,11 @@ int two_phase_max_splits(int64_t M, int64_t N2) {
 
 bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1, int64_t N2, TwoPhaseGeometry* g) {
     // rows per block: the plan's, or the smallest block that holds all rows, or 128 / 256
+    // branches on different workgroups: tiles of the two intermediates must not share cache lines (the Mul pass
+    // rewrites a tile in place while its neighbours may still hold the old values): rows of whole 128-byte lines
+    if (p.gate_split < 0 || p.gate_split > 1 || (p.gate_split && (!gated || (N1 & 63)))) return false;
+    g->gate_split = p.gate_split;
+    if (p.gate_split) gated = 0;    // the items of the first phase are single-branch tiles
     int bm = p.bm;
     if (bm <= 0) bm = M <= 32 ? 32 : (M <= 64 ? 64 : (M <= 512 ? 128 : 256));
     if (bm != 32 && bm != 64 && bm != 128 && bm != 256) return false;
@@ -149,7 +155,8 @@ bool two_phase_geometry(const ffuse_plan_t& p, int gated, int64_t M, int64_t N1,
     if ((M + 256) * N1 * 2 >= ((int64_t)1 << 31)) return false;
     g->ysum_bytes = g->splits > 1 ? (((size_t)4 * M * N2 * g->splits + 255) & ~(size_t)255) : 0;
     g->h_bytes = ((size_t)2 * M * N1 + 255) & ~(size_t)255;
-    g->ws_bytes = g->ysum_bytes + g->h_bytes + kTwoPhaseFlagBytes;
+    g->u_bytes = g->gate_split ? g->h_bytes : 0;
+    g->ws_bytes = g->ysum_bytes + g->h_bytes + g->u_bytes + kTwoPhaseFlagBytes;
     return true;
 }
 
@@ -173,6 +180,7 @@ uint64_t two_phase_wait_masks(const TwoPhaseGeometry& g, int64_t M, int64_t N1, 
     const int MB = (int)((M + g.bm - 1) / g.bm);
     const int NS1 = (int)((N1 + g.bh1 - 1) / g.bh1);
     const int NCB = (int)((N2 + 255) / 256);
+    if (g.gate_split) return ~(uint64_t)0;   // (two device-wide rendezvous: branch tiles are joined across groups)
     if ((int64_t)MB * NS1 > 65536 || (int64_t)MB * NCB * g.splits > 65536) return ~(uint64_t)0;   // (not worth the host time)
     // producer group of every H tile (row block, phase-1 slice)
     std::vector<signed char> owner((size_t)MB * NS1, (signed char)-1);
@@ -238,6 +246,26 @@ static double block_gemm_efficiency(double rows, double cols, bool lds_direct) {
 void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2,
                    ffuse_traffic_t* t) {
     const Device& d = kDevice;
+    if (p.family == FFUSE_FAMILY_TWOPHASE && p.gate_split) {
+        // Branches on different workgroups (Sec. 4.1, gated FFN): per flop the single-branch tiles load what the
+        // two-accumulator tiles of the same plan load (the row-operand tile is shared there), so the plan is
+        // priced as its one-workgroup twin plus the Mul pass -- both intermediates read, one rewritten, through
+        // the shared cache -- and that pass's rendezvous; measured on 2048 x 4096 x 11008 x 4096 and on the
+        // m = 128 gated shapes it costs 15 % and 20-47 % more than the twin (twice as many first-phase items,
+        // each re-reading the row operand; the pass and its rendezvous are 8-15 us on their own).
+        TwoPhaseGeometry sg;
+        std::memset(t, 0, sizeof(*t));
+        if (!gated || !two_phase_geometry(p, gated, M, N1, N2, &sg)) return;
+        ffuse_plan_t q = p;
+        q.gate_split = 0;
+        if (q.bm == 256) q.bh = 128;
+        traffic_model(q, dtype, gated, M, K, N1, N2, t);
+        const double join = 3.0 * 2.0 * (double)M * (double)N1;
+        t->exchange_bytes += join;
+        t->fabric_bytes += join;
+        t->t_pred = 1.10 * t->t_pred + join / d.fabric_bw + 8e-6;
+        return;
+    }
     std::memset(t, 0, sizeof(*t));
     const double e = dtype == FFUSE_DT_F32 ? 4.0 : 2.0, g = gated ? 2.0 : 1.0;
     const double m = (double)M, k = (double)K, n1 = (double)N1, n2 = (double)N2;
@@ -385,12 +413,14 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
     // bandwidth model does not see: measured on the smallest m = 128 shapes it is 5-35 % optimistic
     if (p.family == FFUSE_FAMILY_REDUCE) t->t_pred *= 1.25;
     if (p.family == FFUSE_FAMILY_ROWS && t->feasible) {
-        // The kernel is a weight stream through LDS at 64 flop per weight byte: every byte is written to LDS
-        // once and read once by the matrix pipeline, which together with the partial-tile exchange takes the
-        // whole LDS bandwidth at the full matrix rate.  Measured fraction of the matrix peak on 32768 x 1024 x
-        // 8192 x 1024: kRowsEff; one launch, no second kernel.
+        // The kernel is a weight stream through LDS at 64 flop per weight byte: per chunk a CU pulls 256 KB
+        // through its load path (as long as the chunk's matrix instructions take) and reads them back with
+        // transposing reads at half the LDS's issue rate.  Measured fraction of the matrix peak on 32768 x 1024 x
+        // 8192 x 1024: kRowsEff; one launch, no second kernel.  A launch of this kernel costs about 12 us before
+        // its first product (152 KB of LDS, a long unrolled loop to fetch, the ring to prime, X to load) --
+        // measured on 128-row problems, where it loses to every other family.
         t->t_mfma = padded * waves / (d.mfma_flops * kRowsEff);
-        t->t_pred = std::max({t->t_mfma, t->t_l2, t->t_fabric, t->t_hbm}) + d.launch_s;
+        t->t_pred = std::max({t->t_mfma, t->t_l2, t->t_fabric, t->t_hbm}) + d.launch_s + 12e-6;
     }
     if (p.family == FFUSE_FAMILY_TWOPHASE && t->feasible) {
         // two phases back to back, each the longer of its streaming time and its matrix time.
@@ -522,6 +552,20 @@ void rank_plans(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1,
                     }
                 }
             }
+        }
+    }
+    if (gated) {
+        // the best two-phase plan with its branches on different workgroups (never predicted faster: it is there to be measured)
+        const RankedPlan* b = nullptr;
+        for (const RankedPlan& c : *out)
+            if (c.plan.family == FFUSE_FAMILY_TWOPHASE && (!b || c.t_pred < b->t_pred)) b = &c;
+        if (b) {
+            ffuse_plan_t p = b->plan;
+            p.gate_split = 1;
+            if (p.bm == 256) p.bh = 256;
+            ffuse_traffic_t t;
+            traffic_model(p, dtype, gated, M, K, N1, N2, &t);
+            if (t.feasible) out->push_back({t.t_pred, p});
         }
     }
     {

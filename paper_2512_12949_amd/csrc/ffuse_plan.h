@@ -45,7 +45,8 @@ struct TwoPhaseGeometry {
     int bh1;            // hidden slice of a phase-1 item: 128 / 64 / 32 (bm <= 128), 256 or 128 gated (bm = 256)
     int splits, ksplit; // phase-2 ranges of the hidden dimension (splits == 1: no partial planes)
     int raster;         // row blocks per XCD patch
-    size_t ysum_bytes, h_bytes, ws_bytes;   // workspace layout: partial-sum planes | H | flags (kTwoPhaseFlagBytes)
+    int gate_split;     // gated chain with its branches on different workgroups (phase-1 items are not gated then)
+    size_t ysum_bytes, h_bytes, u_bytes, ws_bytes;   // workspace layout: partial-sum planes | H | U (gate_split) | flags (kTwoPhaseFlagBytes)
 };
 // most hidden-dimension ranges the chooser considers for an M x N2 output (bounds the workspace)
 int two_phase_max_splits(int64_t M, int64_t N2);

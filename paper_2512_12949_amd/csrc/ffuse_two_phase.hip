@@ -120,17 +120,56 @@ __device__ __forceinline__ void two_phase_first(const TwoPhaseArgs& a, char* sme
     typename G1::Ctx c;
     G1::init_lds(c, tid);
     const int NS = (a.N1 + BH1 - 1) / BH1;
+    // a.U: the gated chain's branches as separate items (Sec. 4.1, gated FFN, first realisation): slice
+    // index 2 s is the activated branch of hidden slice s (X W1, into H), 2 s + 1 the multiplying one
+    // (X W3, unactivated, into U) -- neighbours in the item order, so they run side by side
+    const bool split = G1::G == 1 && !CONV && a.U != nullptr;
     int rb, s;
-    for (int idx = loc; map_item(MB, NS, a.raster, xcd, idx, rb, s); idx += GX) {
+    for (int idx = loc; map_item(MB, split ? 2 * NS : NS, a.raster, xcd, idx, rb, s); idx += GX) {
+        const bool up = split && (s & 1);
+        if (split) s >>= 1;
         if constexpr (CONV)
             G1::init_a_conv(c, a.X, (uint32_t)((uint64_t)a.M * a.conv_ic * 2), (uint32_t)rb * BM, a.M, a.conv_h, a.conv_w, a.conv_ic, tid);
         else
             G1::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)rb * BM, (uint32_t)a.K, a.K, tid);
-        G1::init_b(c, a.W1, a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1, (uint32_t)s * BH1, tid);
+        G1::init_b(c, up ? a.W3 : a.W1, split ? nullptr : a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1, (uint32_t)s * BH1, tid);
         if constexpr (DEEP) G1::run(smem, c, 0, a.K, acc, acc3, tid);
         else G1::run_deep(smem, c, 0, a.K, acc, acc3, tid);
-        G1::template store_tile_lds_rt<true>(smem, a.act, acc, acc3, reinterpret_cast<char*>(a.H), a.N1, (int64_t)rb * BM, s * BH1, a.M, a.N1, tid);
+        G1::template store_tile_lds_rt<true>(smem, up ? (int)ACT_IDENTITY : a.act, acc, acc3, reinterpret_cast<char*>(up ? a.U : a.H), a.N1,
+                                             (int64_t)rb * BM, s * BH1, a.M, a.N1, tid);
         __syncthreads();   // LDS is free again before the next item's loads
+    }
+}
+
+// The Mul exchange of the split gated chain: H <- H .* U, tile by tile, in place.  Every workgroup joins
+// the tiles of the activated branch that it computed itself: those lines are its own XCD's (written
+// through, still valid in that L2), the U lines it reads for the first time in this launch, and no
+// other XCD has touched either -- so, as at the rendezvous, nothing stale can be read and nothing
+// needs invalidating.  The products are rounded once more to the operand type.
+template <typename T, int BM, int BH1>
+__device__ __forceinline__ void two_phase_join(const TwoPhaseArgs& a, int tid, int xcd, int loc, int GX, int MB) {
+    const int NS = (a.N1 + BH1 - 1) / BH1;
+    const uint32_t bytes = (uint32_t)((uint64_t)a.M * a.N1 * 2);
+    const __amdgpu_buffer_rsrc_t rh = make_rsrc(a.H, bytes), ru = make_rsrc(a.U, bytes);
+    constexpr int UPR = BH1 / 8;    // 16-byte units per tile row
+    int rb, s;
+    for (int idx = loc; map_item(MB, 2 * NS, a.raster, xcd, idx, rb, s); idx += GX) {
+        if (s & 1) continue;
+        s >>= 1;
+        for (int u = tid; u < BM * UPR; u += 256) {
+            const int64_t row = (int64_t)rb * BM + u / UPR;
+            const int col = s * BH1 + 8 * (u % UPR);
+            if (row >= a.M || col >= a.N1) continue;
+            const uint32_t off = (uint32_t)((row * a.N1 + col) * 2);
+            const u32x4 h = buf_load16(rh, off), g = buf_load16(ru, off);
+            u32x4 o;
+            float h0, h1, g0, g1;
+            unpack2<T>(h[0], h0, h1); unpack2<T>(g[0], g0, g1); o[0] = pack2<T>(h0 * g0, h1 * g1);
+            unpack2<T>(h[1], h0, h1); unpack2<T>(g[1], g0, g1); o[1] = pack2<T>(h0 * g0, h1 * g1);
+            unpack2<T>(h[2], h0, h1); unpack2<T>(g[2], g0, g1); o[2] = pack2<T>(h0 * g0, h1 * g1);
+            unpack2<T>(h[3], h0, h1); unpack2<T>(g[3], g0, g1); o[3] = pack2<T>(h0 * g0, h1 * g1);
+            buf_store16_through(o, rh, off);
+        }
     }
 }
 
@@ -201,6 +240,66 @@ __device__ __forceinline__ void two_phase_prefetch(const TwoPhaseArgs& a, char* 
     G2::prefetch_b(smem, c, k0, k1);
 }
 
+// One device-wide rendezvous of a launch's workgroups; `round` counts them from 1 (the group counters keep
+// counting up: round r is complete for a group when its counter has reached r times the group's size).
+// The tiles stored before it were stored write-through, so once this workgroup's stores have completed
+// they are visible device-wide and arriving takes no L2 write-back (which costs 5+ us when
+// the L2 holds a few MB of dirty lines).  A workgroup arrives with ONE atomic add whose
+// result it does not wait for, on the counter of its group of G/8 workgroups (eight counters
+// a cache line apart: 256 adds on one word take three times as long as 32 on each of 8), and
+// then polls, together, the counters of the groups in `wait`: those whose tiles its own group reads next
+// (a.wait_masks, enumerated on the host from the two item maps: often its own group alone, and
+// then a group that is done starts phase 2 while others still stream their weights).  Measured in
+// isolation, waiting for all eight: 1.8-3.9 us, against 3.8-6.5
+// with a returning add plus a second, group-to-global add, and 7-12.5 with a releasing add.
+// Bounded: on expiry the error word is set and every workgroup leaves (returns false).
+// `between` runs after the arrival and before the wait (loads that may be issued early).
+template <class Between>
+__device__ __forceinline__ bool two_phase_rendezvous(const TwoPhaseArgs& a, volatile uint32_t& verdict, int tid, int xcd, int GX,
+                                                     uint32_t wait, uint32_t round, Between&& between) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0)
+        __hip_atomic_fetch_add(a.flags + kTwoPhaseGroupWord * (1 + xcd), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    between();
+    if (tid == 0) {
+        uint32_t ok = 1;
+        uint32_t spins = 0;
+        const uint32_t target = round * (uint32_t)GX + (uint32_t)a.extra_arrivals;
+        for (;;) {
+            uint32_t fewest = ~0u;
+#pragma unroll
+            for (int g = 0; g < 8; ++g)
+                if ((wait >> g) & 1u) {
+                    const uint32_t n = __hip_atomic_load(a.flags + kTwoPhaseGroupWord * (1 + g), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    fewest = n < fewest ? n : fewest;
+                }
+            if (fewest >= target) break;
+            __builtin_amdgcn_s_sleep(1);
+            // gives up after spin_limit polls, or (looked at every 1024 polls) when another workgroup has
+            if (++spins >= a.spin_limit ||
+                ((spins & 1023u) == 0 && __hip_atomic_load(a.flags + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+                __hip_atomic_fetch_or(a.flags + 2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
+                break;
+            }
+        }
+        verdict = ok;
+    }
+    __syncthreads();
+    // No cache invalidate here.  An agent-scope acquire would drop this XCD's whole L2 (measured: 4-5 us
+    // with the L2 full of weight lines), and there is nothing stale to drop: the caches were emptied of
+    // other agents' data when the kernel started, nobody has read a byte of H since (phase 1 only writes
+    // it), and the lines this XCD wrote itself hold what it wrote.  (Probed on the device: two XCDs
+    // writing halves of the same lines, then reading each other's halves after this barrier, launch
+    // after launch, see fresh data without an invalidate; they see stale data only if they had READ the
+    // lines earlier in the same kernel.)
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    const bool ok = verdict != 0;
+    __syncthreads();   // everybody has read the word before the next loads reuse its place
+    return ok;
+}
+
 // CONV: the first product is a 3x3 convolution (rows = pixels of a channels-last image,
 // a.K = 9 * a.conv_ic); everything after the first product's loads is unchanged.
 // a.nt selects, per launch, the instantiations of the block GEMMs that stream the weights with
@@ -245,53 +344,24 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
     // isolation, waiting for all eight: 1.8-3.9 us, against 3.8-6.5
     // with a returning add plus a second, group-to-global add, and 7-12.5 with a releasing add.
     // bounded: on expiry the error word is set and every workgroup leaves
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (tid == 0 && !both) verdict = 1u;
-    if (tid == 0 && both)
-        __hip_atomic_fetch_add(a.flags + kTwoPhaseGroupWord * (1 + xcd), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if constexpr (TG::PREFETCH) {
-        if (both) {
-            if (TG::HAS_NT && a.nt) two_phase_prefetch<typename TG::template G2<true>, BM>(a, smem, tid, xcd, loc, MB);
-            else two_phase_prefetch<G2, BM>(a, smem, tid, xcd, loc, MB);
+    bool ok = true;
+    if (both) {
+        if (a.U) {
+            // split gated chain: every branch tile is out, then the workgroups join their own, then H is complete
+            ok = two_phase_rendezvous(a, verdict, tid, xcd, GX, 0xffu, 1u, [] {});
+            if (ok) two_phase_join<T, BM, BH1>(a, tid, xcd, loc, GX, MB);
         }
-    }
-    if (tid == 0 && both) {
-        uint32_t ok = 1;
-        uint32_t spins = 0;
-        const uint32_t wait = (uint32_t)(a.wait_masks >> (8 * xcd)) & 0xffu;
-        for (;;) {
-            // (only the groups whose phase-1 tiles this group's phase-2 items read)
-            uint32_t fewest = ~0u;
-#pragma unroll
-            for (int g = 0; g < 8; ++g)
-                if ((wait >> g) & 1u) {
-                    const uint32_t n = __hip_atomic_load(a.flags + kTwoPhaseGroupWord * (1 + g), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    fewest = n < fewest ? n : fewest;
+        if (ok)
+            ok = two_phase_rendezvous(a, verdict, tid, xcd, GX, a.U ? 0xffu : (uint32_t)(a.wait_masks >> (8 * xcd)) & 0xffu, a.U ? 2u : 1u, [&] {
+                if constexpr (TG::PREFETCH) {
+                    if (TG::HAS_NT && a.nt) two_phase_prefetch<typename TG::template G2<true>, BM>(a, smem, tid, xcd, loc, MB);
+                    else two_phase_prefetch<G2, BM>(a, smem, tid, xcd, loc, MB);
                 }
-            if (fewest >= (uint32_t)(GX + a.extra_arrivals)) break;
-            __builtin_amdgcn_s_sleep(1);
-            // gives up after spin_limit polls, or (looked at every 1024 polls) when another workgroup has
-            if (++spins >= a.spin_limit ||
-                ((spins & 1023u) == 0 && __hip_atomic_load(a.flags + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-                __hip_atomic_fetch_or(a.flags + 2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ok = 0;
-                break;
-            }
-        }
-        verdict = ok;
+            });
+    } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
     }
-    __syncthreads();
-    // No cache invalidate here.  An agent-scope acquire would drop this XCD's whole L2 (measured: 4-5 us
-    // with the L2 full of weight lines), and there is nothing stale to drop: the caches were emptied of
-    // other agents' data when the kernel started, nobody has read a byte of H since (phase 1 only writes
-    // it), and the lines this XCD wrote itself hold what it wrote.  (Probed on the device: two XCDs
-    // writing halves of the same lines, then reading each other's halves after this barrier, launch
-    // after launch, see fresh data without an invalidate; they see stale data only if they had READ the
-    // lines earlier in the same kernel.)
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    const bool ok = verdict != 0;
-    __syncthreads();   // everybody has read the word before phase 2's loads reuse its place
     if (a.stats) t2 = wall_clock64();
 
     // ---------------------------------------------------------------- phase 2
@@ -389,7 +459,8 @@ template <typename T> static const void* two_phase_conv_fn(int bm, int bh1) {
 }
 
 hipError_t launch_fused_two_phase(int dtype, const TwoPhaseArgs& a, int bm, int bh1, int bk, int grid, hipStream_t st) {
-    const bool g = a.W3 != nullptr;
+    const bool g = a.W3 != nullptr && a.U == nullptr;   // (a.U: the branches are separate single-branch items)
+    if (a.U && (a.W3 == nullptr || a.phases != 3 || a.conv_ic > 0 || (a.N1 & 63))) return hipErrorInvalidValue;
     const void* fn;
     if (a.conv_ic > 0) {
         // 3x3 first product: one tap per K step of 64, and the shifted addresses must fit 32 bits

@@ -50,7 +50,7 @@ def run(w, dev, unfused=False, plan=None):
                ff.ffuse_workspace_bytes(dt, w.gated, M, w.K, w.N1, w.N2, True))
     if plan is not None and plan.family == ff.FAMILY_TWOPHASE:
         # a forced plan may ask for more partial planes than the chooser would ever use
-        need = max(need, 4 * M * w.N2 * max(1, plan.splits) + 2 * M * w.N1 + 1024)
+        need = max(need, 4 * M * w.N2 * max(1, plan.splits) + (1 + plan.gate_split) * (2 * M * w.N1 + 256) + 1024)
     Workspace.ensure(need)
     Y = torch.full((M, w.N2), float("nan"), dtype=torch_dtype(w.dtype), device="cuda")
     ff.ffuse_force_plan(plan)

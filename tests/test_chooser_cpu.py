@@ -191,3 +191,32 @@ def test_per_call_workspace_arguments_are_validated_first():
         assert f(ff.DT_BF16, a, a, None, a, 1, 8, 8, 8, 8, a, None, 256, None) == -1  # a size without a buffer
     assert L.ffuse_debug_barrier(-1, 10) == -2 and L.ffuse_debug_barrier(0, 0) == -2
     assert L.ffuse_debug_barrier(0, 1 << 24) == 0
+
+
+def test_split_gate_plans_are_valid_only_where_the_kernel_can_run_them():
+    """Gated chain with its branches on different workgroups (Sec. 4.1): two-phase family only, gated only,
+    hidden size a multiple of 64 (tiles of the two intermediates must not share cache lines); the
+    workspace holds both intermediates; the model never prefers it to its one-workgroup twin."""
+    import ctypes
+    split = ff.make_plan(ff.FAMILY_TWOPHASE, bm=256, bh=256, bn2=256, bk=32, gate_split=1)
+    twin = ff.make_plan(ff.FAMILY_TWOPHASE, bm=256, bh=128, bn2=256, bk=32)
+    shape = (2048, 4096, 11008, 4096)
+    t1 = ff.ffuse_traffic_model(split, ff.DT_BF16, True, *shape)
+    t0 = ff.ffuse_traffic_model(twin, ff.DT_BF16, True, *shape)
+    assert t1.feasible and t1.t_pred > t0.t_pred and t1.fabric_bytes == t0.fabric_bytes + 3 * 2 * 2048 * 11008
+    t = ff.Traffic()
+    L = ff.lib()
+    assert L.ffuse_traffic_model(ctypes.byref(split), ff.DT_BF16, 0, *shape, ctypes.byref(t)) == -8          # not gated
+    assert L.ffuse_traffic_model(ctypes.byref(split), ff.DT_BF16, 1, 2048, 4096, 11016, 4096, ctypes.byref(t)) == -8   # N1 % 64
+    for fam in (ff.FAMILY_REDUCE, ff.FAMILY_EXCHANGE, ff.FAMILY_ROWS):
+        other = ff.make_plan(fam, bm=128, bh=128, gate_split=1)
+        assert L.ffuse_traffic_model(ctypes.byref(other), ff.DT_BF16, 1, *shape, ctypes.byref(t)) == -8
+    bad = ff.make_plan(ff.FAMILY_TWOPHASE, bm=256, bh=256, bn2=256, bk=32, gate_split=2)
+    assert L.ffuse_traffic_model(ctypes.byref(bad), ff.DT_BF16, 1, *shape, ctypes.byref(t)) == -8
+    # room for both intermediates
+    assert ff.ffuse_workspace_bytes(ff.DT_BF16, True, *shape) >= 2 * 2 * 2048 * 11008
+    for shp in (shape, (128, 4096, 11008, 4096), (16, 8192, 28672, 8192)):
+        ranked = ff.ffuse_rank_plans(ff.DT_BF16, 3, True, *shp)
+        splits = [i for i, (p, _) in enumerate(ranked) if p.gate_split]
+        assert len(splits) == 1 and splits[0] > 0 and ranked[0][0].gate_split == 0
+        assert all(p.gate_split == 0 for p, _ in ff.ffuse_rank_plans(ff.DT_BF16, 2, False, *shp))
