@@ -99,3 +99,67 @@ def test_split_branches_on_the_llama_configuration():
     for plan in (_plan(256, 256, 1, bk=32, raster=4, splits=1), _plan(256, 256, 1, bk=32, raster=4, splits=2)):
         Y = gu.run(w, dev, plan=plan)
         gu.check(Y, ref, w.dtype, rows=rows, what="llama, split branches")
+
+
+def test_an_expired_wait_at_either_rendezvous_of_the_split_realisation_leaves_cleanly():
+    """The split realisation meets twice per launch.  With the host asking for an arrival that never
+    comes, the first wait expires: the Mul pass and the second product are skipped, every workgroup
+    leaves, the call reports the timeout and the next call is right."""
+    w, host, dev = _case("gs-timeout", 300, 136, 832, 264, "bf16", cfg_id=980)
+    ref = gu.oracle_rows(w, host)
+    plan = _plan(128, 128, 1, splits=2, raster=2)
+    gu.check(gu.run(w, dev, plan=plan), ref, "bf16", what="before")
+    Y = torch.full((w.M, w.N2), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ff.ffuse_force_plan(plan)
+    try:
+        for rep in range(2):
+            ff.ffuse_debug_barrier(1, 64)
+            try:
+                assert ff.ffuse_ffn(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y, check=False) == 0
+                assert ff.ffuse_sync_status(check=False) == -9
+            finally:
+                ff.ffuse_debug_barrier(0, 1 << 24)
+            Y.fill_(float("nan"))
+            assert ff.ffuse_ffn(dev["X"], dev["W1"], dev["W3"], dev["W2"], w.act, Y, check=False) == 0
+            assert ff.ffuse_sync_status(check=False) == 0
+            gu.check(Y, ref, "bf16", what=f"call after the expired wait ({rep})")
+    finally:
+        ff.ffuse_debug_barrier(0, 1 << 24)
+        ff.ffuse_force_plan(None)
+
+
+def test_split_realisation_in_a_replayed_graph_with_the_input_overwritten():
+    shape = (600, 264, 1344, 520)
+    ws_, hs = zip(*[(_case("gs-graph", *shape, "bf16", cfg_id=985 + i)[:2]) for i in range(3)])
+    w = ws_[0]
+    base = {k: gu.to_device(v, "bf16") for k, v in hs[0].items()}
+    hosts = [dict(hs[0], X=h["X"]) for h in hs]
+    refs = [gu.oracle_rows(w, h) for h in hosts]
+    xs = [gu.to_device(h["X"], "bf16") for h in hosts]
+    plan = _plan(256, 256, 1, bk=32, raster=2)
+    gu.check(gu.run(w, base, plan=plan), refs[0], "bf16", what="eager")
+    X = xs[0].clone()
+    Y = torch.zeros((w.M, w.N2), dtype=torch.bfloat16, device="cuda")
+    side = torch.cuda.Stream()
+    ff.ffuse_force_plan(plan)
+    try:
+        with torch.cuda.stream(side):
+            ff.ffuse_ffn(X, base["W1"], base["W3"], base["W2"], w.act, Y)
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                ff.ffuse_ffn(X, base["W1"], base["W3"], base["W2"], w.act, Y)
+        torch.cuda.synchronize()
+        for rep in range(5):
+            i = (rep + 1) % 3
+            X.copy_(xs[i])
+            if rep % 2 == 1:       # the one-workgroup realisation runs eagerly in the same workspace between replays
+                gu.check(gu.run(w, dict(base, X=xs[i]), plan=_plan(128, 128, 0, splits=2)), refs[i], "bf16", what="eager twin")
+                ff.ffuse_force_plan(plan)
+            Y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            gu.check(Y, refs[i], "bf16", what=f"replay {rep} (input {i})")
+    finally:
+        ff.ffuse_force_plan(None)

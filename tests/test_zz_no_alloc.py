@@ -60,3 +60,40 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit():
     torch.cuda.synchronize()
     rows = inputs.sample_rows(w.M, 256, 3, seed=3)
     gu.check(Yr, gu.oracle_rows(w, host, rows), "bf16", rows=rows, what="static scratch, large M")
+
+
+def test_static_scratch_entry_point_recorded_into_a_graph():
+    """What the entry point is for: after one eager call (which resolves the address of the built-in
+    memory) a call is captured and replayed, with the input overwritten in place and with eager calls
+    of other shapes using the same built-in memory between the replays."""
+    w, host, dev = _problem("static-graph", 128, 520, 2056, 520, True, 993)
+    hosts = [host] + [dict(host, X=inputs.make(inputs.custom("static-graph-x", w.M, w.K, w.N1, w.N2, dtype="bf16", act=w.act, gated=True,
+                                                              cfg_id=994 + i))["X"]) for i in range(2)]
+    refs = [gu.oracle_rows(w, h) for h in hosts]
+    xs = [gu.to_device(h["X"], "bf16") for h in hosts]
+    ow, ohost, odev = _problem("static-other", 77, 264, 840, 136, False, 997)
+    oref = gu.oracle_rows(ow, ohost)
+    X = xs[0].clone()
+    Y = torch.zeros((w.M, w.N2), dtype=torch.bfloat16, device="cuda")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ff.ffuse_ffn_static(ff.DT_BF16, X, dev["W1"], dev["W3"], dev["W2"], w.act, Y)
+        side.synchronize()
+        gu.check(Y, refs[0], "bf16", what="eager")
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            ff.ffuse_ffn_static(ff.DT_BF16, X, dev["W1"], dev["W3"], dev["W2"], w.act, Y)
+    torch.cuda.synchronize()
+    for rep in range(5):
+        i = (rep + 1) % 3
+        X.copy_(xs[i])
+        if rep % 2 == 1:
+            Yo = torch.full((ow.M, ow.N2), float("nan"), dtype=torch.bfloat16, device="cuda")
+            ff.ffuse_ffn_static(ff.DT_BF16, odev["X"], odev["W1"], None, odev["W2"], ow.act, Yo)
+            torch.cuda.synchronize()
+            gu.check(Yo, oref, "bf16", what="eager call of another shape between replays")
+        Y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        gu.check(Y, refs[i], "bf16", what=f"replay {rep} (input {i})")
