@@ -20,11 +20,13 @@
 // each wave issues LDS-direct loads (buffer_load ... lds) into its own ring of 4 KB slots, four to five
 // slots ahead, and waits on its own vmcnt.  The only barriers are the two around the partial-tile exchange.
 //
-// What bounds it (measured, 32768 x 1024 x 8192 x 1024: LDS busy 91 % of the time, matrix pipelines about
-// half): with 64 rows per workgroup a weight fragment feeds two MFMAs, so per 64 matrix cycles every wave
-// pulls 1 KB through a transposing LDS read -- the whole rate of those reads -- and the same bytes arrive
-// through LDS-direct writes beside them.  The family trades that for memory traffic: the weights are filled
-// into an XCD's L2 once per round of row blocks, X and Y cross the fabric once, nothing else does.
+// What bounds it (measured, 32768 x 1024 x 8192 x 1024: matrix pipelines about half occupied): with 64 rows per
+// workgroup a weight byte feeds 64 rows only, so per chunk a compute unit pulls 256 KB through its L2 -> LDS
+// path -- at that path's 64 bytes per clock as long as the chunk's matrix instructions take -- and the eight
+// L2s deliver 17 GB per call, 2.0 TB/s each, close to what an L2 delivers on hits.  The family trades that for
+// memory traffic: the weights are filled into an XCD's L2 once per round of row blocks, X and Y cross the
+// fabric once, nothing else does.  (Tried and dropped: the exchange of chunk c + 1 riding inside the second
+// product of chunk c, with two H buffers -- no faster: the exchange costs LDS issue slots, not idle time.)
 //
 // Why X sits in registers: measured on this chip, 32 workgroups per XCD that each re-read a private
 // 128 KB row block once per chunk evict each other from the 4 MB L2 completely (2 GiB of refills per
@@ -158,6 +160,15 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
     constexpr int NW = 32 * NT2;            // output columns per wave
     constexpr int KQ = 16 * NKS;            // k range per wave
     static_assert(NKS % 2 == 0 && NT2 % 4 == 0 && SPC > RING, "slot arithmetic");
+    // The first product's accumulator: with the output block in all 256 accumulation registers (NT2 = 8) it has to
+    // live in ordinary registers, which only hand-written matrix instructions can say (RowsMmaV).  The compiler
+    // does not know that their results arrive late: it must never copy those registers between two of them, which
+    // holds only as long as it has no reason to -- no spare accumulation registers to park values in (seen once,
+    // with NT2 = 4 and a few registers too many in flight: the tiles were parked in the idle half of the accumulation
+    // file between two instructions, and a few hundred output elements per call came out wrong).  With half the
+    // output block (NT2 = 4) there is room for the accumulator beside it, and the compiler's own instructions, whose
+    // timing it knows, are used.
+    constexpr bool P_BY_HAND = NT2 > 4;
     static_assert((RING - 1) * 4 <= 63, "vmcnt holds 6 bits");
     __shared__ __attribute__((aligned(16))) char smem[kRowsLdsBytes];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -308,7 +319,7 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) p[ht][mt][r] = 0.0f;
-            rows_mfma_settle(p);
+            if constexpr (P_BY_HAND) rows_mfma_settle(p);
             vec8 hb[2][2];                              // H fragments of hidden step ks2, set ks2 & 1
             rows_static_for([&](auto tc) {
                 constexpr int t = decltype(tc)::value;
@@ -330,7 +341,8 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
                 for (int m = 0; m < 4; ++m) {
                     const int e = m >> 1, mt = m & 1;
                     if constexpr (t < NST1) {
-                        RowsMmaV<T>::mma(fr[cur][e], xf[t][mt], p[e][mt]);
+                        if constexpr (P_BY_HAND) RowsMmaV<T>::mma(fr[cur][e], xf[t][mt], p[e][mt]);
+                        else p[e][mt] = Mma<T>::mma(fr[cur][e], xf[t][mt], p[e][mt]);
                     } else {
                         constexpr int u = t - NST1, ks2 = u / (2 * NH2), half = (u / 2) % NH2;
                         const int ht = 2 * (u & 1) + e;
@@ -355,7 +367,7 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
                 if (!first) pos = pn;
                 if (t == NST1 - 1) {
                     // ---- Add exchange of the partial tiles: wave t collects tile t = 2 ht + mt ------------
-                    rows_mfma_settle(p);
+                    if constexpr (P_BY_HAND) rows_mfma_settle(p);
                     f32x16 s;
 #pragma unroll
                     for (int tt = 0; tt < 4; ++tt) {
@@ -364,7 +376,12 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
                             continue;
                         }
                         const int src = (wave - tt + 4) % 4 - 1;     // 0..2: which of tile tt's three foreign parts
-                        char* dst = part + (tt * 3 + src) * SLOT + lane * 16;
+                        // (lane made opaque: these addresses do not depend on the chunk, and hoisted out of the chunk
+                        //  loop they would live in registers this kernel does not have -- spilled, and every reload
+                        //  of a spilled register makes the compiler wait for ALL outstanding loads, the ring's included)
+                        uint32_t l = (uint32_t)lane;
+                        asm volatile("" : "+v"(l));
+                        char* dst = part + (tt * 3 + src) * SLOT + l * 16;
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
                             const f32x16& v = p[tt >> 1][tt & 1];
@@ -377,7 +394,9 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
                     {
 #pragma unroll
                         for (int src = 0; src < 3; ++src) {
-                            const char* from = part + (wave * 3 + src) * SLOT + lane * 16;
+                            uint32_t l = (uint32_t)lane;
+                            asm volatile("" : "+v"(l));
+                            const char* from = part + (wave * 3 + src) * SLOT + l * 16;
 #pragma unroll
                             for (int q = 0; q < 4; ++q) {
                                 const f32x4 v = *reinterpret_cast<const f32x4*>(from + q * 1024);
@@ -386,7 +405,9 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
                             __builtin_amdgcn_sched_barrier(0);
                         }
                         // activation on complete sums, round to the operand type, into H: tile (ht, mt) = (wave / 2, wave % 2)
-                        const uint32_t x = lane & 31, h = lane >> 5;
+                        uint32_t l = (uint32_t)lane;
+                        asm volatile("" : "+v"(l));
+                        const uint32_t x = l & 31, h = l >> 5;
                         const uint32_t hrow = 32u * (wave & 1) + x, ht = (uint32_t)(wave >> 1);
                         const int nlim = N1 - 64 * c - 32 * (int)ht - 4 * (int)h;
                         switch (a.act) {

@@ -5,7 +5,9 @@
 //   phase 1: work items (row block of BM rows, hidden slice of BH1 columns); each computes,
 //            with K complete, H[rows, slice] = act(X W1[:, slice]) [.* X W3[:, slice]];
 //   barrier : every workgroup has published its tiles (write-through stores, counted arrivals;
-//            no cache invalidate is needed: nobody has read H in this launch yet);
+//            no cache invalidate is needed: nobody has read H in this launch yet).  A gated chain
+//            whose branches are separate first-phase items (TwoPhaseArgs::U) meets twice, with the
+//            Mul pass that joins the two intermediates in between;
 //   phase 2: work items (row block, 256 output columns, one of `splits` ranges of the hidden
 //            dimension); each multiplies its part of H with its W2 block.  With splits == 1
 //            the tile goes straight to Y; otherwise every range stores its partial tile into
@@ -330,20 +332,9 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
     }
 
     if (a.stats) { t1 = wall_clock64(); c1 = clock64(); }
-    // ---------------------------------------------------------------- device-wide barrier
+    // ---------------------------------------------------------------- rendezvous between the phases
     // (only when both phases run in this launch: launched one phase at a time, the kernel
-    // boundary is the barrier -- the unfused comparison path)
-    // The tiles of H were stored write-through, so once this workgroup's stores have completed
-    // they are visible device-wide and arriving takes no L2 write-back (which costs 5+ us when
-    // the L2 holds a few MB of dirty lines).  A workgroup arrives with ONE atomic add whose
-    // result it does not wait for, on the counter of its group of G/8 workgroups (eight counters
-    // a cache line apart: 256 adds on one word take three times as long as 32 on each of 8), and
-    // then polls, together, the counters of the groups whose tiles of H its own group's phase-2 items read
-    // (a.wait_masks, enumerated on the host from the two item maps: often its own group alone, and
-    // then a group that is done starts phase 2 while others still stream their weights).  Measured in
-    // isolation, waiting for all eight: 1.8-3.9 us, against 3.8-6.5
-    // with a returning add plus a second, group-to-global add, and 7-12.5 with a releasing add.
-    // bounded: on expiry the error word is set and every workgroup leaves
+    // boundary is the barrier -- the unfused comparison path).  See two_phase_rendezvous.
     bool ok = true;
     if (both) {
         if (a.U) {
