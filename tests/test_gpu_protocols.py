@@ -199,16 +199,26 @@ def test_litmus_loop_over_the_flag_protocols(kind):
 
 def test_seeded_walk_over_every_family():
     """Bounded seeded walk over shapes, operand types, activations and plans of EVERY family (reduce,
-    exchange, two-phase, rows) against the oracle, all on one workspace."""
+    exchange, two-phase in both gated realisations, rows) against the oracle, all on one workspace."""
     import random
     rng = random.Random(20260101)
-    for n in range(36):
-        fam = rng.choice(["reduce", "exchange", "two", "rows"])
-        gated = rng.random() < 0.5 and fam != "rows"
+    for n in range(44):
+        fam = rng.choice(["reduce", "exchange", "two", "rows"]) if n < 36 else "split"
+        gated = (rng.random() < 0.5 and fam != "rows") or fam == "split"
         dtype, act = rng.choice(["bf16", "f16"]), rng.choice([0, 1, 2, 3])
         M = rng.choice([1, 33, 64, 130, 257, 520, 900])
         K, N1, N2 = 8 * rng.randint(1, 64), 8 * rng.randint(1, 200), 8 * rng.randint(1, 80)
-        if fam == "reduce":
+        if fam == "split":       # the gated chain with its branches on different workgroups: hidden size in whole cache lines
+            N1 = 64 * rng.randint(1, 25)
+            bm = rng.choice([128, 256]) if M > 64 else rng.choice([32, 64, 128])
+            if bm == 32 and M > 128:
+                bm = 128
+            plan = ff.make_plan(ff.FAMILY_TWOPHASE, bm=bm, bh=256 if bm == 256 else 128, bn2=256, bk=rng.choice([32, 64]),
+                                splits=rng.choice([1, 2, 3]), raster=rng.choice([1, 2]), gate_split=1)
+            fam = "two-split"
+        if fam == "two-split":
+            pass
+        elif fam == "reduce":
             bm, bh = rng.choice([(256, 128), (128, 128), (128, 64)] if gated else [(256, 256), (128, 256), (128, 128), (128, 64)])
             plan = ff.make_plan(ff.FAMILY_REDUCE, bm, bh, bn2=128, raster=rng.choice([1, 2]), splits=(N1 + bh - 1) // bh)
         elif fam == "exchange":
