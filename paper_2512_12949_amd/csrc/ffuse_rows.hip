@@ -167,8 +167,9 @@ __global__ __launch_bounds__(256) void fused_rows_kernel(RowsArgs a) {
     // with NT2 = 4 and a few registers too many in flight: the tiles were parked in the idle half of the accumulation
     // file between two instructions, and a few hundred output elements per call came out wrong).  With half the
     // output block (NT2 = 4) there is room for the accumulator beside it, and the compiler's own instructions, whose
-    // timing it knows, are used.
-    constexpr bool P_BY_HAND = NT2 > 4;
+    // timing it knows, are used; so they are with half of X (NKS = 8), where the compiler finds room without
+    // spilling inside the chunk loop.  Only the largest instantiation issues them by hand.
+    constexpr bool P_BY_HAND = NT2 > 4 && NKS > 8;
     static_assert((RING - 1) * 4 <= 63, "vmcnt holds 6 bits");
     __shared__ __attribute__((aligned(16))) char smem[kRowsLdsBytes];
     const int tid = threadIdx.x, lane = tid & 63;
