@@ -26,7 +26,8 @@
 // L2s deliver 17 GB per call, 2.0 TB/s each, close to what an L2 delivers on hits.  The family trades that for
 // memory traffic: the weights are filled into an XCD's L2 once per round of row blocks, X and Y cross the
 // fabric once, nothing else does.  (Tried and dropped: the exchange of chunk c + 1 riding inside the second
-// product of chunk c, with two H buffers -- no faster: the exchange costs LDS issue slots, not idle time.)
+// product of chunk c, with two H buffers -- no faster; and one plain
+// 16-byte read per fragment in place of the two transposing reads -- no faster either: the LDS is not the limit.)
 //
 // Why X sits in registers: measured on this chip, 32 workgroups per XCD that each re-read a private
 // 128 KB row block once per chunk evict each other from the 4 MB L2 completely (2 GiB of refills per
