@@ -96,7 +96,7 @@ struct RowsArgs {
     int act;
     uint64_t* stats;  // nullptr, or 2 words per workgroup: 100 MHz ticks and core clocks from start to end
 };
-static constexpr int kRowsRing = 6;                                                 // 4 KB weight slots per wave
+static constexpr int kRowsRing = 4;    // 4 KB weight slots per wave (measured on 32768 x 1024 x 8192 x 1024: 3 slots 1182 us, 4 1056, 5 1079, 6 1077)
 static constexpr int kRowsLdsBytes = 4 * kRowsRing * 4096 + 12 * 4096 + 64 * 128;   // rings | partial tiles | H chunk
 
 // 16-bit paths (dtype 0 = bf16, 1 = fp16)

@@ -47,8 +47,8 @@ void set_device_units(int cus) {
 }
 
 static double cdiv(double a, double b) { return std::ceil(a / b); }
-static constexpr double kRowsEff = 0.41;   // rows family: fraction of the MFMA peak its loop sustains (measured: bound by the L2 -> LDS load path)
-static constexpr double kRowsLdsModel = 4 * 6 * 4096 + 12 * 4096 + 64 * 128;   // rows family: rings, partial tiles, H chunk
+static constexpr double kRowsEff = 0.43;   // rows family: fraction of the MFMA peak its loop sustains (measured: bound by the L2 -> LDS load path)
+static constexpr double kRowsLdsModel = 4 * 4 * 4096 + 12 * 4096 + 64 * 128;   // rows family: rings, partial tiles, H chunk
 
 bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
     (void)M; (void)K; (void)N1; (void)N2;
@@ -416,7 +416,7 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         // The kernel is a weight stream through LDS at 64 flop per weight byte: per chunk a CU pulls 256 KB
         // through its load path, as long as the chunk's matrix instructions take.  Measured fraction of the matrix peak on 32768 x 1024 x
         // 8192 x 1024: kRowsEff; one launch, no second kernel.  A launch of this kernel costs about 12 us before
-        // its first product (152 KB of LDS, a long unrolled loop to fetch, the ring to prime, X to load) --
+        // its first product (120 KB of LDS, a long unrolled loop to fetch, the ring to prime, X to load) --
         // measured on 128-row problems, where it loses to every other family.
         t->t_mfma = padded * waves / (d.mfma_flops * kRowsEff);
         t->t_pred = std::max({t->t_mfma, t->t_l2, t->t_fabric, t->t_hbm}) + d.launch_s + 12e-6;

@@ -17,7 +17,7 @@
 //   second product: Y[:, cols(w)] += H * W2[chunk, cols(w)], wave w owning N2/4 output columns, H
 //   from LDS and W2 from the same private ring.
 // Every weight element is used by exactly one wave, so the weight stream needs no workgroup barrier:
-// each wave issues LDS-direct loads (buffer_load ... lds) into its own ring of 4 KB slots, four to five
+// each wave issues LDS-direct loads (buffer_load ... lds) into its own ring of 4 KB slots, two to three
 // slots ahead, and waits on its own vmcnt.  The only barriers are the two around the partial-tile exchange.
 //
 // What bounds it (measured, 32768 x 1024 x 8192 x 1024: matrix pipelines about half occupied): with 64 rows per
