@@ -135,7 +135,7 @@ def measure(name, args, ff, inputs, np, torch, cal, *, steps, warmup, tune, head
     # objective would take
     by_bytes = None
     if w.dtype != "f32" and not args.fused_only and plan_from != "forced":
-        pt = ff.ffuse_choose_plan(dt, w.act, w.gated, w.M, w.K, w.N1, w.N2)
+        pt = ff.ffuse_rank_plans(dt, w.act, w.gated, w.M, w.K, w.N1, w.N2)[0][0]     # the model's fastest, before any tie-break
         ff.ffuse_set_objective(ff.OBJECTIVE_BYTES)
         pb = ff.ffuse_choose_plan(dt, w.act, w.gated, w.M, w.K, w.N1, w.N2)
         ff.ffuse_set_objective(ff.OBJECTIVE_TIME)

@@ -274,7 +274,7 @@ int ffuse_sync_status(void* stream);
  *      overwritten with a valid result every time), records the fastest for M's bin (M <= 16,
  *      then one bin per power of two) and returns it; near-ties go to the analytical order: a
  *      plan ranked later has to be more than 1 % faster to win -- except that a plan measured within
- *      5 % of the fastest takes its place when the model gives it at most half the bytes between the
+ *      8 % of the fastest takes its place when the model gives it at most half the bytes between the
  *      L2s and the rest of the memory system (equal time, far less traffic).  Later fused calls with the same dtype, gate, K, N1,
  *      N2 and an M of that bin use it when it is valid for their M and fits their workspace;
  *      otherwise, and for bins never tuned, the model's choice for the exact M is used (and

@@ -828,7 +828,8 @@ int ffuse_tune(int dtype, const void* X, const void* W1, const void* W3, const v
             if (c.ms < 1e30 && c.ms < best * 0.99) { best = c.ms; bestp = c.plan; }
         }
         // ... and a near-tie in time goes to the schedule that keeps far more of the traffic on the chip: a candidate
-        // measured within 5 % of the fastest whose modelled bytes between the L2s and the fabric are at most half
+        // measured within 8 % of the fastest in these short runs (the rows family reaches its steady clock more
+        // slowly than the others: at steady state the gap is 1-2 %) whose modelled bytes between the L2s and the fabric are at most half
         // of the fastest plan's takes its place (the rows family on 32768 x 1024 x 8192 x 1024: equal time within
         // the noise of the measurement, 0.3 of the bytes)
         if (best < 1e30) {
@@ -836,7 +837,7 @@ int ffuse_tune(int dtype, const void* X, const void* W1, const void* W3, const v
             ffuse::traffic_model(bestp, dtype, gated, M, K, N1, N2, &tb);
             const double fastest = best;
             for (const Cand& c : cands) {
-                if (c.ms >= 1e30 || c.ms > fastest * 1.05) continue;
+                if (c.ms >= 1e30 || c.ms > fastest * 1.08) continue;
                 ffuse_traffic_t tc;
                 ffuse::traffic_model(c.plan, dtype, gated, M, K, N1, N2, &tc);
                 if (tc.feasible && tc.fabric_bytes <= 0.5 * tb.fabric_bytes) { best = c.ms; bestp = c.plan; tb = tc; }

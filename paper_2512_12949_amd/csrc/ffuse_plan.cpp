@@ -47,7 +47,7 @@ void set_device_units(int cus) {
 }
 
 static double cdiv(double a, double b) { return std::ceil(a / b); }
-static constexpr double kRowsEff = 0.43;   // rows family: fraction of the MFMA peak its loop sustains (measured: bound by the L2 -> LDS load path)
+static constexpr double kRowsEff = 0.45;   // rows family: fraction of the MFMA peak its chunk loop sustains at K = N2 = 1024 (bound by the L2 -> LDS load path)
 static constexpr double kRowsLdsModel = 4 * 4 * 4096 + 12 * 4096 + 64 * 128;   // rows family: rings, partial tiles, H chunk
 
 bool plan_valid(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64_t K, int64_t N1, int64_t N2) {
@@ -413,13 +413,22 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
     // bandwidth model does not see: measured on the smallest m = 128 shapes it is 5-35 % optimistic
     if (p.family == FFUSE_FAMILY_REDUCE) t->t_pred *= 1.25;
     if (p.family == FFUSE_FAMILY_ROWS && t->feasible) {
-        // The kernel is a weight stream through LDS at 64 flop per weight byte: per chunk a CU pulls 256 KB
-        // through its load path, as long as the chunk's matrix instructions take.  Measured fraction of the matrix peak on 32768 x 1024 x
-        // 8192 x 1024: kRowsEff; one launch, no second kernel.  A launch of this kernel costs about 12 us before
-        // its first product (120 KB of LDS, a long unrolled loop to fetch, the ring to prime, X to load) --
-        // measured on 128-row problems, where it loses to every other family.
-        t->t_mfma = padded * waves / (d.mfma_flops * kRowsEff);
-        t->t_pred = std::max({t->t_mfma, t->t_l2, t->t_fabric, t->t_hbm}) + d.launch_s + 12e-6;
+        // The kernel is a weight stream through LDS at 64 flop per weight byte: per chunk a CU pulls the chunk's
+        // weights through its load path, as long as the chunk's matrix instructions take.  Fitted on the device
+        // (row-block rounds x (chunks x chunk time + a fixed part per row block)): the fraction of the matrix peak
+        // a chunk sustains grows with its size -- 0.36 for K = N2 = 512 (8.4 Mflop per chunk: 32768 x 512 x 4096 x 512
+        // in 368 us), kRowsEff for K = N2 = 1024 (16.8 Mflop: 32768 x 1024 x 8192 x 1024 in 1056 us, x 1024 x 1024 in
+        // 170) -- and every row block pays about 20 us on top (X into registers, the ring primed again after the
+        // output stores, the output block stored; the first one also the kernel's start: 120 KB of LDS, a long
+        // unrolled loop to fetch), which is why the family loses to every other on problems of a few row blocks.
+        RowsGeometry rg;
+        rows_geometry(p, gated, M, K, N1, N2, &rg);
+        const double chunk_flops = 2.0 * 64.0 * 64.0 * (64.0 * rg.nks + 128.0 * rg.nt2);
+        const double small = 2.0 * 64.0 * 64.0 * 1024.0, big = 2.0 * small;
+        const double eff = std::min(kRowsEff, std::max(0.30, 0.36 + (kRowsEff - 0.36) * (chunk_flops - small) / (big - small)));
+        const double t_chunk = chunk_flops / (d.mfma_flops / d.cus * eff);
+        t->t_mfma = cdiv(cdiv(m, 64.0), d.cus) * (cdiv(n1, 64.0) * t_chunk + 20e-6);
+        t->t_pred = std::max({t->t_mfma, t->t_l2, t->t_fabric, t->t_hbm}) + d.launch_s;
     }
     if (p.family == FFUSE_FAMILY_TWOPHASE && t->feasible) {
         // two phases back to back, each the longer of its streaming time and its matrix time.
@@ -470,7 +479,8 @@ void traffic_model(const ffuse_plan_t& p, int dtype, int gated, int64_t M, int64
         // the efficiencies above were measured on items whose inner loop runs over 4096: they contain those items'
         // ring fill and epilogue (about 10 us of a 256-row item, a tenth of it).  An item with a shorter loop
         // pays the same fixed part on less work: the part the calibration does not already contain is added.
-        const double item_fixed = sg.bm == 256 ? 10e-6 : 0.0;
+        // (128-row items: 3.5 us, fitted on 32768 x 512 x 4096 x 512 and 65536 x 256 x 2048 x 256, where the model was 25-40 % optimistic)
+        const double item_fixed = sg.bm == 256 ? 10e-6 : (sg.bm == 128 ? 3.5e-6 : 0.0);
         const auto short_loop = [&](double loop) { return item_fixed * std::max(0.0, 1.0 - loop / 4096.0); };
         const double m1 = (2.0 * sg.bm * bh1 * g * k / f1 + short_loop(k)) * rounds(items1);
         const double m2 = (2.0 * sg.bm * 256.0 * sg.ksplit / f2 + short_loop(sg.ksplit)) * rounds(items);
@@ -600,7 +610,19 @@ void choose_plan(int dtype, int act, int gated, int64_t M, int64_t K, int64_t N1
         return;
     }
     *out = r.front().plan;
-    if (objective != FFUSE_OBJECTIVE_BYTES) return;
+    if (objective != FFUSE_OBJECTIVE_BYTES) {
+        // time objective: a near-tie goes to the schedule that keeps the traffic on the chip -- a plan predicted
+        // within 6 % of the fastest whose bytes between the L2s and the fabric are at most half of its
+        ffuse_traffic_t tb;
+        traffic_model(*out, dtype, gated, M, K, N1, N2, &tb);
+        for (const RankedPlan& c : r) {
+            if (c.t_pred > 1.06 * r.front().t_pred) break;
+            ffuse_traffic_t t;
+            traffic_model(c.plan, dtype, gated, M, K, N1, N2, &t);
+            if (t.feasible && t.fabric_bytes <= 0.5 * tb.fabric_bytes) { *out = c.plan; tb = t; }
+        }
+        return;
+    }
     // fewest bytes between the L2s and the rest of the memory system among the plans predicted within
     // kBytesObjectiveSlack of the fastest (the ranking is sorted: stop at the first plan beyond the slack)
     double best_bytes = 0.0;

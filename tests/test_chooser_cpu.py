@@ -114,15 +114,25 @@ def test_rows_family_geometry():
 def test_bytes_objective_prefers_the_rows_family_where_it_is_close_enough():
     ff.ffuse_plan_table_clear()
     try:
+        shape = (32768, 1024, 8192, 1024)
         ff.ffuse_set_objective(ff.OBJECTIVE_BYTES)
-        p, _ = ff.ffuse_plan_lookup(ff.DT_F16, 1, False, 32768, 1024, 8192, 1024)
+        p, _ = ff.ffuse_plan_lookup(ff.DT_F16, 1, False, *shape)
         assert p.family == ff.FAMILY_ROWS
-        tb = ff.ffuse_traffic_model(p, ff.DT_F16, False, 32768, 1024, 8192, 1024)
+        tb = ff.ffuse_traffic_model(p, ff.DT_F16, False, *shape)
         ff.ffuse_set_objective(ff.OBJECTIVE_TIME)
-        q, _ = ff.ffuse_plan_lookup(ff.DT_F16, 1, False, 32768, 1024, 8192, 1024)
-        tq = ff.ffuse_traffic_model(q, ff.DT_F16, False, 32768, 1024, 8192, 1024)
-        assert q.family == ff.FAMILY_TWOPHASE and tq.t_pred <= tb.t_pred <= 1.35 * tq.t_pred
-        assert tb.fabric_bytes < 0.5 * tq.fabric_bytes
+        # the fastest plan by the model is a 256-row two-phase plan; the rows family is predicted within a few per
+        # cent of it with less than half its fabric bytes, and such a near-tie goes to it under the time objective too
+        fastest, t_fastest = ff.ffuse_rank_plans(ff.DT_F16, 1, False, *shape)[0]
+        tq = ff.ffuse_traffic_model(fastest, ff.DT_F16, False, *shape)
+        assert fastest.family == ff.FAMILY_TWOPHASE and fastest.bm == 256
+        assert tq.t_pred <= tb.t_pred <= 1.06 * tq.t_pred and tb.fabric_bytes < 0.5 * tq.fabric_bytes
+        q, _ = ff.ffuse_plan_lookup(ff.DT_F16, 1, False, *shape)
+        assert q.family == ff.FAMILY_ROWS
+        # where the family is clearly slower (short K and few output columns: smaller chunks, the same fixed part per
+        # row block) the time objective keeps the fastest plan
+        for other in ((32768, 512, 4096, 512), (65536, 256, 2048, 256), (128, 1024, 4096, 1024)):
+            r, _ = ff.ffuse_plan_lookup(ff.DT_F16, 1, False, *other)
+            assert r.family != ff.FAMILY_ROWS
         # a shape the family cannot run keeps the time plan under either objective
         ff.ffuse_set_objective(ff.OBJECTIVE_BYTES)
         g, _ = ff.ffuse_plan_lookup(ff.DT_BF16, 2, False, 4096, 4096, 16384, 4096)
