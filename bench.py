@@ -139,8 +139,7 @@ def measure(name, args, ff, inputs, np, torch, cal, *, steps, warmup, tune, head
         ff.ffuse_set_objective(ff.OBJECTIVE_BYTES)
         pb = ff.ffuse_choose_plan(dt, w.act, w.gated, w.M, w.K, w.N1, w.N2)
         ff.ffuse_set_objective(ff.OBJECTIVE_TIME)
-        others = [(o, p) for o, p in (("time", pt), ("bytes", pb)) if p.family != plan.family] or \
-                 [(o, p) for o, p in (("bytes", pb),) if p.as_dict() != plan.as_dict()]
+        others = [(o, p) for o, p in (("time", pt), ("bytes", pb)) if p.family != plan.family]   # (another schedule, not another tile size)
         if others:
             objective, po = others[0]
             ff.ffuse_force_plan(po)
