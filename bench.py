@@ -43,13 +43,15 @@ def calibrate(ff, torch):
     the power limit allows a kernel that does nothing else) and a streaming read of 1 GiB."""
     scratch = torch.zeros(16384, dtype=torch.uint8, device="cuda")
     buf = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
-    def mfma(dtype, iters):   # best of three: the rate wanders by +-8 % with the chip's temperature and power state
-        return max(ff.ffuse_calibrate(ff.CAL_MFMA, dtype, None, iters, scratch) for _ in range(3)) * 1e-12
-    cal = {"mfma_bf16_burst_tflops": mfma(ff.DT_BF16, 256), "mfma_bf16_tflops": mfma(ff.DT_BF16, 16384),
+    def mfma(dtype, iters, what=ff.CAL_MFMA):   # best of three: the rate wanders by +-8 % with the chip's temperature and power state
+        return max(ff.ffuse_calibrate(what, dtype, None, iters, scratch) for _ in range(3)) * 1e-12
+    cal = {"mfma_bf16_zero_operands_tflops": mfma(ff.DT_BF16, 16384, ff.CAL_MFMA_IDLE),
+           "mfma_bf16_burst_tflops": mfma(ff.DT_BF16, 256), "mfma_bf16_tflops": mfma(ff.DT_BF16, 16384),
            "mfma_f16_tflops": mfma(ff.DT_F16, 16384),
            "read_gbs": ff.ffuse_calibrate(ff.CAL_READ, ff.DT_BF16, buf, 4, scratch) * 1e-9,
            "kind": "ffuse_calibrate, best of 3: 32x32x16 issue loop on every SIMD over pseudo-random operands, 16384 rounds of 4 "
-                   "products (about 2 ms: the power-limited rate) and a burst of 256 rounds (about 30 us); streaming read of 1 GiB, 4 passes"}
+                   "products (about 2 ms: the power-limited rate), a burst of 256 rounds (about 30 us), and the 2 ms loop over all-zero operands "
+                   "(nothing toggles: the issue rate); streaming read of 1 GiB, 4 passes"}
     del buf
     return cal
 

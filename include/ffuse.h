@@ -333,12 +333,14 @@ const char* ffuse_status_string(int status);
  *      the two ends on the device at hand).  FFUSE_CAL_MFMA: every SIMD of the device issues `iters`
  *      rounds of four independent 32x32x16 products of `dtype` (bf16 or fp16) on pseudo-random operands and
  *      nothing else -- the matrix rate no kernel can exceed at the clock the power limit allows; *result is
- *      flop/s (buf and bytes are ignored).  FFUSE_CAL_READ: `buf` (device, 16-byte aligned, `bytes` a
+ *      flop/s (buf and bytes are ignored).  FFUSE_CAL_MFMA_IDLE: the same loop on all-zero operands, which
+ *      toggle nothing and draw the least power -- the rate the issue logic alone allows; the distance between the
+ *      two is the power limit's doing.  FFUSE_CAL_READ: `buf` (device, 16-byte aligned, `bytes` a
  *      multiple of 16) is streamed through the device once as a warm-up and `iters` more times, timed;
  *      *result is bytes/s.  `scratch16k` is 16 KiB of device memory the probes may write (they do not in
  *      practice); `result` is a host pointer.  The call times its own launches with events on `stream` and
  *      waits for them.  Status as elsewhere (FFUSE_ERR_ACT: unknown probe or dtype). --------------------- */
-enum { FFUSE_CAL_MFMA = 0, FFUSE_CAL_READ = 1 };
+enum { FFUSE_CAL_MFMA = 0, FFUSE_CAL_READ = 1, FFUSE_CAL_MFMA_IDLE = 2 };
 int ffuse_calibrate(int what, int dtype, const void* buf, int64_t bytes, int64_t iters, void* scratch16k,
                     double* result, void* stream);
 

@@ -236,7 +236,7 @@ def ffuse_ffn_static(dtype, X, W1, W3, W2, act, Y, stream=None, check=True):
     return rc
 
 
-CAL_MFMA, CAL_READ = 0, 1
+CAL_MFMA, CAL_READ, CAL_MFMA_IDLE = 0, 1, 2
 
 
 def ffuse_calibrate(what, dtype=DT_BF16, buf=None, iters=1, scratch=None, stream=None):

@@ -16,7 +16,7 @@ namespace ffuse {
 // the upper bound of any kernel's matrix rate.  Operands are pseudo-random values of magnitude
 // 0.5..1 so that the data paths toggle as they do on real data (a loop over zeros draws less power
 // and clocks higher than anything useful).
-template <typename T> __global__ __launch_bounds__(256) void mfma_issue_kernel(float* out, int iters) {
+template <typename T> __global__ __launch_bounds__(256) void mfma_issue_kernel(float* out, int iters, int zeros) {
     typedef typename Mma<T>::vec8 vec8;
     union { vec8 v; uint16_t h[8]; } a, b;
     uint32_t s = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
@@ -27,6 +27,7 @@ template <typename T> __global__ __launch_bounds__(256) void mfma_issue_kernel(f
         const uint16_t mant = __is_same(T, __bf16) ? 0x007F : 0x03FF;
         a.h[i] = (uint16_t)(top | ((s >> 8) & mant) | ((s >> 16) & 0x8000));
         b.h[i] = (uint16_t)(top | ((s >> 3) & mant) | ((s >> 11) & 0x8000));
+        if (zeros) a.h[i] = b.h[i] = 0;     // nothing toggles: what the issue logic alone allows
     }
     f32x16 c0 = {}, c1 = {}, c2 = {}, c3 = {};
     for (int i = 0; i < iters; ++i) {
@@ -76,15 +77,15 @@ extern "C" int ffuse_calibrate(int what, int dtype, const void* buf, int64_t byt
     int rc = FFUSE_OK;
     double work = 0.0;   // flop or bytes of the timed launch
     (void)hipGetLastError();
-    if (what == FFUSE_CAL_MFMA) {
+    if (what == FFUSE_CAL_MFMA || what == FFUSE_CAL_MFMA_IDLE) {
         if (dtype != FFUSE_DT_BF16 && dtype != FFUSE_DT_F16) rc = FFUSE_ERR_ACT;
         const int grid = cus * 2;   // two workgroups of four waves per CU: two waves per SIMD
         for (int rep = 0; rep < 2 && rc == FFUSE_OK; ++rep) {   // the first launch warms up, the second is timed
             if (rep) (void)hipEventRecord(e0, st);
             if (dtype == FFUSE_DT_BF16)
-                ffuse::mfma_issue_kernel<__bf16><<<grid, 256, 0, st>>>(static_cast<float*>(scratch16k), (int)iters);
+                ffuse::mfma_issue_kernel<__bf16><<<grid, 256, 0, st>>>(static_cast<float*>(scratch16k), (int)iters, what == FFUSE_CAL_MFMA_IDLE);
             else
-                ffuse::mfma_issue_kernel<_Float16><<<grid, 256, 0, st>>>(static_cast<float*>(scratch16k), (int)iters);
+                ffuse::mfma_issue_kernel<_Float16><<<grid, 256, 0, st>>>(static_cast<float*>(scratch16k), (int)iters, what == FFUSE_CAL_MFMA_IDLE);
             if (rep) (void)hipEventRecord(e1, st);
         }
         work = (double)grid * 4 /*waves*/ * (double)iters * 4 /*products*/ * (2.0 * 32 * 32 * 16);

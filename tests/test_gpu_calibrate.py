@@ -16,6 +16,11 @@ def test_probe_rates_are_plausible():
     for dt in (ff.DT_BF16, ff.DT_F16):
         rate = ff.ffuse_calibrate(ff.CAL_MFMA, dt, None, 4096, scratch)
         assert 0.35 * 2.5166e15 < rate <= 1.02 * 2.5166e15, rate
+    # on all-zero operands the loop runs at what the issue logic allows: close to the published peak, and never
+    # slower than on data that toggles the multipliers
+    idle = max(ff.ffuse_calibrate(ff.CAL_MFMA_IDLE, ff.DT_BF16, None, 16384, scratch) for _ in range(3))
+    busy = max(ff.ffuse_calibrate(ff.CAL_MFMA, ff.DT_BF16, None, 16384, scratch) for _ in range(3))
+    assert 0.7 * 2.5166e15 < idle <= 1.02 * 2.5166e15 and idle >= 0.95 * busy, (idle, busy)
     buf = torch.ones(1 << 26, dtype=torch.float32, device="cuda")
     rate = ff.ffuse_calibrate(ff.CAL_READ, ff.DT_BF16, buf, 4, scratch)
     assert 2.0e12 < rate < 8.0e12, rate
