@@ -359,6 +359,17 @@ def ffuse_plan_table_load(path) -> int:
     return n
 
 
+SHIPPED_PLANS = os.path.join(HERE, "plans_mi355x.txt")
+
+
+def ffuse_load_shipped_plans() -> int:
+    """Loads the plan table measured on an MI355X for the benchmark configurations and the paper's m = 128
+    shapes (written by ``python -m paper_2512_12949_amd.tune_plans``); returns the number of entries, 0 if
+    the file is not there.  Fused calls on those shapes (same dtype, gate, K, N1, N2, same bin of M) then
+    use the measured plan instead of the model's choice."""
+    return ffuse_plan_table_load(SHIPPED_PLANS) if os.path.exists(SHIPPED_PLANS) else 0
+
+
 def ffuse_plan_table_clear():
     _check(lib().ffuse_plan_table_clear(), "ffuse_plan_table_clear")
 

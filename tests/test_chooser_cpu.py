@@ -230,3 +230,31 @@ def test_split_gate_plans_are_valid_only_where_the_kernel_can_run_them():
         splits = [i for i, (p, _) in enumerate(ranked) if p.gate_split]
         assert len(splits) == 1 and splits[0] > 0 and ranked[0][0].gate_split == 0
         assert all(p.gate_split == 0 for p, _ in ff.ffuse_rank_plans(ff.DT_BF16, 2, False, *shp))
+
+
+def test_the_shipped_plan_table_loads_and_every_entry_is_runnable():
+    """The plan table measured offline on an MI355X (paper_2512_12949_amd/plans_mi355x.txt, written by
+    paper_2512_12949_amd.tune_plans): it parses, it covers the benchmark configurations and the paper's
+    m = 128 tables, every plan is valid for its shape, and a lookup returns it for any M of its bin."""
+    from paper_2512_12949_amd import inputs
+    ff.ffuse_plan_table_clear()
+    try:
+        n = ff.ffuse_load_shipped_plans()
+        names = ["gpt", "llama", "large", "decode16", "decode64"] + [f"G{i}" for i in range(1, 11)] + [f"S{i}" for i in range(1, 9)]
+        assert n == len(names)
+        for name in names:
+            w = inputs.WORKLOADS[name]
+            dt = ff.DTYPE_CODE[w.dtype]
+            plan, ms = ff.ffuse_plan_lookup(dt, w.act, w.gated, w.M, w.K, w.N1, w.N2)
+            assert ms > 0.0, name                                    # a measured entry, not the model's choice
+            t = ff.ffuse_traffic_model(plan, dt, w.gated, w.M, w.K, w.N1, w.N2)     # raises on a plan that is not valid here
+            assert t.feasible and 0.3 * t.t_pred < ms * 1e-3 < 3.0 * t.t_pred, (name, ms, t.t_pred)
+        # the bin of M, not the exact M: 100 rows share the 65..128 bin with the table's 128
+        w = inputs.WORKLOADS["G8"]
+        a, ms_a = ff.ffuse_plan_lookup(ff.DT_BF16, w.act, False, 100, w.K, w.N1, w.N2)
+        b, ms_b = ff.ffuse_plan_lookup(ff.DT_BF16, w.act, False, 128, w.K, w.N1, w.N2)
+        assert ms_a == ms_b > 0 and a.as_dict() == b.as_dict()
+        _, ms_c = ff.ffuse_plan_lookup(ff.DT_BF16, w.act, False, 300, w.K, w.N1, w.N2)
+        assert ms_c == 0.0
+    finally:
+        ff.ffuse_plan_table_clear()

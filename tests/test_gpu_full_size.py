@@ -81,3 +81,27 @@ def test_paper_shape_tables(name):
     Y100 = gu.run(w, dev100)
     keep = rows[rows < 100]
     gu.check(Y100, ref[: len(keep)], w.dtype, rows=keep, what=f"{name} fused, 100 rows")
+
+
+def test_shipped_plan_table_plans_run_and_match():
+    """With the shipped plan table loaded, a call on a listed shape runs the table's plan (no tuning launches), and
+    that plan's output meets the parity bar on the oracle's row sample -- the paper's m = 128 tables and the
+    decode configurations (the three large configurations' tuned plans are covered by test_full_size)."""
+    ff.ffuse_plan_table_clear()
+    try:
+        assert ff.ffuse_load_shipped_plans() >= 23
+        for name in ["decode16", "decode64"] + TABLE_NAMES:
+            w = inputs.WORKLOADS[name]
+            host = inputs.make(w)
+            dev = {k: gu.to_device(v, w.dtype) for k, v in host.items()}
+            rows = inputs.sample_rows(w.M, 32, 2, seed=w.cfg_id)
+            ref = gu.oracle_rows(w, host, rows)
+            want, ms = ff.ffuse_plan_lookup(ff.DTYPE_CODE[w.dtype], w.act, w.gated, w.M, w.K, w.N1, w.N2)
+            assert ms > 0.0, name
+            Y = gu.run(w, dev)
+            assert ff.ffuse_last_plan().as_dict() == want.as_dict(), name
+            rel = gu.check(Y, ref, w.dtype, rows=rows, what=f"{name} shipped plan")
+            assert bool(torch.isfinite(Y.float()).all())
+            print(f"[{name}] shipped plan {want.as_dict()} ({ms * 1e3:.1f} us when tuned) rel err {rel:.3e}", flush=True)
+    finally:
+        ff.ffuse_plan_table_clear()
