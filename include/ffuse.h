@@ -254,6 +254,9 @@ int ffuse_force_plan(const ffuse_plan_t* plan);
  *   FFUSE_GROUP_BARRIER=0  the two-phase kernel's barrier always waits for every workgroup (default: a group
  *                  of workgroups waits for the groups whose tiles of the intermediate its second-phase
  *                  items read -- for itself alone where ffuse_plan_group_local says 1).
+ *   FFUSE_EARLY_FILL=0  256-row tiles of the two-phase kernel start the loads of a workgroup's next first-phase
+ *                  item after the epilogue of the present one (default: before it, so that they travel under
+ *                  it).  Same bits either way; for A/B timing.
  *   FFUSE_LOG=1    (read once) per-launch diagnostics on stderr from ffuse_sync_status.
  *   FFUSE_COOPERATIVE_LAUNCH=1  launch the persistent kernels with the runtime's cooperative launch. */
 /* Plan used by the most recent fused call of this process. */

@@ -254,6 +254,13 @@ bool group_barrier() {
     return !env || std::atoi(env) != 0;
 }
 
+// FFUSE_EARLY_FILL=0: 256-row tiles start a workgroup's next first-phase ring fill after the epilogue instead of
+// under it (for A/B timing; same bits); read per call
+int early_fill() {
+    const char* env = std::getenv("FFUSE_EARLY_FILL");
+    return (!env || std::atoi(env) != 0) ? 1 : 0;
+}
+
 // launches one validated plan in workspace `w`; the caller holds the lock.  two_launches (two-phase
 // family only): each phase is a launch of its own and the kernel boundary replaces the barrier.
 int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1, const void* W3, const void* W2, int act,
@@ -335,7 +342,7 @@ int run_plan(const ffuse_plan_t& plan, int dtype, const void* X, const void* W1,
                               M, (int)K, (int)N1, (int)N2, act, sg.splits, sg.ksplit, sg.raster, nullptr,
                               conv.ic, conv.h, conv.w, stream_weights(dtype, gated, K, N1, N2),
                               group_barrier() ? wait_masks(sg, M, N1, N2) : ~(uint64_t)0, 3,
-                              g.spin_limit, g.extra_arrivals, sg.gate_split ? base + sg.ysum_bytes + sg.h_bytes : nullptr};
+                              g.spin_limit, g.extra_arrivals, early_fill(), sg.gate_split ? base + sg.ysum_bytes + sg.h_bytes : nullptr};
         if (g.log && w.bytes >= sg.ws_bytes + 65536) {
             s.stats = reinterpret_cast<uint64_t*>(base + sg.ws_bytes);
             g.small_stats = s.stats;

@@ -531,6 +531,79 @@ struct FirstGemm {
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+    // store_tile_lds in slabs of 32 rows per wave: the same values and the same coalesced stores, but only
+    // 4 * 32 * EPI_RB bytes of staging (32 KB at most) at `staging`, reused slab after slab -- a wave's LDS
+    // operations complete in order and the region is its own, so a slab's reads are done before the next
+    // slab's writes land.  For callers that have loads in flight to the rest of LDS meanwhile (the next
+    // item's ring fill, DeepGemm::prefill).  `wave`: the wave's number in the workgroup, uniform (a scalar).
+    template <int ACT, bool THROUGH = false>
+    static __device__ __forceinline__ void store_tile_slabs(char* staging, const f32x16 (&acc)[HT][MT],
+                                                            const f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
+                                                            char* C, int64_t ldc, int64_t row0, int col0,
+                                                            int64_t row_lim, int col_lim, int wave) {
+        // the lane number from the hardware, not from the thread index: that one lives in scratch memory by now, and
+        // a reload here would wait for every load the caller has in flight
+        const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        const int wm = wave % WM, wn = wave / WM;
+        const uint32_t x = lane & 31, h = lane >> 5;
+        char* mine = staging + wave * (32 * EPI_RB);
+        const uint32_t wkey = epi_key(x);               // epi_key(32 mt + x) = epi_key(x)
+        const uint32_t rin = lane / EPI_LPR, ch = lane % EPI_LPR;
+        const int col = col0 + wn * WHR + 8 * (int)ch;
+        constexpr int NOUT = 32 / EPI_RPI;              // store instructions per slab: 8, 4 or 2
+        __amdgpu_buffer_rsrc_t rc;
+        if constexpr (THROUGH) rc = make_rsrc(C, (uint32_t)(row_lim * ldc * 2));
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = activate<ACT>(acc[ht][mt][4 * q + e]);
+                        if (GATED) v[e] *= acc3[ht][mt][4 * q + e];
+                    }
+                    uint2 o;
+                    o.x = pack2<T>(v[0], v[1]);
+                    o.y = pack2<T>(v[2], v[3]);
+                    const uint32_t slot = (uint32_t)(8 * ht + 2 * q) + h;
+                    *reinterpret_cast<uint2*>(mine + x * EPI_RB + ((slot ^ wkey) << 3)) = o;
+                }
+            u32x4 v[NOUT];
+#pragma unroll
+            for (int i = 0; i < NOUT; ++i) {
+                const uint32_t row = (uint32_t)(i * EPI_RPI) + rin;
+                const uint32_t key = epi_key(row);
+                v[i] = *reinterpret_cast<const u32x4*>(mine + row * EPI_RB + ((ch ^ (key >> 1)) << 4));
+                if (key & 1u) { u32x4 w = {v[i][2], v[i][3], v[i][0], v[i][1]}; v[i] = w; }
+            }
+#pragma unroll
+            for (int i = 0; i < NOUT; ++i) {
+                const int64_t grow = row0 + wm * WMR + 32 * mt + i * EPI_RPI + rin;
+                if constexpr (THROUGH) {
+                    const uint32_t off = (grow < row_lim && col < col_lim) ? (uint32_t)((grow * ldc + col) * 2) : kOob;
+                    buf_store16_through(v[i], rc, off);
+                } else {
+                    if (grow < row_lim && col < col_lim) *reinterpret_cast<u32x4*>(C + (grow * ldc + col) * 2) = v[i];
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    template <bool THROUGH = false>
+    static __device__ __forceinline__ void store_tile_slabs_rt(char* staging, int act, const f32x16 (&acc)[HT][MT],
+                                                               const f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],
+                                                               char* C, int64_t ldc, int64_t row0, int col0,
+                                                               int64_t row_lim, int col_lim, int wave) {
+        switch (act) {
+            case ACT_RELU: store_tile_slabs<ACT_RELU, THROUGH>(staging, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, wave); break;
+            case ACT_GELU_TANH: store_tile_slabs<ACT_GELU_TANH, THROUGH>(staging, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, wave); break;
+            case ACT_SILU: store_tile_slabs<ACT_SILU, THROUGH>(staging, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, wave); break;
+            default: store_tile_slabs<ACT_IDENTITY, THROUGH>(staging, acc, acc3, C, ldc, row0, col0, row_lim, col_lim, wave); break;
+        }
+    }
     template <bool THROUGH = false>
     static __device__ __forceinline__ void store_tile_lds_rt(char* smem, int act, const f32x16 (&acc)[HT][MT],
                                                              const f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1],

@@ -226,15 +226,34 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
         }
     }
 
+    // The loads that fill the ring for a stream of steps over [kbegin, kend): stages 0..NS-2 <- steps 0..NS-2.
+    // Nothing is waited for.  May be called while slot NS - 1 of the ring is still in use as the staging
+    // area of the previous tile's epilogue (store_tile_lds with SLAB): the fill of a workgroup's next item
+    // then travels under that epilogue, and run(..., prefilled = true) picks it up.
+    static __device__ __forceinline__ void prefill(char* smem, const Ctx& c, int kbegin, int kend) {
+        const int KT = (kend - kbegin + 31) / 32;
+        const int xlim = kend < c.KX ? kend : c.KX;
+#pragma unroll
+        for (int j = 0; j < NS - 1; ++j) issue(smem + j * STAGE, c, kbegin + 32 * j, kbegin + 32 * j, xlim, KT > j);
+    }
+    static constexpr int STAGING_SLOT = (NS - 1) * STAGE;   // where such an epilogue may stage (STAGE bytes)
+    // Waits for the first stage of a filled ring and leaves the fragments of step 0 in f[0].  after_stores:
+    // the fill was issued before a slab epilogue, whose WMR / EPI_RPI global stores per wave are younger
+    // than every load of the fill and count in the same counter, which is decremented in issue order: once
+    // no more than that many operations are outstanding, the whole fill has landed.
+    static __device__ __forceinline__ void await_fill(char* smem, const Ctx& c, bool after_stores, Frags (&f)[2]) {
+        if (after_stores) loads_in_flight_at_most<WMR / Base::EPI_RPI>();
+        else loads_in_flight_at_most<(NS - 2) * NLOAD>();
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NR; ++i) read_one(smem, c, 0, i, f[0]);
+    }
     // Fills the ring for a stream of steps that starts at (kx, kw): stages 0..NS-2 <- steps
     // 0..NS-2, and leaves the fragments of step 0 in f[0].  `nvalid` says how many of them exist.
     static __device__ __forceinline__ void prime(char* smem, const Ctx& c, int kx, int kw, int xlim, int nvalid, Frags (&f)[2]) {
 #pragma unroll
         for (int j = 0; j < NS - 1; ++j) issue(smem + j * STAGE, c, kx + 32 * j, kw + 32 * j, xlim, nvalid > j);
-        loads_in_flight_at_most<(NS - 2) * NLOAD>();
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < NR; ++i) read_one(smem, c, 0, i, f[0]);
+        await_fill(smem, c, false, f);
     }
     // After the last step: the loads still in flight target stages nobody reads any more, but
     // LDS must be quiet, and every wave done with it, before anybody reuses it.
@@ -245,13 +264,14 @@ struct DeepGemm : FirstGemm<T, GATED, BM, BH, WM, WN> {
 
     static __device__ __forceinline__ void run(char* smem, const Ctx& c, int kbegin, int kend, f32x16 (&acc)[HT][MT],
                                                f32x16 (&acc3)[GATED ? HT : 1][GATED ? MT : 1], int tid,
-                                               uint64_t* t_loop = nullptr) {
+                                               bool prefilled = false, uint64_t* t_loop = nullptr) {
         (void)tid;
         Base::zero(acc, acc3);
         const int KT = (kend - kbegin + 31) / 32;
         const int xlim = kend < c.KX ? kend : c.KX;
         Frags f[2];
-        prime(smem, c, kbegin, kbegin, xlim, KT, f);
+        if (!prefilled) prefill(smem, c, kbegin, kend);
+        await_fill(smem, c, prefilled, f);
         if (t_loop) *t_loop = wall_clock64();
         for (int s = 0; s < KT; ++s) {
             const char* cur = smem + (s & (NS - 1)) * STAGE;

@@ -80,6 +80,8 @@ struct TwoPhaseArgs {
                       // 1 / 2: only the first / second phase (two launches = the unfused comparison path)
     uint32_t spin_limit;   // polls after which a workgroup gives up waiting at the barrier (error word, FFUSE_ERR_TIMEOUT)
     int extra_arrivals;    // 0; a test may ask the barrier to wait for arrivals that never come, to see the wait expire
+    int early_fill;        // != 0: 256-row tiles issue the ring fill of a workgroup's next first-phase item before the
+                           // epilogue of the present one (FFUSE_EARLY_FILL=0 switches it off: the fill then follows the epilogue)
     void* U;               // nullptr, or (gated chain with the branches on different workgroups) [M][N1]: X W3 in the
                            // operand type; H then first holds act(X W1) and a Mul pass joins the two in place
 };

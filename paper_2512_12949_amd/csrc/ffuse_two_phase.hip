@@ -126,21 +126,46 @@ __device__ __forceinline__ void two_phase_first(const TwoPhaseArgs& a, char* sme
     // index 2 s is the activated branch of hidden slice s (X W1, into H), 2 s + 1 the multiplying one
     // (X W3, unactivated, into U) -- neighbours in the item order, so they run side by side
     const bool split = G1::G == 1 && !CONV && a.U != nullptr;
-    int rb, s;
-    for (int idx = loc; map_item(MB, split ? 2 * NS : NS, a.raster, xcd, idx, rb, s); idx += GX) {
-        const bool up = split && (s & 1);
-        if (split) s >>= 1;
+    // 256-row tiles (DeepGemm): the ring fill of a workgroup's NEXT item is issued before the epilogue of the
+    // present one and travels under it -- the epilogue stages through the one ring slot the fill leaves alone
+    constexpr bool EARLY = DEEP && BM == 256 && !CONV;
+    const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int NI = split ? 2 * NS : NS;
+    int rb, s, idx = loc;
+    bool have = map_item(MB, NI, a.raster, xcd, idx, rb, s), filled = false;
+    auto aim = [&](int rb_, int s_) {   // points the loader at item (rb_, s_)
+        const bool up_ = split && (s_ & 1);
+        const int sl_ = split ? s_ >> 1 : s_;
         if constexpr (CONV)
-            G1::init_a_conv(c, a.X, (uint32_t)((uint64_t)a.M * a.conv_ic * 2), (uint32_t)rb * BM, a.M, a.conv_h, a.conv_w, a.conv_ic, tid);
+            G1::init_a_conv(c, a.X, (uint32_t)((uint64_t)a.M * a.conv_ic * 2), (uint32_t)rb_ * BM, a.M, a.conv_h, a.conv_w, a.conv_ic, tid);
         else
-            G1::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)rb * BM, (uint32_t)a.K, a.K, tid);
-        G1::init_b(c, up ? a.W3 : a.W1, split ? nullptr : a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1, (uint32_t)s * BH1, tid);
-        if constexpr (DEEP) G1::run(smem, c, 0, a.K, acc, acc3, tid);
+            G1::init_a(c, a.X, (uint32_t)((uint64_t)a.M * a.K * 2), 0u, (uint32_t)rb_ * BM, (uint32_t)a.K, a.K, tid);
+        G1::init_b(c, up_ ? a.W3 : a.W1, split ? nullptr : a.W3, (uint32_t)((uint64_t)a.K * a.N1 * 2), (uint32_t)a.N1, (uint32_t)a.N1, (uint32_t)sl_ * BH1, tid);
+    };
+    while (have) {
+        const bool up = split && (s & 1);
+        const int sl = split ? s >> 1 : s;
+        if (!filled) aim(rb, s);
+        if constexpr (EARLY) G1::run(smem, c, 0, a.K, acc, acc3, tid, filled);
+        else if constexpr (DEEP) G1::run(smem, c, 0, a.K, acc, acc3, tid);
         else G1::run_deep(smem, c, 0, a.K, acc, acc3, tid);
-        G1::template store_tile_lds_rt<true>(smem, up ? (int)ACT_IDENTITY : a.act, acc, acc3, reinterpret_cast<char*>(up ? a.U : a.H), a.N1,
-                                             (int64_t)rb * BM, s * BH1, a.M, a.N1, tid);
-        __syncthreads();   // LDS is free again before the next item's loads
+        int rbn, sn;
+        idx += GX;
+        have = map_item(MB, NI, a.raster, xcd, idx, rbn, sn);
+        char* C = reinterpret_cast<char*>(up ? a.U : a.H);
+        const int act = up ? (int)ACT_IDENTITY : a.act;
+        if constexpr (EARLY) {
+            filled = have && a.early_fill;
+            if (filled) { aim(rbn, sn); G1::prefill(smem, c, 0, a.K); }
+            G1::template store_tile_slabs_rt<true>(smem + G1::STAGING_SLOT, act, acc, acc3, C, a.N1, (int64_t)rb * BM, sl * BH1, a.M, a.N1, wave_u);
+            // (no barrier: the next run() has one between this epilogue and the first load aimed at its slot)
+        } else {
+            G1::template store_tile_lds_rt<true>(smem, act, acc, acc3, C, a.N1, (int64_t)rb * BM, sl * BH1, a.M, a.N1, tid);
+            __syncthreads();   // LDS is free again before the next item's loads
+        }
+        rb = rbn; s = sn;
     }
+    if constexpr (EARLY) __syncthreads();   // every wave is done with the staging slot
 }
 
 // The Mul exchange of the split gated chain: H <- H .* U, tile by tile, in place.  Every workgroup joins
@@ -186,6 +211,7 @@ __device__ __forceinline__ void two_phase_second(const TwoPhaseArgs& a, char* sm
     const int NCB = (a.N2 + BH2 - 1) / BH2;
     const int wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
     constexpr int WM2 = G2::WMR == BM ? 1 : 2;   // waves along the rows of a phase-2 tile
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int wm = wave % WM2, wn = wave / WM2;
     int rb, u;
     // slices of this phase: u = range * NCB + column block, so that neighbours share their part of H
@@ -197,8 +223,12 @@ __device__ __forceinline__ void two_phase_second(const TwoPhaseArgs& a, char* sm
         if constexpr (DEEP) G2::run(smem, c, k0, k1, acc, acc3, tid);
         else G2::run_deep(smem, c, k0, k1, acc, acc3, tid);
         if (a.splits == 1) {
-            G2::template store_tile_lds<ACT_IDENTITY>(smem, acc, acc3, reinterpret_cast<char*>(a.Y), a.N2, (int64_t)rb * BM,
-                                                      cb * BH2, a.M, a.N2, tid);
+            if constexpr (DEEP && BM == 256)   // (the slab epilogue keeps everything in registers: no reloads that wait for stores)
+                G2::template store_tile_slabs<ACT_IDENTITY>(smem, acc, acc3, reinterpret_cast<char*>(a.Y), a.N2, (int64_t)rb * BM,
+                                                            cb * BH2, a.M, a.N2, wave_u);
+            else
+                G2::template store_tile_lds<ACT_IDENTITY>(smem, acc, acc3, reinterpret_cast<char*>(a.Y), a.N2, (int64_t)rb * BM,
+                                                          cb * BH2, a.M, a.N2, tid);
             __syncthreads();
             continue;
         }
