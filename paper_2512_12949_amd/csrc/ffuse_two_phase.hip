@@ -413,16 +413,31 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
     }
 }
 
-// Y = sum over planes (fixed order) of fp32 partial sums, rounded once to the operand type.
+// Y = sum over planes (fixed order: plane 0 first) of fp32 partial sums, rounded once to the operand type.
+// The loads of eight planes are issued together and only then summed: the pass is a handful of memory round
+// trips deep whatever its size (the planes were written by other XCDs and come from behind the L2), and with
+// one round trip per plane it took 4-5 us on every shape, the smallest included.
 template <typename T> __global__ __launch_bounds__(256) void finalize_planes_kernel(const float* __restrict__ part, void* __restrict__ Y,
                                                                                  int64_t n8, int64_t plane_elems, int planes) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n8) return;
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
-    for (int p = 0; p < planes; ++p) {
-        const f32x4* q = reinterpret_cast<const f32x4*>(part + (size_t)p * plane_elems) + 2 * i;
-        s0 += q[0];
-        s1 += q[1];
+    const f32x4 zero = s0;
+    for (int p0 = 0; p0 < planes; p0 += 8) {
+        f32x4 v0[8], v1[8];
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const bool live = p0 + p < planes;
+            const f32x4* q = reinterpret_cast<const f32x4*>(part + (size_t)(live ? p0 + p : 0) * plane_elems) + 2 * i;
+            v0[p] = live ? q[0] : zero;
+            v1[p] = live ? q[1] : zero;
+        }
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+            if (p0 + p < planes) {   // (x + 0 is x, but -0 + 0 is +0: dead planes are skipped, not added)
+                s0 += v0[p];
+                s1 += v1[p];
+            }
     }
     u32x4 o;
     o[0] = pack2<T>(s0[0], s0[1]);
