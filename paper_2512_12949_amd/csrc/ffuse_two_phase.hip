@@ -414,9 +414,9 @@ __global__ __launch_bounds__(256) void fused_two_phase_kernel(TwoPhaseArgs a) {
 }
 
 // Y = sum over planes (fixed order: plane 0 first) of fp32 partial sums, rounded once to the operand type.
-// The loads of eight planes are issued together and only then summed: the pass is a handful of memory round
-// trips deep whatever its size (the planes were written by other XCDs and come from behind the L2), and with
-// one round trip per plane it took 4-5 us on every shape, the smallest included.
+// The loads of eight planes are issued together and only then summed: the pass is latency-bound on small
+// outputs (the planes were written by other XCDs and come from behind the L2), and one round trip per plane
+// instead of one per eight made every call on the small shapes 1.2-1.5 us longer.
 template <typename T> __global__ __launch_bounds__(256) void finalize_planes_kernel(const float* __restrict__ part, void* __restrict__ Y,
                                                                                  int64_t n8, int64_t plane_elems, int planes) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
