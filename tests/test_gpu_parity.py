@@ -172,6 +172,31 @@ def test_two_phase_non_temporal_weight_streaming(dtype, gated, monkeypatch):
     monkeypatch.delenv("FFUSE_NT")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("gated", [False, True])
+def test_two_phase_256_row_tiles_with_several_items_per_workgroup(dtype, gated, monkeypatch):
+    """256-row tiles where some workgroups own two first-phase items (286 items, ragged last row block and
+    last hidden slice): the second item's ring fill is issued before the first item's epilogue and travels
+    under it.  K shorter than the ring is deep, and longer; same bits with the fill behind the epilogue
+    (FFUSE_EARLY_FILL=0)."""
+    act = ACT_SILU if gated else ACT_GELU_TANH
+    N1 = 3208 if gated else 6408
+    for K in (72, 328):
+        w, host, dev = _case("fill", 2600, K, N1, 264, dtype, act, gated)
+        rows = inputs.sample_rows(2600, 256, 6, seed=11)
+        ref = gu.oracle_rows(w, host, rows)
+        plans = [ff.make_plan(ff.FAMILY_TWOPHASE, bm=256, splits=1, raster=4), ff.make_plan(ff.FAMILY_TWOPHASE, bm=256, splits=2, raster=2)]
+        for plan in plans:
+            print(f"early fill {dtype} gated={gated} K={K} splits={plan.splits} raster={plan.raster}", flush=True)
+            monkeypatch.setenv("FFUSE_EARLY_FILL", "1")
+            early = gu.run(w, dev, plan=plan)
+            gu.check(early, ref, dtype, rows=rows, what=f"early fill K={K} splits={plan.splits}")
+            monkeypatch.setenv("FFUSE_EARLY_FILL", "0")
+            late = gu.run(w, dev, plan=plan)
+            assert torch.equal(early, late)
+    monkeypatch.delenv("FFUSE_EARLY_FILL")
+
+
 def test_two_launches_give_the_fused_calls_bits():
     """The unfused comparison path runs the fused kernel one phase per launch in the model's
     best two-phase plan: forced to that plan, the fused call must produce the same bits."""
