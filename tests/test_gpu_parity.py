@@ -181,7 +181,7 @@ def test_two_phase_256_row_tiles_with_several_items_per_workgroup(dtype, gated, 
     (FFUSE_EARLY_FILL=0)."""
     act = ACT_SILU if gated else ACT_GELU_TANH
     N1 = 3208 if gated else 6408
-    for K in (72, 328):
+    for K in (8, 40, 72, 328):          # 1, 2 and 3 K steps (the ring is filled three steps deep), and 11
         w, host, dev = _case("fill", 2600, K, N1, 264, dtype, act, gated)
         rows = inputs.sample_rows(2600, 256, 6, seed=11)
         ref = gu.oracle_rows(w, host, rows)
